@@ -1,0 +1,143 @@
+"""sp24 oracle -- TEST INFRASTRUCTURE ONLY (never part of the product path).
+
+Thin ctypes access to ``sp24_oracle.c``: a plain scalar CPU statement of
+prune / compress / decompress / product for 2:4 structured sparsity, written
+from the paper (Sec. 3.1, Sec. 3.2, Sec. 4.1 Step 2).  Only tests, the smoke
+check and the benchmark's cpu_baseline leg may import this package; it shares
+nothing with the GPU library and does not import it.
+
+Arrays are numpy: 16-bit floats travel as ``uint16`` bit patterns, int8 as
+``int8``.  ``dtype`` is one of "f16", "bf16", "i8".
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sp24_oracle.c")
+_LIB = os.path.join(_HERE, "libsp24_oracle.so")
+_TYPES = {"f16": 0, "bf16": 1, "i8": 2}
+_lib = None
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (OpenMP over rows of the product only)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-std=c11", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_long, ctypes.c_int
+        lib.sp24o_prune.argtypes = [vp, vp, i64, i64, i32]
+        lib.sp24o_compress.argtypes = [vp, vp, vp, i64, i64, i32]
+        lib.sp24o_decompress.argtypes = [vp, vp, vp, i64, i64, i32]
+        lib.sp24o_gemm_f64.argtypes = [vp, vp, vp, i64, i64, i64, i32]
+        lib.sp24o_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64]
+        lib.sp24o_f16_to_double.argtypes = [ctypes.c_uint16]
+        lib.sp24o_f16_to_double.restype = ctypes.c_double
+        lib.sp24o_bf16_to_double.argtypes = [ctypes.c_uint16]
+        lib.sp24o_bf16_to_double.restype = ctypes.c_double
+        _lib = lib
+    return _lib
+
+
+def _np_dtype(dtype):
+    return np.int8 if dtype == "i8" else np.uint16
+
+
+def _check(a, dtype, ndim=2):
+    if a.dtype != _np_dtype(dtype) or a.ndim != ndim or not a.flags.c_contiguous:
+        raise ValueError(f"expected C-contiguous {ndim}-d {_np_dtype(dtype).__name__} array")
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def prune(A, dtype):
+    """Sec. 4.1 Step 2: zero the two smallest-magnitude entries of every group of 4."""
+    _check(A, dtype)
+    M, K = A.shape
+    P = np.empty_like(A)
+    rc = _load().sp24o_prune(_ptr(A), _ptr(P), M, K, _TYPES[dtype])
+    if rc:
+        raise ValueError(f"oracle prune failed ({rc}): K must be a multiple of 4")
+    return P
+
+
+def compress(A, dtype):
+    """Sec. 3.1: (V [M,K/2], meta [M,K/8] uint8) in the canonical packing."""
+    _check(A, dtype)
+    M, K = A.shape
+    if K % 8:
+        raise ValueError("K must be a multiple of 8")
+    V = np.empty((M, K // 2), dtype=A.dtype)
+    meta = np.empty((M, K // 8), dtype=np.uint8)
+    rc = _load().sp24o_compress(_ptr(A), _ptr(V), _ptr(meta), M, K, _TYPES[dtype])
+    if rc:
+        raise ValueError(f"oracle compress failed ({rc})")
+    return V, meta
+
+
+def decompress(V, meta, dtype):
+    """Inverse of compress: scatter the kept values, +0 elsewhere."""
+    _check(V, dtype)
+    M, K2 = V.shape
+    K = 2 * K2
+    if meta.dtype != np.uint8 or meta.shape != (M, K // 8) or not meta.flags.c_contiguous:
+        raise ValueError("meta must be C-contiguous uint8 [M, K/8]")
+    P = np.empty((M, K), dtype=V.dtype)
+    rc = _load().sp24o_decompress(_ptr(V), _ptr(meta), _ptr(P), M, K, _TYPES[dtype])
+    if rc:
+        raise ValueError(f"oracle decompress failed ({rc}): illegal metadata code")
+    return P
+
+
+def gemm(P, B, dtype):
+    """Sec. 3.2 / Fig. 2 by definition: D = P @ B with B [K,N] row-major.
+
+    Returns float64 [M,N] for f16/bf16 (exact conversion, double accumulation)
+    and int32 for i8.
+    """
+    _check(P, dtype)
+    _check(B, dtype)
+    M, K = P.shape
+    K2, N = B.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ")
+    lib = _load()
+    if dtype == "i8":
+        D = np.empty((M, N), dtype=np.int32)
+        lib.sp24o_gemm_i32(_ptr(P), _ptr(B), _ptr(D), M, N, K)
+    else:
+        D = np.empty((M, N), dtype=np.float64)
+        lib.sp24o_gemm_f64(_ptr(P), _ptr(B), _ptr(D), M, N, K, _TYPES[dtype])
+    return D
+
+
+def spmm(V, meta, B, dtype):
+    """The sparse product as the paper defines it: the dense product of the
+    decompressed first operand (Fig. 2)."""
+    return gemm(decompress(V, meta, dtype), B, dtype)
+
+
+def to_double(bits, dtype):
+    """Exact value of 16-bit patterns (or int8) as float64, element by element."""
+    if dtype == "i8":
+        return bits.astype(np.float64)
+    fn = _load().sp24o_f16_to_double if dtype == "f16" else _load().sp24o_bf16_to_double
+    flat = np.ascontiguousarray(bits).reshape(-1)
+    return np.array([fn(int(b)) for b in flat], dtype=np.float64).reshape(bits.shape)
+
+
+def threads():
+    return int(_load().sp24o_threads())

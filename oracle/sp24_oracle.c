@@ -1,0 +1,259 @@
+/*
+ * sp24 oracle -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, scalar CPU statement of what the 2:4 structured-sparse
+ * matrix-multiply path computes, written from the paper ("Accelerating Sparse
+ * Deep Neural Networks", arXiv 2104.08378).  It exists so that tests, the
+ * smoke check and the benchmark's cpu_baseline leg have something independent
+ * to compare the GPU library with.  It shares no code, headers, tables or
+ * helpers with the GPU library and must never be reached from the product path.
+ *
+ * Notation (Sec. 3, Fig. 2): A is the first GEMM operand, M x K, row-major,
+ * K contiguous.  Groups are 4 consecutive elements of a row, aligned to
+ * column 0.  V is the M x K/2 array of kept values, meta the 2-bit positions.
+ *
+ * Element types: 0 = fp16 (IEEE binary16), 1 = bf16, 2 = int8.  The 16-bit
+ * types are passed as raw uint16_t bit patterns.
+ *
+ * Readings where the paper is silent (all listed again in the design notes):
+ *   - ties in magnitude: the lower column index wins (is kept);
+ *   - every NaN has the same, largest, magnitude (above infinity);
+ *   - |-128| for int8 is 128 (no wrap);
+ *   - a removed slot holds +0 (all bits clear);
+ *   - a group with more than two zeros still records two positions, chosen by
+ *     the same rule (Sec. 3.1, last sentence of the metadata paragraph);
+ *   - inside a group positions are recorded in ascending order, groups in
+ *     column order (the [[0,3],[1,2]] example of Sec. 3.1);
+ *   - canonical metadata packing: one 4-bit code  pos0 | pos1<<2  per group,
+ *     two groups per byte, the even group in bits 0..3; bytes laid out
+ *     [M][K/8].  The paper does not give a packing; this one is ours.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { T_F16 = 0, T_BF16 = 1, T_I8 = 2 };
+
+/* ---- exact conversion of the 16-bit storage formats to double ---------- */
+
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+double sp24o_f16_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int f = h & 0x3ff;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24); /* subnormal: f * 2^-10 * 2^-14 */
+    else if (e == 31)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
+/* bfloat16: the upper half of an IEEE binary32 (1 sign, 8 exponent, 7 fraction). */
+double sp24o_bf16_to_double(uint16_t b)
+{
+    int sign = (b >> 15) & 1;
+    int e = (b >> 7) & 0xff;
+    int f = b & 0x7f;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -7 - 126);
+    else if (e == 255)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp(1.0 + (double)f / 128.0, e - 127);
+    return sign ? -v : v;
+}
+
+static double elem_to_double(const void *p, long i, int t)
+{
+    if (t == T_F16)
+        return sp24o_f16_to_double(((const uint16_t *)p)[i]);
+    if (t == T_BF16)
+        return sp24o_bf16_to_double(((const uint16_t *)p)[i]);
+    return (double)((const int8_t *)p)[i];
+}
+
+/* ---- the selection rule (Sec. 4.1, Step 2) ----------------------------- */
+
+/* Magnitude as an ordered pair: NaN above everything, else |x|. */
+typedef struct { int is_nan; double abs; } mag_t;
+
+static mag_t magnitude(double x)
+{
+    mag_t m;
+    m.is_nan = isnan(x) ? 1 : 0;
+    m.abs = m.is_nan ? 0.0 : fabs(x);
+    return m;
+}
+
+static int mag_greater(mag_t a, mag_t b)
+{
+    if (a.is_nan != b.is_nan)
+        return a.is_nan > b.is_nan;
+    return a.abs > b.abs;
+}
+
+static int mag_equal(mag_t a, mag_t b)
+{
+    return a.is_nan == b.is_nan && a.abs == b.abs;
+}
+
+/*
+ * keep[i] = 1 for the two elements of the group that survive: element i is
+ * removed when at least two others come before it in the order
+ * (magnitude descending, column ascending).  "Removes the two smallest
+ * weights in each group of four."
+ */
+static void select_two(const double x[4], int keep[4])
+{
+    mag_t m[4];
+    for (int i = 0; i < 4; ++i)
+        m[i] = magnitude(x[i]);
+    for (int i = 0; i < 4; ++i) {
+        int ahead = 0;
+        for (int j = 0; j < 4; ++j) {
+            if (j == i)
+                continue;
+            if (mag_greater(m[j], m[i]) || (mag_equal(m[j], m[i]) && j < i))
+                ++ahead;
+        }
+        keep[i] = ahead < 2;
+    }
+}
+
+static void group_keep(const void *A, long base, int t, int keep[4])
+{
+    double x[4];
+    for (int i = 0; i < 4; ++i)
+        x[i] = elem_to_double(A, base + i, t);
+    select_two(x, keep);
+}
+
+static long esize(int t) { return t == T_I8 ? 1 : 2; }
+
+/* ---- O1: prune (dense -> dense, Sec. 4.1 Step 2; pattern of Sec. 3) ---- */
+int sp24o_prune(const void *A, void *P, long M, long K, int t)
+{
+    if (K % 4 || t < 0 || t > 2)
+        return 1;
+    long es = esize(t);
+    for (long m = 0; m < M; ++m)
+        for (long g = 0; g < K / 4; ++g) {
+            long base = m * K + 4 * g;
+            int keep[4];
+            group_keep(A, base, t, keep);
+            for (int i = 0; i < 4; ++i) {
+                char *dst = (char *)P + (base + i) * es;
+                const char *src = (const char *)A + (base + i) * es;
+                if (keep[i])
+                    memmove(dst, src, es); /* bit-for-bit */
+                else
+                    memset(dst, 0, es);    /* +0 */
+            }
+        }
+    return 0;
+}
+
+/* ---- O2: compress (Sec. 3.1: value array + 2-bit positions) ------------ */
+int sp24o_compress(const void *A, void *V, uint8_t *meta, long M, long K, int t)
+{
+    if (K % 8 || t < 0 || t > 2)
+        return 1;
+    long es = esize(t);
+    memset(meta, 0, (size_t)(M * K / 8));
+    for (long m = 0; m < M; ++m)
+        for (long g = 0; g < K / 4; ++g) {
+            long base = m * K + 4 * g;
+            int keep[4], pos[2], n = 0;
+            group_keep(A, base, t, keep);
+            for (int i = 0; i < 4; ++i)
+                if (keep[i])
+                    pos[n++] = i; /* ascending */
+            for (int s = 0; s < 2; ++s)
+                memcpy((char *)V + (m * (K / 2) + 2 * g + s) * es,
+                       (const char *)A + (base + pos[s]) * es, es);
+            unsigned code = (unsigned)pos[0] | ((unsigned)pos[1] << 2);
+            meta[m * (K / 8) + g / 2] |= (uint8_t)(code << (4 * (g & 1)));
+        }
+    return 0;
+}
+
+/* ---- O3: decompress (inverse scatter) ---------------------------------- */
+int sp24o_decompress(const void *V, const uint8_t *meta, void *P, long M, long K, int t)
+{
+    if (K % 8 || t < 0 || t > 2)
+        return 1;
+    long es = esize(t);
+    memset(P, 0, (size_t)(M * K * es));
+    for (long m = 0; m < M; ++m)
+        for (long g = 0; g < K / 4; ++g) {
+            unsigned code = (meta[m * (K / 8) + g / 2] >> (4 * (g & 1))) & 0xf;
+            int pos[2] = { (int)(code & 3), (int)(code >> 2) };
+            if (pos[0] >= pos[1])
+                return 2; /* not one of the six legal codes */
+            for (int s = 0; s < 2; ++s)
+                memcpy((char *)P + (m * K + 4 * g + pos[s]) * es,
+                       (const char *)V + (m * (K / 2) + 2 * g + s) * es, es);
+        }
+    return 0;
+}
+
+/*
+ * ---- O4: the product, by definition (Sec. 3.2, Fig. 2) -------------------
+ * D[m][n] = sum_k P[m][k] * B[k][n] over the full, decompressed P (zeros are
+ * multiplied out, not skipped).  B is K x N row-major, D is M x N row-major.
+ * 16-bit inputs are converted exactly to double and accumulated in double;
+ * int8 accumulates in int32.  The k loop runs in ascending order for every
+ * output; rows are independent, which is all the OpenMP pragma uses.
+ */
+int sp24o_gemm_f64(const uint16_t *P, const uint16_t *B, double *D,
+                   long M, long N, long K, int t)
+{
+    if (t != T_F16 && t != T_BF16)
+        return 1;
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < M; ++m) {
+        double *d = D + m * N;
+        for (long n = 0; n < N; ++n)
+            d[n] = 0.0;
+        for (long k = 0; k < K; ++k) {
+            double a = elem_to_double(P, m * K + k, t);
+            for (long n = 0; n < N; ++n)
+                d[n] += a * elem_to_double(B, k * N + n, t);
+        }
+    }
+    return 0;
+}
+
+int sp24o_gemm_i32(const int8_t *P, const int8_t *B, int32_t *D,
+                   long M, long N, long K)
+{
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < M; ++m) {
+        int32_t *d = D + m * N;
+        for (long n = 0; n < N; ++n)
+            d[n] = 0;
+        for (long k = 0; k < K; ++k) {
+            int32_t a = P[m * K + k];
+            for (long n = 0; n < N; ++n)
+                d[n] += a * (int32_t)B[k * N + n];
+        }
+    }
+    return 0;
+}
+
+int sp24o_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,97 @@
+"""Seeded synthetic inputs shared by the tests, the smoke check and bench.py.
+
+Holds no part of the 2:4 method (no pruning, packing or products): only random
+draws, one rounding to the storage type, and the im2col gather that shapes the
+convolution workload.  16-bit floats are returned as ``uint16`` bit patterns,
+int8 as ``int8``.  The five workloads mirror transformer and CNN layer shapes
+(Sec. 3.2: N = batch x sequence; Sec. 4.2: conv inner dimension C*R*S).
+"""
+import numpy as np
+
+WORKLOADS = {
+    # name: dtype, M, K, N, out dtype
+    "tiny_f16": dict(id=1, dtype="f16", M=256, K=256, N=256, out="f32"),
+    "ffn_bf16": dict(id=2, dtype="bf16", M=4096, K=1024, N=8192, out="bf16"),
+    "conv3x3_f16": dict(id=3, dtype="f16", M=256, K=2304, N=12544, out="f16"),
+    "square_i8": dict(id=4, dtype="i8", M=8192, K=8192, N=8192, out="i32"),
+    "skinny_bf16": dict(id=5, dtype="bf16", M=8192, K=8192, N=16, out="bf16"),
+}
+
+
+def f64_to_f16_bits(x):
+    """Round-to-nearest-even to IEEE binary16, returned as uint16 bits."""
+    return np.asarray(x, dtype=np.float64).astype(np.float16).view(np.uint16)
+
+
+def f64_to_bf16_bits(x):
+    """Round-to-nearest-even to bfloat16 via the binary32 bit pattern."""
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    rounded = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    out = rounded.astype(np.uint16)
+    nan = np.isnan(f)
+    if nan.any():
+        out = np.where(nan, np.uint16(0x7FC0), out)
+    return out
+
+
+def to_bits(x, dtype):
+    if dtype == "f16":
+        return f64_to_f16_bits(x)
+    if dtype == "bf16":
+        return f64_to_bf16_bits(x)
+    raise ValueError(dtype)
+
+
+def _rng(seed, config_id, tensor_id):
+    return np.random.default_rng([seed, config_id, tensor_id])
+
+
+def normal_bits(shape, sigma, dtype, seed, config_id, tensor_id):
+    return to_bits(_rng(seed, config_id, tensor_id).standard_normal(shape) * sigma, dtype)
+
+
+def int8_uniform(shape, seed, config_id, tensor_id):
+    return _rng(seed, config_id, tensor_id).integers(-127, 128, size=shape, dtype=np.int8)
+
+
+def im2col_nhwc(x, R=3, S=3, pad=1):
+    """x: [batch, H, W, C] -> [batch*H*W, R*S*C], k = (r*S + s)*C + c, stride 1."""
+    b, H, W, C = x.shape
+    xp = np.zeros((b, H + 2 * pad, W + 2 * pad, C), dtype=x.dtype)
+    xp[:, pad:pad + H, pad:pad + W, :] = x
+    cols = np.empty((b, H, W, R * S, C), dtype=x.dtype)
+    for r in range(R):
+        for s in range(S):
+            cols[:, :, :, r * S + s, :] = xp[:, r:r + H, s:s + W, :]
+    return cols.reshape(b * H * W, R * S * C)
+
+
+def make(name, seed=0, M=None, N=None, K=None):
+    """Return (A [M,K], Bt [N,K]) for a named workload; Bt is the second operand
+    stored K-contiguous (one row per token / output pixel).  M, N, K may be
+    overridden to cut a smaller problem of the same distribution."""
+    w = WORKLOADS[name]
+    cid, dt = w["id"], w["dtype"]
+    M = w["M"] if M is None else M
+    N = w["N"] if N is None else N
+    K = w["K"] if K is None else K
+    if name == "tiny_f16":
+        A = normal_bits((M, K), 1.0, dt, seed, cid, 0)
+        Bt = normal_bits((N, K), 1.0, dt, seed, cid, 1)
+    elif name in ("ffn_bf16", "skinny_bf16"):
+        A = normal_bits((M, K), 0.02, dt, seed, cid, 0)
+        Bt = normal_bits((N, K), 1.0, dt, seed, cid, 1)
+    elif name == "conv3x3_f16":
+        C = K // 9
+        if C * 9 != K or N % 196:
+            raise ValueError("conv workload needs K = 9*C and N = batch*14*14")
+        A = normal_bits((M, K), 0.05, dt, seed, cid, 0)
+        act = np.maximum(_rng(seed, cid, 1).standard_normal((N // 196, 14, 14, C)), 0.0)
+        Bt = im2col_nhwc(f64_to_f16_bits(act))
+    elif name == "square_i8":
+        A = int8_uniform((M, K), seed, cid, 0)
+        Bt = int8_uniform((N, K), seed, cid, 1)
+    else:
+        raise KeyError(name)
+    return np.ascontiguousarray(A), np.ascontiguousarray(Bt)
