@@ -1,0 +1,162 @@
+/*
+ * sp24 -- 2:4 structured-sparse matrix multiply for AMD MI355X (gfx950, CDNA4).
+ *
+ * C ABI of libsp24.so.  The operations are those of "Accelerating Sparse Deep
+ * Neural Networks" (arXiv 2104.08378):
+ *   - the 2:4 pattern: every aligned group of 4 consecutive values along a row
+ *     of the first GEMM operand holds at least 2 zeros (Sec. 1, Sec. 3);
+ *   - magnitude pruning to that pattern (Sec. 4.1, Step 2);
+ *   - the compressed format: a half-width value array plus 2 bits of position
+ *     metadata per kept value (Sec. 3.1);
+ *   - sparse x dense = dense matrix multiply with the compressed matrix as the
+ *     first operand (Sec. 3.2, Fig. 2), and a same-shape dense multiply, the
+ *     denominator of the paper's speedups (Sec. 3.2, Fig. 3).
+ *
+ * Notation: A is M x K (first operand, K contiguous, row stride lda elements);
+ * groups run along K from column 0.  P = pruned A.  V = kept values, M x K/2.
+ * B is the dense second operand K x N, D the M x N result (row-major, row
+ * stride ldd elements).
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates, frees and synchronises nothing and never changes the current
+ *     device.  (sp24_*_bytes and sp24_status_string touch no device at all.)
+ *   - Every call is asynchronous on the caller's HIP stream, passed as void*
+ *     (a hipStream_t; NULL = the default stream).  Results are valid once the
+ *     caller has synchronised that stream.
+ *   - All validation happens on the host before any launch: a call that
+ *     returns anything but SP24_OK has launched nothing and written nothing.
+ *   - Leading dimensions are in elements.  A, P, V and meta must be 16-byte
+ *     aligned and every row of A and P must start 16-byte aligned
+ *     (ld * element_size % 16 == 0); B and D need only the alignment of their
+ *     element type and any leading dimension that covers a row.  Otherwise
+ *     SP24_ERR_ALIGN.  (The fast product kernels are chosen when B and D rows
+ *     are 16-byte aligned too; other cases run a general kernel.)
+ *   - K must be a multiple of 16 for 16-bit types and of 32 for int8
+ *     (the dimension rule of Sec. 3.2 / Sec. 4.2, applied to the inner
+ *     dimension), else SP24_ERR_SHAPE.  M and N may be any positive value; a
+ *     zero M or N is accepted and does nothing.
+ *   - Selection rule where the paper is silent: magnitudes are compared
+ *     exactly; on equal magnitude the lower column is kept; every NaN counts
+ *     as one magnitude above infinity; |-128| = 128; a removed slot holds +0.
+ */
+#ifndef SP24_H
+#define SP24_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SP24_OK = 0,
+    SP24_ERR_NULL = 1,   /* a required pointer is NULL                         */
+    SP24_ERR_SHAPE = 2,  /* negative size, illegal K, ld too small, or buffers overlap */
+    SP24_ERR_ALIGN = 3,  /* pointer or leading dimension not 16-byte aligned    */
+    SP24_ERR_DTYPE = 4,  /* unknown type or unsupported in/out combination      */
+    SP24_ERR_LAYOUT = 5, /* unknown layout, or shape not legal for that layout  */
+    SP24_ERR_LAUNCH = 6  /* the HIP runtime rejected a launch                   */
+} sp24_status;
+
+typedef enum {
+    SP24_F16 = 0,  /* IEEE binary16                                   */
+    SP24_BF16 = 1, /* bfloat16                                        */
+    SP24_I8 = 2,   /* signed 8-bit integer                            */
+    SP24_F32 = 3,  /* output only                                     */
+    SP24_I32 = 4   /* output only (required for SP24_I8 inputs)       */
+} sp24_dtype;
+
+/*
+ * Layout of the compressed pair (V, meta) -- Sec. 3.1 fixes the content (two
+ * kept values per group in column order; 2 bits per kept value giving its
+ * position in the group), not the packing.  A group's code is
+ * pos0 | pos1 << 2 with pos0 < pos1 (six legal codes: 0x4 0x8 0x9 0xC 0xD 0xE).
+ *
+ * SP24_LAYOUT_CANONICAL  V row-major [M][K/2]; meta bytes [M][K/8], the even
+ *     group of a byte in bits 0..3.  Interchange format.
+ *
+ * SP24_LAYOUT_TILED  the same codes and values permuted so that one wavefront
+ *     loads the operands of a 32x32 sparse-MFMA tile with contiguous 16-byte
+ *     and 4-byte accesses.  Needs M % 32 == 0 and K % 64 == 0, else
+ *     SP24_ERR_LAYOUT.  Tiles of 32 rows x 64 columns of A are stored in
+ *     order [M/32][K/64]; with slot = (m % 32) + 32 * h, where h = 0,1 names
+ *     the 32-column half of the tile:
+ *       meta: one uint32 per slot, 64 per tile: the canonical bytes
+ *             8*kb + 4*h .. +3 of row m as a little-endian word;
+ *       V, 8-bit : 16 bytes per slot, 64 slots per tile: canonical V columns
+ *             32*kb + 16*h .. +15 of row m;
+ *       V, 16-bit: two runs of 64 slots x 16 bytes per tile; run s = 0,1
+ *             holds canonical V columns 32*kb + 16*h + 8*s .. +7 of row m.
+ *     Total sizes equal the canonical ones.
+ */
+typedef enum { SP24_LAYOUT_CANONICAL = 0, SP24_LAYOUT_TILED = 1 } sp24_layout;
+
+/* Storage order of the dense second operand B (K x N). */
+typedef enum {
+    SP24_B_KMAJOR = 0, /* element (k,n) at B[n*ldb + k]: one row per token / pixel */
+    SP24_B_NMAJOR = 1  /* element (k,n) at B[k*ldb + n]                            */
+} sp24_border;
+
+/* Sizes in bytes of V and meta for an M x K matrix (Sec. 3.1: K/2 values and
+ * K/8 metadata bytes per row -- 36 bits per group of four 16-bit values).
+ * Return 0 for an illegal type, shape or layout. */
+size_t sp24_values_bytes(int64_t M, int64_t K, sp24_dtype t);
+size_t sp24_meta_bytes(int64_t M, int64_t K, sp24_dtype t, sp24_layout l);
+
+/*
+ * Sec. 4.1 Step 2: P = A with the two smallest-magnitude entries of every
+ * group of four set to +0; kept entries are copied bit for bit.
+ * A, P: device, M x K, row strides lda, ldp (elements).  P may equal A
+ * (in place, then ldp must equal lda); partial overlap is not allowed.
+ */
+sp24_status sp24_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp,
+                       sp24_dtype t, void* stream);
+
+/*
+ * Sec. 3.1: prune (same rule as sp24_prune) and compress in one pass.
+ * A: device, M x K, row stride lda.  V: device, sp24_values_bytes(M,K,t)
+ * bytes.  meta: device, sp24_meta_bytes(M,K,t,l) bytes.  Neither may overlap A.
+ * Compressing an already pruned matrix keeps exactly its non-zeros.
+ */
+sp24_status sp24_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda,
+                          sp24_dtype t, sp24_layout l, void* stream);
+
+/*
+ * Inverse of sp24_compress: P (M x K, row stride ldp) receives the kept values
+ * at their recorded positions and +0 elsewhere.  Metadata codes other than the
+ * six legal ones give unspecified values in that group (never an out-of-range
+ * access).
+ */
+sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp,
+                            sp24_dtype t, sp24_layout l, void* stream);
+
+/*
+ * Sec. 3.2, Fig. 2: D = decompress(V, meta) x B.  Products of 16-bit inputs
+ * are accumulated in fp32 and written as `out` = SP24_F32, SP24_F16 or
+ * SP24_BF16 (one rounding, to nearest even); int8 products are accumulated in
+ * int32 and `out` must be SP24_I32 (exact for K <= 2^17).
+ * B: device, ldb >= K (K-major) or ldb >= N (N-major).  D: device, M x N,
+ * ldd >= N; must not overlap the inputs.
+ */
+sp24_status sp24_spmm(const void* V, const void* meta, const void* B, void* D, int64_t M, int64_t N,
+                      int64_t K, int64_t ldb, int64_t ldd, sp24_dtype in, sp24_dtype out,
+                      sp24_border bo, sp24_layout l, void* stream);
+
+/*
+ * The same-shape dense product D = A x B on the dense matrix cores, with the
+ * same types, accumulation and layouts as sp24_spmm: the denominator of the
+ * sparse-vs-dense speedup (Sec. 3.2, Fig. 3).  A: device, M x K, row stride lda.
+ */
+sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, int64_t N, int64_t K,
+                            int64_t lda, int64_t ldb, int64_t ldd, sp24_dtype in, sp24_dtype out,
+                            sp24_border bo, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* sp24_status_string(sp24_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SP24_H */

@@ -1,0 +1,179 @@
+// C ABI of libsp24: argument validation on the host, then kernel selection.
+// Nothing here allocates, synchronises or touches the current device.
+#include "common.hpp"
+#include "launch.hpp"
+
+using namespace sp24;
+
+namespace {
+
+bool is_input_type(sp24_dtype t) { return t == SP24_F16 || t == SP24_BF16 || t == SP24_I8; }
+bool is_layout(sp24_layout l) { return l == SP24_LAYOUT_CANONICAL || l == SP24_LAYOUT_TILED; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Dimension rule of Sec. 3.2 / Sec. 4.2 on the inner dimension.
+bool k_legal(int64_t K, sp24_dtype t) { return K > 0 && K % (t == SP24_I8 ? 32 : 16) == 0; }
+
+bool layout_fits(int64_t M, int64_t K, sp24_layout l)
+{
+    return l == SP24_LAYOUT_CANONICAL || (M % 32 == 0 && K % 64 == 0);
+}
+
+bool out_legal(sp24_dtype in, sp24_dtype out)
+{
+    if (in == SP24_I8) return out == SP24_I32;
+    return out == SP24_F32 || out == SP24_F16 || out == SP24_BF16;
+}
+
+// a matrix of `rows` rows, `cols` used columns, leading dimension ld (elements of size es);
+// vec16: rows must start on 16-byte boundaries (the streaming kernels use 16-byte accesses),
+// otherwise natural element alignment is enough.
+sp24_status check_matrix(const void* p, int64_t rows, int64_t cols, int64_t ld, int es, bool vec16 = true)
+{
+    if (rows == 0) return SP24_OK;
+    if (!p) return SP24_ERR_NULL;
+    if (ld < cols) return SP24_ERR_SHAPE;
+    if (vec16 ? (!aligned16(p) || (ld * es) % 16 != 0) : (reinterpret_cast<uintptr_t>(p) % es != 0)) return SP24_ERR_ALIGN;
+    return SP24_OK;
+}
+
+bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb)
+{
+    uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + nb && y < x + na;
+}
+
+} // namespace
+
+extern "C" {
+
+size_t sp24_values_bytes(int64_t M, int64_t K, sp24_dtype t)
+{
+    if (!is_input_type(t) || M < 0 || !k_legal(K, t)) return 0;
+    return (size_t)M * (size_t)(K / 2) * (size_t)esize_of(t);
+}
+
+size_t sp24_meta_bytes(int64_t M, int64_t K, sp24_dtype t, sp24_layout l)
+{
+    if (!is_input_type(t) || !is_layout(l) || M < 0 || !k_legal(K, t) || !layout_fits(M, K, l)) return 0;
+    return (size_t)M * (size_t)(K / 8);
+}
+
+sp24_status sp24_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (M < 0 || !k_legal(K, t)) return SP24_ERR_SHAPE;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(A, M, K, lda, es);
+    if (s != SP24_OK) return s;
+    s = check_matrix(P, M, K, ldp, es);
+    if (s != SP24_OK) return s;
+    if (M > 0 && A == P && lda != ldp) return SP24_ERR_SHAPE;
+    if (M > 0 && A != P) {
+        size_t na = ((size_t)(M - 1) * lda + K) * es, np = ((size_t)(M - 1) * ldp + K) * es;
+        if (ranges_overlap(A, na, P, np)) return SP24_ERR_SHAPE;
+    }
+    return launch_prune(A, P, M, K, lda, ldp, t, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_dtype t,
+                          sp24_layout l, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (!is_layout(l)) return SP24_ERR_LAYOUT;
+    if (M < 0 || !k_legal(K, t)) return SP24_ERR_SHAPE;
+    if (!layout_fits(M, K, l)) return SP24_ERR_LAYOUT;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(A, M, K, lda, es);
+    if (s != SP24_OK) return s;
+    if (M == 0) return SP24_OK;
+    if (!V || !meta) return SP24_ERR_NULL;
+    if (!aligned16(V) || !aligned16(meta)) return SP24_ERR_ALIGN;
+    size_t na = ((size_t)(M - 1) * lda + K) * es;
+    if (ranges_overlap(A, na, V, sp24_values_bytes(M, K, t)) || ranges_overlap(A, na, meta, sp24_meta_bytes(M, K, t, l)))
+        return SP24_ERR_SHAPE;
+    return launch_compress(A, V, meta, M, K, lda, t, l, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp, sp24_dtype t,
+                            sp24_layout l, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (!is_layout(l)) return SP24_ERR_LAYOUT;
+    if (M < 0 || !k_legal(K, t)) return SP24_ERR_SHAPE;
+    if (!layout_fits(M, K, l)) return SP24_ERR_LAYOUT;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(P, M, K, ldp, es);
+    if (s != SP24_OK) return s;
+    if (M == 0) return SP24_OK;
+    if (!V || !meta) return SP24_ERR_NULL;
+    if (!aligned16(V) || !aligned16(meta)) return SP24_ERR_ALIGN;
+    size_t np = ((size_t)(M - 1) * ldp + K) * es;
+    if (ranges_overlap(P, np, V, sp24_values_bytes(M, K, t)) || ranges_overlap(P, np, meta, sp24_meta_bytes(M, K, t, l)))
+        return SP24_ERR_SHAPE;
+    return launch_decompress(V, meta, P, M, K, ldp, t, l, static_cast<hipStream_t>(stream));
+}
+
+static sp24_status mm_common(MmArgs& a, hipStream_t st)
+{
+    if (!is_input_type(a.in) || !out_legal(a.in, a.out)) return SP24_ERR_DTYPE;
+    if (a.bo != SP24_B_KMAJOR && a.bo != SP24_B_NMAJOR) return SP24_ERR_LAYOUT;
+    if (a.M < 0 || a.N < 0 || !k_legal(a.K, a.in)) return SP24_ERR_SHAPE;
+    if (a.sparse) {
+        if (!is_layout(a.layout)) return SP24_ERR_LAYOUT;
+        if (!layout_fits(a.M, a.K, a.layout)) return SP24_ERR_LAYOUT;
+    }
+    if (a.M == 0 || a.N == 0) return SP24_OK;
+    int es = esize_of(a.in), os = esize_of(a.out);
+    sp24_status s;
+    if (a.sparse) {
+        if (!a.A || !a.meta) return SP24_ERR_NULL;
+        if (!aligned16(a.A) || !aligned16(a.meta)) return SP24_ERR_ALIGN;
+    } else {
+        s = check_matrix(a.A, a.M, a.K, a.lda, es);
+        if (s != SP24_OK) return s;
+    }
+    s = (a.bo == SP24_B_KMAJOR) ? check_matrix(a.B, a.N, a.K, a.ldb, es, false) : check_matrix(a.B, a.K, a.N, a.ldb, es, false);
+    if (s != SP24_OK) return s;
+    s = check_matrix(a.D, a.M, a.N, a.ldd, os, false);
+    if (s != SP24_OK) return s;
+    size_t nd = ((size_t)(a.M - 1) * a.ldd + a.N) * os;
+    size_t nb = (a.bo == SP24_B_KMAJOR) ? ((size_t)(a.N - 1) * a.ldb + a.K) * es : ((size_t)(a.K - 1) * a.ldb + a.N) * es;
+    size_t nA = a.sparse ? sp24_values_bytes(a.M, a.K, a.in) : ((size_t)(a.M - 1) * a.lda + a.K) * es;
+    if (ranges_overlap(a.D, nd, a.B, nb) || ranges_overlap(a.D, nd, a.A, nA)) return SP24_ERR_SHAPE;
+    if (a.sparse && ranges_overlap(a.D, nd, a.meta, sp24_meta_bytes(a.M, a.K, a.in, a.layout))) return SP24_ERR_SHAPE;
+    bool handled = false;
+    s = launch_mm_tiled(a, st, &handled);
+    if (handled) return s;
+    return launch_mm_simple(a, st);
+}
+
+sp24_status sp24_spmm(const void* V, const void* meta, const void* B, void* D, int64_t M, int64_t N, int64_t K, int64_t ldb,
+                      int64_t ldd, sp24_dtype in, sp24_dtype out, sp24_border bo, sp24_layout l, void* stream)
+{
+    MmArgs a{V, meta, B, D, M, N, K, 0, ldb, ldd, in, out, bo, l, true};
+    return mm_common(a, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
+                            int64_t ldd, sp24_dtype in, sp24_dtype out, sp24_border bo, void* stream)
+{
+    MmArgs a{A, nullptr, B, D, M, N, K, lda, ldb, ldd, in, out, bo, SP24_LAYOUT_CANONICAL, false};
+    return mm_common(a, static_cast<hipStream_t>(stream));
+}
+
+const char* sp24_status_string(sp24_status s)
+{
+    switch (s) {
+    case SP24_OK: return "ok";
+    case SP24_ERR_NULL: return "a required pointer is NULL";
+    case SP24_ERR_SHAPE: return "illegal shape, leading dimension or overlapping buffers";
+    case SP24_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
+    case SP24_ERR_DTYPE: return "unknown or unsupported element type";
+    case SP24_ERR_LAYOUT: return "unknown layout or shape not legal for the layout";
+    case SP24_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+} // extern "C"

@@ -1,0 +1,95 @@
+// Shared device-side helpers of libsp24 (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sp24.h"
+
+namespace sp24 {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef int int8v __attribute__((ext_vector_type(8)));
+typedef int int16v __attribute__((ext_vector_type(16)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+
+__host__ __device__ inline int esize_of(sp24_dtype t)
+{
+    return (t == SP24_I8) ? 1 : (t == SP24_F16 || t == SP24_BF16) ? 2 : 4;
+}
+
+// ---------------------------------------------------------------------------
+// Selection rule (Sec. 4.1 Step 2: drop the two smallest magnitudes of four).
+// Magnitudes are compared through an unsigned key: for 16-bit floats the bit
+// pattern without its sign, with every NaN clamped to one key just above
+// infinity; for int8 the absolute value in a wider type (|-128| = 128).
+// Equal keys: the lower column wins.
+// ---------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ uint32_t mag_key16(uint32_t bits)
+{
+    constexpr uint32_t inf = (DT == SP24_F16) ? 0x7C00u : 0x7F80u;
+    uint32_t a = bits & 0x7FFFu;
+    return a > inf ? inf + 1u : a;
+}
+
+__device__ __forceinline__ uint32_t mag_key8(uint32_t byte)
+{
+    int v = (int)(int8_t)byte;
+    return (uint32_t)(v < 0 ? -v : v);
+}
+
+// Returns the 4-bit keep mask (bit i set = column i survives); exactly two bits set.
+__device__ __forceinline__ uint32_t keep_mask(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3)
+{
+    // c_ab = 1 when column a outranks column b (a < b, so a also wins ties)
+    uint32_t c01 = k0 >= k1, c02 = k0 >= k2, c03 = k0 >= k3;
+    uint32_t c12 = k1 >= k2, c13 = k1 >= k3, c23 = k2 >= k3;
+    uint32_t ahead0 = 3u - c01 - c02 - c03;
+    uint32_t ahead1 = c01 + 2u - c12 - c13;
+    uint32_t ahead2 = c02 + c12 + 1u - c23;
+    uint32_t ahead3 = c03 + c13 + c23;
+    return (ahead0 < 2u) | ((ahead1 < 2u) << 1) | ((ahead2 < 2u) << 2) | ((ahead3 < 2u) << 3);
+}
+
+// Metadata code pos0 | pos1 << 2 for a keep mask with two bits set (Sec. 3.1:
+// 2 bits per kept value, positions in ascending order).
+__device__ __forceinline__ uint32_t code_of_mask(uint32_t mask)
+{
+    // nibble table indexed by mask: 0011->0x4 0101->0x8 0110->0x9 1001->0xC 1010->0xD 1100->0xE
+    constexpr uint64_t table = (0x4ull << (4 * 0x3)) | (0x8ull << (4 * 0x5)) | (0x9ull << (4 * 0x6)) |
+                               (0xCull << (4 * 0x9)) | (0xDull << (4 * 0xA)) | (0xEull << (4 * 0xC));
+    return (uint32_t)(table >> (4 * mask)) & 0xFu;
+}
+
+// ---------------------------------------------------------------------------
+// fp32 -> 16-bit storage, round to nearest even.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u); // quiet NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
+{
+    _Float16 h = (_Float16)f; // v_cvt_f16_f32: round to nearest even
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+template <int OUT>
+__device__ __forceinline__ void store_out(void* D, int64_t idx, float v)
+{
+    if constexpr (OUT == SP24_F32) reinterpret_cast<float*>(D)[idx] = v;
+    else if constexpr (OUT == SP24_F16) reinterpret_cast<uint16_t*>(D)[idx] = f32_to_f16_bits(v);
+    else reinterpret_cast<uint16_t*>(D)[idx] = f32_to_bf16_bits(v);
+}
+
+} // namespace sp24

@@ -1,0 +1,34 @@
+// Internal launch entry points shared by the C-ABI layer (api.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "../../include/sp24.h"
+
+namespace sp24 {
+
+sp24_status launch_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t, hipStream_t st);
+sp24_status launch_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_dtype t, sp24_layout l, hipStream_t st);
+sp24_status launch_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp, sp24_dtype t, sp24_layout l, hipStream_t st);
+
+// Problem description for the matrix-multiply kernels.  For the sparse product
+// A = V and lda is unused; for the dense product meta is null.
+struct MmArgs {
+    const void* A;      // V (sparse) or dense A
+    const void* meta;   // sparse only
+    const void* B;
+    void* D;
+    int64_t M, N, K;
+    int64_t lda, ldb, ldd; // elements
+    sp24_dtype in, out;
+    sp24_border bo;
+    sp24_layout layout;    // sparse only
+    bool sparse;
+};
+
+// General kernel: any M, N; both layouts; both B orders.  One wavefront per 32x32 tile of D.
+sp24_status launch_mm_simple(const MmArgs& a, hipStream_t st);
+
+// Tiled kernels for large shapes; return false in *handled when the shape does not fit them.
+sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled);
+
+} // namespace sp24

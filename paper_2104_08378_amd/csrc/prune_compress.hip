@@ -1,0 +1,313 @@
+// Prune / compress / decompress kernels: one streaming pass each, HBM-bound.
+//
+// Sec. 3.1 notes that the fixed 2-of-4 structure needs no indirection: the
+// position of every kept value in memory follows from the compression rate
+// alone.  That is what lets each lane below work on a fixed 16..64 byte piece
+// of a row with full-width loads and stores and no inter-lane traffic.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace sp24 {
+
+// ---- per-group arithmetic ------------------------------------------------
+
+// 16-bit: a group is two dwords (x0 | x1<<16, x2 | x3<<16).
+template <int DT>
+__device__ __forceinline__ uint32_t mask16(uint32_t w0, uint32_t w1)
+{
+    return keep_mask(mag_key16<DT>(w0), mag_key16<DT>(w0 >> 16), mag_key16<DT>(w1), mag_key16<DT>(w1 >> 16));
+}
+
+// int8: a group is one dword.
+__device__ __forceinline__ uint32_t mask8(uint32_t w)
+{
+    return keep_mask(mag_key8(w & 0xFFu), mag_key8((w >> 8) & 0xFFu), mag_key8((w >> 16) & 0xFFu), mag_key8(w >> 24));
+}
+
+__device__ __forceinline__ void prune16(uint32_t& w0, uint32_t& w1, uint32_t m)
+{
+    w0 &= ((m & 1u) ? 0xFFFFu : 0u) | ((m & 2u) ? 0xFFFF0000u : 0u);
+    w1 &= ((m & 4u) ? 0xFFFFu : 0u) | ((m & 8u) ? 0xFFFF0000u : 0u);
+}
+
+__device__ __forceinline__ uint32_t prune8(uint32_t w, uint32_t m)
+{
+    return w & (((m & 1u) ? 0xFFu : 0u) | ((m & 2u) ? 0xFF00u : 0u) | ((m & 4u) ? 0xFF0000u : 0u) | ((m & 8u) ? 0xFF000000u : 0u));
+}
+
+// the two survivors in column order, packed low/high
+__device__ __forceinline__ uint32_t pack16(uint32_t w0, uint32_t w1, uint32_t m)
+{
+    uint32_t x0 = w0 & 0xFFFFu, x1 = w0 >> 16, x2 = w1 & 0xFFFFu, x3 = w1 >> 16;
+    uint32_t first = (m & 1u) ? x0 : (m & 2u) ? x1 : x2;
+    uint32_t second = (m & 8u) ? x3 : (m & 4u) ? x2 : x1;
+    return first | (second << 16);
+}
+
+__device__ __forceinline__ uint32_t pack8(uint32_t w, uint32_t m)
+{
+    uint32_t x0 = w & 0xFFu, x1 = (w >> 8) & 0xFFu, x2 = (w >> 16) & 0xFFu, x3 = w >> 24;
+    uint32_t first = (m & 1u) ? x0 : (m & 2u) ? x1 : x2;
+    uint32_t second = (m & 8u) ? x3 : (m & 4u) ? x2 : x1;
+    return first | (second << 8);
+}
+
+// scatter two values back by a 4-bit code (pos0 | pos1 << 2)
+__device__ __forceinline__ void unpack16(uint32_t pair, uint32_t code, uint32_t& w0, uint32_t& w1)
+{
+    uint32_t p0 = code & 3u, p1 = (code >> 2) & 3u;
+    uint32_t v0 = pair & 0xFFFFu, v1 = pair >> 16;
+    uint32_t x0 = (p0 == 0u) ? v0 : 0u;
+    uint32_t x1 = (p0 == 1u) ? v0 : (p1 == 1u) ? v1 : 0u;
+    uint32_t x2 = (p0 == 2u) ? v0 : (p1 == 2u) ? v1 : 0u;
+    uint32_t x3 = (p1 == 3u) ? v1 : 0u;
+    w0 = x0 | (x1 << 16);
+    w1 = x2 | (x3 << 16);
+}
+
+__device__ __forceinline__ uint32_t unpack8(uint32_t pair, uint32_t code)
+{
+    uint32_t p0 = code & 3u, p1 = (code >> 2) & 3u;
+    uint32_t v0 = pair & 0xFFu, v1 = (pair >> 8) & 0xFFu;
+    uint32_t x0 = (p0 == 0u) ? v0 : 0u;
+    uint32_t x1 = (p0 == 1u) ? v0 : (p1 == 1u) ? v1 : 0u;
+    uint32_t x2 = (p0 == 2u) ? v0 : (p1 == 2u) ? v1 : 0u;
+    uint32_t x3 = (p1 == 3u) ? v1 : 0u;
+    return x0 | (x1 << 8) | (x2 << 16) | (x3 << 24);
+}
+
+// ---- prune: dense -> dense ----------------------------------------------
+// One lane per 16-byte piece of a row.
+template <int DT>
+__global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, uint8_t* __restrict__ P, int64_t M,
+                                               int64_t chunks_per_row, int64_t lda_bytes, int64_t ldp_bytes)
+{
+    int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= M * chunks_per_row) return;
+    int64_t m = id / chunks_per_row, c = id - m * chunks_per_row;
+    uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
+    if constexpr (DT == SP24_I8) {
+        for (int g = 0; g < 4; ++g) w[g] = prune8(w[g], mask8(w[g]));
+    } else {
+        for (int g = 0; g < 2; ++g) {
+            uint32_t w0 = w[2 * g], w1 = w[2 * g + 1];
+            prune16(w0, w1, mask16<DT>(w0, w1));
+            w[2 * g] = w0;
+            w[2 * g + 1] = w1;
+        }
+    }
+    *reinterpret_cast<uint4v*>(P + m * ldp_bytes + c * 16) = w;
+}
+
+// ---- compress, canonical layout -------------------------------------------
+// One lane per 16 input bytes: 8 bytes of V and 1 (16-bit) or 2 (int8) bytes
+// of metadata; consecutive lanes write consecutive addresses in both arrays.
+template <int DT>
+__global__ __launch_bounds__(256) void k_compress_canon(const uint8_t* __restrict__ A, uint8_t* __restrict__ V,
+                                                        uint8_t* __restrict__ meta, int64_t M, int64_t chunks_per_row,
+                                                        int64_t lda_bytes)
+{
+    int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= M * chunks_per_row) return;
+    int64_t m = id / chunks_per_row, c = id - m * chunks_per_row;
+    uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
+    uint2v v;
+    if constexpr (DT == SP24_I8) {
+        uint32_t m0 = mask8(w[0]), m1 = mask8(w[1]), m2 = mask8(w[2]), m3 = mask8(w[3]);
+        v[0] = pack8(w[0], m0) | (pack8(w[1], m1) << 16);
+        v[1] = pack8(w[2], m2) | (pack8(w[3], m3) << 16);
+        uint32_t codes = code_of_mask(m0) | (code_of_mask(m1) << 4) | (code_of_mask(m2) << 8) | (code_of_mask(m3) << 12);
+        *reinterpret_cast<uint16_t*>(meta + id * 2) = (uint16_t)codes; // rows are K/8 = 2*chunks bytes: id*2 is exact
+    } else {
+        uint32_t m0 = mask16<DT>(w[0], w[1]), m1 = mask16<DT>(w[2], w[3]);
+        v[0] = pack16(w[0], w[1], m0);
+        v[1] = pack16(w[2], w[3], m1);
+        meta[id] = (uint8_t)(code_of_mask(m0) | (code_of_mask(m1) << 4)); // rows are K/8 = chunks bytes
+    }
+    *reinterpret_cast<uint2v*>(V + id * 8) = v; // V rows are 8 * chunks bytes in both cases
+}
+
+// ---- compress, tiled layout -----------------------------------------------
+// One lane per slot: 32 consecutive elements of one row (half of a 32x64
+// tile).  A wavefront covers one whole tile, so its V and metadata stores are
+// contiguous runs of 1 KiB and 256 bytes.
+template <int DT>
+__global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restrict__ A, uint8_t* __restrict__ V,
+                                                        uint32_t* __restrict__ meta, int64_t tiles, int64_t KB,
+                                                        int64_t lda_bytes)
+{
+    int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t tile = id >> 6;
+    if (tile >= tiles) return;
+    uint32_t slot = (uint32_t)id & 63u, r = slot & 31u, h = slot >> 5;
+    int64_t rb = tile / KB, kb = tile - rb * KB;
+    int64_t m = rb * 32 + r;
+    uint32_t codes = 0;
+    if constexpr (DT == SP24_I8) {
+        const uint4v* src = reinterpret_cast<const uint4v*>(A + m * lda_bytes + kb * 64 + h * 32);
+        uint4v v;
+        for (int q = 0; q < 2; ++q) {
+            uint4v w = src[q];
+            uint32_t pk[4];
+            for (int g = 0; g < 4; ++g) {
+                uint32_t mk = mask8(w[g]);
+                pk[g] = pack8(w[g], mk);
+                codes |= code_of_mask(mk) << (4 * (4 * q + g));
+            }
+            v[2 * q] = pk[0] | (pk[1] << 16);
+            v[2 * q + 1] = pk[2] | (pk[3] << 16);
+        }
+        *reinterpret_cast<uint4v*>(V + (tile * 64 + slot) * 16) = v;
+    } else {
+        const uint4v* src = reinterpret_cast<const uint4v*>(A + m * lda_bytes + kb * 128 + h * 64);
+        for (int s = 0; s < 2; ++s) {
+            uint4v v;
+            for (int q = 0; q < 2; ++q) {
+                uint4v w = src[2 * s + q];
+                uint32_t m0 = mask16<DT>(w[0], w[1]), m1 = mask16<DT>(w[2], w[3]);
+                v[2 * q] = pack16(w[0], w[1], m0);
+                v[2 * q + 1] = pack16(w[2], w[3], m1);
+                codes |= (code_of_mask(m0) | (code_of_mask(m1) << 4)) << (8 * (2 * s + q));
+            }
+            *reinterpret_cast<uint4v*>(V + ((tile * 2 + s) * 64 + slot) * 16) = v;
+        }
+    }
+    meta[tile * 64 + slot] = codes;
+}
+
+// ---- decompress -----------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void k_decompress_canon(const uint8_t* __restrict__ V, const uint8_t* __restrict__ meta,
+                                                          uint8_t* __restrict__ P, int64_t M, int64_t chunks_per_row,
+                                                          int64_t ldp_bytes)
+{
+    int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= M * chunks_per_row) return;
+    int64_t m = id / chunks_per_row, c = id - m * chunks_per_row;
+    uint2v v = *reinterpret_cast<const uint2v*>(V + id * 8);
+    uint4v w;
+    if constexpr (DT == SP24_I8) {
+        uint32_t codes = *reinterpret_cast<const uint16_t*>(meta + id * 2);
+        w[0] = unpack8(v[0] & 0xFFFFu, codes & 0xFu);
+        w[1] = unpack8(v[0] >> 16, (codes >> 4) & 0xFu);
+        w[2] = unpack8(v[1] & 0xFFFFu, (codes >> 8) & 0xFu);
+        w[3] = unpack8(v[1] >> 16, codes >> 12);
+    } else {
+        uint32_t codes = meta[id];
+        uint32_t a, b;
+        unpack16(v[0], codes & 0xFu, a, b);
+        w[0] = a; w[1] = b;
+        unpack16(v[1], codes >> 4, a, b);
+        w[2] = a; w[3] = b;
+    }
+    *reinterpret_cast<uint4v*>(P + m * ldp_bytes + c * 16) = w;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_decompress_tiled(const uint8_t* __restrict__ V, const uint32_t* __restrict__ meta,
+                                                          uint8_t* __restrict__ P, int64_t tiles, int64_t KB,
+                                                          int64_t ldp_bytes)
+{
+    int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t tile = id >> 6;
+    if (tile >= tiles) return;
+    uint32_t slot = (uint32_t)id & 63u, r = slot & 31u, h = slot >> 5;
+    int64_t rb = tile / KB, kb = tile - rb * KB;
+    int64_t m = rb * 32 + r;
+    uint32_t codes = meta[tile * 64 + slot];
+    if constexpr (DT == SP24_I8) {
+        uint4v v = *reinterpret_cast<const uint4v*>(V + (tile * 64 + slot) * 16);
+        uint4v* dst = reinterpret_cast<uint4v*>(P + m * ldp_bytes + kb * 64 + h * 32);
+        for (int q = 0; q < 2; ++q) {
+            uint4v w;
+            w[0] = unpack8(v[2 * q] & 0xFFFFu, (codes >> (16 * q)) & 0xFu);
+            w[1] = unpack8(v[2 * q] >> 16, (codes >> (16 * q + 4)) & 0xFu);
+            w[2] = unpack8(v[2 * q + 1] & 0xFFFFu, (codes >> (16 * q + 8)) & 0xFu);
+            w[3] = unpack8(v[2 * q + 1] >> 16, (codes >> (16 * q + 12)) & 0xFu);
+            dst[q] = w;
+        }
+    } else {
+        uint4v* dst = reinterpret_cast<uint4v*>(P + m * ldp_bytes + kb * 128 + h * 64);
+        for (int s = 0; s < 2; ++s) {
+            uint4v v = *reinterpret_cast<const uint4v*>(V + ((tile * 2 + s) * 64 + slot) * 16);
+            for (int q = 0; q < 2; ++q) {
+                uint32_t cc = (codes >> (8 * (2 * s + q))) & 0xFFu;
+                uint4v w;
+                uint32_t a, b;
+                unpack16(v[2 * q], cc & 0xFu, a, b);
+                w[0] = a; w[1] = b;
+                unpack16(v[2 * q + 1], cc >> 4, a, b);
+                w[2] = a; w[3] = b;
+                dst[2 * s + q] = w;
+            }
+        }
+    }
+}
+
+// ---- launchers ------------------------------------------------------------
+static inline unsigned blocks_for(int64_t items) { return (unsigned)((items + 255) / 256); }
+
+template <int DT>
+static void run_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, hipStream_t st)
+{
+    constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
+    int64_t cpr = K * es / 16;
+    k_prune<DT><<<blocks_for(M * cpr), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)P, M, cpr, lda * es, ldp * es);
+}
+
+template <int DT>
+static void run_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_layout l, hipStream_t st)
+{
+    constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
+    if (l == SP24_LAYOUT_CANONICAL) {
+        int64_t cpr = K * es / 16;
+        k_compress_canon<DT><<<blocks_for(M * cpr), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint8_t*)meta, M, cpr, lda * es);
+    } else {
+        int64_t KB = K / 64, tiles = (M / 32) * KB;
+        k_compress_tiled<DT><<<blocks_for(tiles * 64), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint32_t*)meta, tiles, KB, lda * es);
+    }
+}
+
+template <int DT>
+static void run_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp, sp24_layout l, hipStream_t st)
+{
+    constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
+    if (l == SP24_LAYOUT_CANONICAL) {
+        int64_t cpr = K * es / 16;
+        k_decompress_canon<DT><<<blocks_for(M * cpr), 256, 0, st>>>((const uint8_t*)V, (const uint8_t*)meta, (uint8_t*)P, M, cpr, ldp * es);
+    } else {
+        int64_t KB = K / 64, tiles = (M / 32) * KB;
+        k_decompress_tiled<DT><<<blocks_for(tiles * 64), 256, 0, st>>>((const uint8_t*)V, (const uint32_t*)meta, (uint8_t*)P, tiles, KB, ldp * es);
+    }
+}
+
+static sp24_status launch_result() { return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH; }
+
+sp24_status launch_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t, hipStream_t st)
+{
+    if (M * K == 0) return SP24_OK;
+    if (t == SP24_F16) run_prune<SP24_F16>(A, P, M, K, lda, ldp, st);
+    else if (t == SP24_BF16) run_prune<SP24_BF16>(A, P, M, K, lda, ldp, st);
+    else run_prune<SP24_I8>(A, P, M, K, lda, ldp, st);
+    return launch_result();
+}
+
+sp24_status launch_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_dtype t, sp24_layout l, hipStream_t st)
+{
+    if (M * K == 0) return SP24_OK;
+    if (t == SP24_F16) run_compress<SP24_F16>(A, V, meta, M, K, lda, l, st);
+    else if (t == SP24_BF16) run_compress<SP24_BF16>(A, V, meta, M, K, lda, l, st);
+    else run_compress<SP24_I8>(A, V, meta, M, K, lda, l, st);
+    return launch_result();
+}
+
+sp24_status launch_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp, sp24_dtype t, sp24_layout l, hipStream_t st)
+{
+    if (M * K == 0) return SP24_OK;
+    if (t == SP24_F16) run_decompress<SP24_F16>(V, meta, P, M, K, ldp, l, st);
+    else if (t == SP24_BF16) run_decompress<SP24_BF16>(V, meta, P, M, K, ldp, l, st);
+    else run_decompress<SP24_I8>(V, meta, P, M, K, ldp, l, st);
+    return launch_result();
+}
+
+} // namespace sp24

@@ -1,0 +1,155 @@
+"""Python binding of libsp24.so: argument marshalling only.
+
+Each function mirrors the C entry point of the same name (``include/sp24.h``):
+it checks that the tensors live on the GPU, allocates the outputs with torch,
+passes raw device pointers and the current HIP stream, and raises on a non-zero
+status.  Every arithmetic step runs in the library's HIP kernels; there is no
+fallback: if ``libsp24.so`` is not built the import of the symbols fails loudly.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsp24.so")
+
+F16, BF16, I8, F32, I32 = 0, 1, 2, 3, 4
+CANONICAL, TILED = 0, 1
+B_KMAJOR, B_NMAJOR = 0, 1
+
+_DT = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8, torch.float32: F32, torch.int32: I32}
+_LAYOUT = {"canonical": CANONICAL, "tiled": TILED}
+_lib = None
+
+
+class Sp24Error(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib():
+    """Load libsp24.so (built by ``python -m paper_2104_08378_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2104_08378_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.sp24_values_bytes.argtypes = [i64, i64, i32]
+        L.sp24_values_bytes.restype = ctypes.c_size_t
+        L.sp24_meta_bytes.argtypes = [i64, i64, i32, i32]
+        L.sp24_meta_bytes.restype = ctypes.c_size_t
+        L.sp24_prune.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp]
+        L.sp24_compress.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
+        L.sp24_decompress.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
+        L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
+        L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
+        L.sp24_status_string.argtypes = [i32]
+        L.sp24_status_string.restype = ctypes.c_char_p
+        for name in ("sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().sp24_status_string(int(status)).decode()
+
+
+def sp24_values_bytes(M, K, dtype):
+    return lib().sp24_values_bytes(M, K, _DT[dtype])
+
+
+def sp24_meta_bytes(M, K, dtype, layout="canonical"):
+    return lib().sp24_meta_bytes(M, K, _DT[dtype], _LAYOUT[layout])
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    return t
+
+
+def _rowmajor(t, name):
+    _dev(t, name)
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{name} must be 2-d with unit column stride")
+    return t
+
+
+def _check(status, where):
+    if status != 0:
+        raise Sp24Error(status, where)
+
+
+def sp24_prune(A, out=None):
+    """P = A with the two smallest-magnitude entries of each group of 4 zeroed; out may be A."""
+    _rowmajor(A, "A")
+    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
+    M, K = A.shape
+    _check(lib().sp24_prune(A.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype], _stream()),
+           "sp24_prune")
+    return P
+
+
+def sp24_compress(A, layout="canonical"):
+    """Return (V, meta): V [M, K/2] of A's dtype, meta uint8 [M, K/8] (both flat-permuted for "tiled")."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    V = torch.empty((M, K // 2), dtype=A.dtype, device=A.device)
+    meta = torch.empty((M, K // 8), dtype=torch.uint8, device=A.device)
+    _check(lib().sp24_compress(A.data_ptr(), V.data_ptr(), meta.data_ptr(), M, K, A.stride(0), _DT[A.dtype],
+                               _LAYOUT[layout], _stream()), "sp24_compress")
+    return V, meta
+
+
+def sp24_decompress(V, meta, layout="canonical", out=None):
+    _dev(V, "V"), _dev(meta, "meta")
+    M, K = V.shape[0], V.shape[1] * 2
+    P = torch.empty((M, K), dtype=V.dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_decompress(V.data_ptr(), meta.data_ptr(), P.data_ptr(), M, K, P.stride(0), _DT[V.dtype],
+                                 _LAYOUT[layout], _stream()), "sp24_decompress")
+    return P
+
+
+def _b_args(B, b_order):
+    _rowmajor(B, "B")
+    if b_order == "k":      # B given as [N, K]: one row per column of the math operand
+        N, K = B.shape
+        return N, K, B_KMAJOR
+    if b_order == "n":      # B given as [K, N]
+        K, N = B.shape
+        return N, K, B_NMAJOR
+    raise ValueError("b_order must be 'k' or 'n'")
+
+
+def sp24_spmm(V, meta, B, out_dtype, b_order="k", layout="canonical", out=None):
+    """D [M, N] = decompress(V, meta) @ B.  B is [N, K] for b_order "k", [K, N] for "n"."""
+    _dev(V, "V"), _dev(meta, "meta")
+    M, K = V.shape[0], V.shape[1] * 2
+    N, Kb, bo = _b_args(B, b_order)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_spmm(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0),
+                           D.stride(0), _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], _stream()), "sp24_spmm")
+    return D
+
+
+def sp24_gemm_dense(A, B, out_dtype, b_order="k", out=None):
+    """D [M, N] = A @ B on the dense matrix cores (speedup denominator)."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    N, Kb, bo = _b_args(B, b_order)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_gemm_dense(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0),
+                                 D.stride(0), _DT[A.dtype], _DT[D.dtype], bo, _stream()), "sp24_gemm_dense")
+    return D

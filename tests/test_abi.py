@@ -1,0 +1,101 @@
+"""Host-only checks of the C ABI: the library loads, exports everything the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2104_08378_amd import sp24
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sp24.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sp24_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert {"sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense"} <= set(names)
+    L = sp24.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_size_functions_follow_the_storage_closed_forms():
+    # Sec. 3.1: K/2 values and 2 bits per kept value -> K/8 bytes per row
+    for dt, es in ((sp24.torch.float16, 2), (sp24.torch.bfloat16, 2), (sp24.torch.int8, 1)):
+        M, K = 96, 256
+        v, m = sp24.sp24_values_bytes(M, K, dt), sp24.sp24_meta_bytes(M, K, dt)
+        assert v == M * K // 2 * es and m == M * K // 8
+        assert v + m == M * K * (es / 2 + 1 / 8)
+        assert sp24.sp24_meta_bytes(M, K, dt, "tiled") == m
+    assert sp24.sp24_values_bytes(8, 24, sp24.torch.float16) == 0      # K % 16
+    assert sp24.sp24_values_bytes(8, 48, sp24.torch.int8) == 0         # K % 32
+    assert sp24.sp24_meta_bytes(48, 64, sp24.torch.int8, "tiled") == 0  # M % 32
+    assert sp24.sp24_meta_bytes(64, 96, sp24.torch.int8, "tiled") == 0  # K % 64
+
+
+def test_status_strings():
+    assert sp24.status_string(0) == "ok"
+    for s in range(1, 7):
+        assert sp24.status_string(s) not in ("ok", "unknown status")
+
+
+OK, NULL, SHAPE, ALIGN, DTYPE, LAYOUT = 0, 1, 2, 3, 4, 5
+P = 0x10000  # a fake, aligned, never dereferenced device address
+
+
+@pytest.mark.parametrize("args,want", [
+    ((0, P, 32, 64, 64, 64, sp24.F16, None), NULL),
+    ((P, P + 0x100000, 32, 24, 64, 64, sp24.F16, None), SHAPE),      # K % 16
+    ((P, P + 0x100000, 32, 48, 64, 64, sp24.I8, None), SHAPE),       # K % 32
+    ((P, P + 0x100000, 32, 64, 32, 64, sp24.F16, None), SHAPE),      # lda < K
+    ((P + 2, P + 0x100000, 32, 64, 64, 64, sp24.F16, None), ALIGN),
+    ((P, P + 0x100000, 32, 64, 68, 64, sp24.F16, None), ALIGN),      # row pitch not 16 B
+    ((P, P + 0x100000, 32, 64, 64, 64, 7, None), DTYPE),
+    ((P, P + 0x100000, 32, 64, 64, 64, sp24.F32, None), DTYPE),
+    ((P, P + 64, 32, 64, 64, 64, sp24.F16, None), SHAPE),            # partial overlap
+    ((P, P, 32, 64, 64, 128, sp24.F16, None), SHAPE),                # in place needs equal pitch
+    ((P, P + 0x100000, -1, 64, 64, 64, sp24.F16, None), SHAPE),
+    ((0, 0, 0, 64, 64, 64, sp24.F16, None), OK),                     # empty: nothing to do
+])
+def test_prune_rejects_bad_arguments_on_the_host(args, want):
+    assert sp24.lib().sp24_prune(*args) == want
+
+
+def test_compress_and_decompress_validation():
+    L = sp24.lib()
+    big = P + 0x1000000
+    assert L.sp24_compress(P, big, big * 2, 48, 64, 64, sp24.F16, sp24.TILED, None) == LAYOUT
+    assert L.sp24_compress(P, big, big * 2, 64, 96, 96, sp24.I8, sp24.TILED, None) == LAYOUT
+    assert L.sp24_compress(P, big, big * 2, 64, 64, 64, sp24.F16, 9, None) == LAYOUT
+    assert L.sp24_compress(P, 0, big, 64, 64, 64, sp24.F16, sp24.CANONICAL, None) == NULL
+    assert L.sp24_compress(P, P + 16, big, 64, 64, 64, sp24.F16, sp24.CANONICAL, None) == SHAPE   # V inside A
+    assert L.sp24_compress(P, big + 8, big * 2, 64, 64, 64, sp24.F16, sp24.CANONICAL, None) == ALIGN
+    assert L.sp24_decompress(big, big * 2, P, 64, 40, 64, sp24.F16, sp24.CANONICAL, None) == SHAPE
+    assert L.sp24_decompress(big, 0, P, 64, 64, 64, sp24.F16, sp24.CANONICAL, None) == NULL
+    assert L.sp24_decompress(0, 0, 0, 0, 64, 64, sp24.I8, sp24.CANONICAL, None) == OK
+
+
+def test_matmul_validation():
+    L = sp24.lib()
+    V, Mt, B, D = P, P + 0x1000000, P + 0x2000000, P + 0x3000000
+
+    def spmm(M=64, N=64, K=64, ldb=64, ldd=64, i=sp24.F16, o=sp24.F32, bo=0, lay=0, V=V, Mt=Mt, B=B, D=D):
+        return L.sp24_spmm(V, Mt, B, D, M, N, K, ldb, ldd, i, o, bo, lay, None)
+
+    assert spmm(o=sp24.I32) == DTYPE and spmm(i=sp24.I8, o=sp24.F32) == DTYPE and spmm(i=sp24.F32) == DTYPE
+    assert spmm(K=72) == SHAPE and spmm(ldb=32) == SHAPE and spmm(ldd=32) == SHAPE and spmm(N=-2) == SHAPE
+    assert spmm(bo=2) == LAYOUT and spmm(lay=3) == LAYOUT and spmm(M=48, lay=sp24.TILED) == LAYOUT
+    assert spmm(B=0) == NULL and spmm(Mt=0) == NULL and spmm(D=0) == NULL
+    assert spmm(D=D + 2) == ALIGN and spmm(B=B + 1) == ALIGN and spmm(V=V + 8) == ALIGN
+    assert spmm(D=B) == SHAPE                                         # output aliases an input
+    assert spmm(M=0) == OK and spmm(N=0) == OK
+    assert L.sp24_gemm_dense(V, B, D, 64, 64, 64, 32, 64, 64, sp24.F16, sp24.F32, 0, None) == SHAPE
+    assert L.sp24_gemm_dense(0, B, D, 64, 64, 64, 64, 64, 64, sp24.F16, sp24.F32, 0, None) == NULL
+    assert L.sp24_gemm_dense(V, B, D, 64, 64, 64, 64, 64, 64, sp24.I8, sp24.F16, 0, None) == DTYPE

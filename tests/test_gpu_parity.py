@@ -1,0 +1,162 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on the same seeded inputs.  Bit-exact for prune / compress / metadata /
+decompress and for the int8 product; floating products within max relative
+error 1e-2 of the fp64 oracle (the denominator floored at 1e-3 of the result's
+RMS so that cancelled-out entries do not blow the ratio up)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2104_08378_amd import sp24, synth
+from util import OUT_DT, out_to_f64, tiled_from_canonical, to_bits, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+NAME_OF = {"f16": "tiny_f16", "bf16": "ffn_bf16", "i8": "square_i8"}
+REL_TOL = 1e-2
+
+
+def rel_err(got, ref):
+    floor = 1e-3 * np.sqrt(np.mean(ref * ref)) + 1e-300
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), floor)))
+
+
+def adversarial(dtype, M, K, seed):
+    """Ties, zeros, signed zeros, NaN/inf, -128: every corner of the selection rule."""
+    rng = np.random.default_rng(seed)
+    if dtype == "i8":
+        pool = np.array([-128, -127, -2, -1, 0, 0, 1, 2, 127], dtype=np.int8)
+        return rng.choice(pool, size=(M, K))
+    if dtype == "f16":
+        pool = np.array([0x0000, 0x8000, 0x3C00, 0xBC00, 0x3C01, 0x0001, 0x8001, 0x7C00, 0xFC00, 0x7E00, 0xFE01, 0x7BFF], dtype=np.uint16)
+    else:
+        pool = np.array([0x0000, 0x8000, 0x3F80, 0xBF80, 0x3F81, 0x0001, 0x8001, 0x7F80, 0xFF80, 0x7FC0, 0xFF81, 0x7F7F], dtype=np.uint16)
+    return rng.choice(pool, size=(M, K))
+
+
+SHAPES = [(1, 16), (5, 48), (33, 80), (64, 64), (96, 192), (257, 1040)]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("kind", ["workload", "adversarial"])
+def test_prune_compress_decompress_canonical_bit_exact(dtype, kind):
+    for i, (M, K) in enumerate(SHAPES):
+        if dtype == "i8":
+            K = (K + 31) // 32 * 32
+        if kind == "workload":
+            A, _ = synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=i)
+        else:
+            A = adversarial(dtype, M, K, i)
+        Ad = to_gpu(A, dtype)
+        P = sp24.sp24_prune(Ad)
+        V, meta = sp24.sp24_compress(Ad)
+        P2 = sp24.sp24_decompress(V, meta)
+        torch.cuda.synchronize()
+        oP = oracle.prune(A, dtype)
+        oV, ometa = oracle.compress(A, dtype)
+        assert np.array_equal(to_bits(P), oP), (dtype, kind, M, K)
+        assert np.array_equal(to_bits(V), oV), (dtype, kind, M, K)
+        assert np.array_equal(to_bits(meta), ometa), (dtype, kind, M, K)
+        assert np.array_equal(to_bits(P2), oP), (dtype, kind, M, K)
+        # in place
+        Q = Ad.clone()
+        sp24.sp24_prune(Q, out=Q)
+        assert np.array_equal(to_bits(Q), oP)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_strided_rows(dtype):
+    M, K, ld = 37, 96, 160
+    A, _ = synth.make(NAME_OF[dtype], M=M, N=16, K=ld, seed=3)
+    Ad = to_gpu(A, dtype)[:, :K]
+    Pbuf = torch.zeros((M, ld), dtype=Ad.dtype, device="cuda")
+    sp24.sp24_prune(Ad, out=Pbuf[:, :K])
+    V, meta = sp24.sp24_compress(Ad)
+    oP = oracle.prune(np.ascontiguousarray(A[:, :K]), dtype)
+    oV, ometa = oracle.compress(np.ascontiguousarray(A[:, :K]), dtype)
+    assert np.array_equal(to_bits(Pbuf)[:, :K], oP)
+    assert (to_bits(Pbuf)[:, K:] == 0).all()
+    assert np.array_equal(to_bits(V), oV) and np.array_equal(to_bits(meta), ometa)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_tiled_layout_is_the_documented_permutation(dtype):
+    for i, (M, K) in enumerate([(32, 64), (64, 192), (160, 320)]):
+        A = adversarial(dtype, M, K, 10 + i) if i == 1 else synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=i)[0]
+        Ad = to_gpu(A, dtype)
+        V, meta = sp24.sp24_compress(Ad, layout="tiled")
+        P = sp24.sp24_decompress(V, meta, layout="tiled")
+        oV, ometa = oracle.compress(A, dtype)
+        wantV, wantmeta = tiled_from_canonical(oV, ometa, dtype)
+        assert np.array_equal(to_bits(V), wantV), (dtype, M, K)
+        assert np.array_equal(to_bits(meta), wantmeta), (dtype, M, K)
+        assert np.array_equal(to_bits(P), oracle.prune(A, dtype))
+
+
+MM_CASES = [
+    # dtype, out, M, N, K
+    ("f16", "f32", 32, 32, 64),
+    ("f16", "f16", 96, 80, 208),      # ragged N, K % 64 != 0
+    ("bf16", "bf16", 64, 200, 128),
+    ("bf16", "f32", 50, 33, 48),      # ragged M and N
+    ("i8", "i32", 64, 96, 128),
+    ("i8", "i32", 45, 70, 96),
+]
+
+
+def run_mm_case(dtype, out, M, N, K, layout, b_order, sparse, seed=0):
+    A, Bt = synth.make(NAME_OF[dtype], M=M, N=N, K=K, seed=seed)
+    Pn = oracle.prune(A, dtype)
+    Bmath = np.ascontiguousarray(Bt.T)                      # K x N
+    ref = oracle.gemm(Pn, Bmath, dtype)
+    Bd = to_gpu(Bt, dtype) if b_order == "k" else to_gpu(Bmath, dtype)
+    if sparse:
+        V, meta = sp24.sp24_compress(to_gpu(A, dtype), layout=layout)
+        D = sp24.sp24_spmm(V, meta, Bd, OUT_DT[out], b_order=b_order, layout=layout)
+    else:
+        D = sp24.sp24_gemm_dense(to_gpu(Pn, dtype), Bd, OUT_DT[out], b_order=b_order)
+    torch.cuda.synchronize()
+    if dtype == "i8":
+        assert np.array_equal(D.cpu().numpy(), ref), (dtype, M, N, K, layout, b_order, sparse)
+    else:
+        e = rel_err(out_to_f64(D), ref)
+        assert e <= REL_TOL, (dtype, out, M, N, K, layout, b_order, sparse, e)
+        if out == "f32":
+            assert e <= 1e-4
+
+
+@pytest.mark.parametrize("case", MM_CASES)
+@pytest.mark.parametrize("b_order", ["k", "n"])
+def test_spmm_canonical_matches_oracle(case, b_order):
+    run_mm_case(*case, layout="canonical", b_order=b_order, sparse=True)
+
+
+@pytest.mark.parametrize("case", [c for c in MM_CASES if c[2] % 32 == 0 and c[4] % 64 == 0])
+def test_spmm_tiled_matches_oracle(case):
+    run_mm_case(*case, layout="tiled", b_order="k", sparse=True)
+
+
+@pytest.mark.parametrize("case", MM_CASES)
+def test_dense_gemm_matches_oracle(case):
+    run_mm_case(*case, layout="canonical", b_order="k", sparse=False)
+    run_mm_case(*case, layout="canonical", b_order="n", sparse=False, seed=1)
+
+
+def test_all_equal_rows_and_identity_operand():
+    # ties everywhere in A; B = identity returns the pruned matrix itself
+    M = K = N = 64
+    A = np.full((M, K), 0x3C00, dtype=np.uint16)
+    V, meta = sp24.sp24_compress(to_gpu(A, "f16"))
+    eye = synth.to_bits(np.eye(K), "f16")
+    D = sp24.sp24_spmm(V, meta, to_gpu(eye, "f16"), torch.float32)
+    want = oracle.to_double(oracle.prune(A, "f16"), "f16")
+    assert np.array_equal(out_to_f64(D), want)
+
+
+def test_empty_problem_is_a_no_op():
+    A = torch.empty((0, 64), dtype=torch.float16, device="cuda")
+    assert sp24.sp24_prune(A).shape == (0, 64)
+    V, meta = sp24.sp24_compress(A)
+    B = torch.zeros((16, 64), dtype=torch.float16, device="cuda")
+    assert sp24.sp24_spmm(V, meta, B, torch.float32).shape == (0, 16)
