@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the 2:4 sparse matrix-multiply hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input:
+prune -> compress (tiled layout) -> decompress -> sparse product -> same-shape
+dense product.  All inputs are resident in HBM before the timed region; every
+step works on the next of several rotating copies of the inputs so that the
+footprint of the loop exceeds the 256 MB last-level cache.
+
+Prints one JSON line:  metric = dense-equivalent TFLOP/s of the sparse product
+(2*M*N*K / its mean duration, measured with HIP events on the launch stream
+inside the timed region), plus the roofline of that kernel and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_DENSE = {"f16": 2.5e15, "bf16": 2.5e15, "i8": 5.0e15}   # MI355X published dense matrix-core peaks
+PEAK_HBM = 8.0e12
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--workload", default="ffn_bf16")
+    p.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
+    p.add_argument("--only", default="", help="comma list of ops to run in a step (profiling aid); default all")
+    return p.parse_args()
+
+
+def cpu_baseline(name, A, Bt, budget_s):
+    """The oracle as it stands on a bounded sample: prune + compress + decompress + triple-loop
+    product on the first rows of A against the first columns of B."""
+    import numpy as np
+    import oracle
+    from paper_2104_08378_amd import synth
+    w = synth.WORKLOADS[name]
+    dt, K = w["dtype"], w["K"]
+    rows, cols = 16, min(w["N"], 1024)
+    Bs = np.ascontiguousarray(Bt[:cols].T)
+
+    def run(r):
+        As = np.ascontiguousarray(A[:r])
+        t0 = time.perf_counter()
+        V, meta = oracle.compress(As, dt)
+        P = oracle.decompress(V, meta, dt)
+        oracle.gemm(P, Bs, dt)
+        return time.perf_counter() - t0
+
+    t = run(rows)
+    # scale the row count so that the sample takes about the budget
+    rows = int(max(rows, min(w["M"], rows * budget_s / max(t, 1e-3))))
+    rows -= rows % 16
+    t = run(rows)
+    flops = 2.0 * rows * cols * K
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {rows} rows of A x first {cols} columns of B, K={K}: compress + decompress + fp64/int32 triple loop, {t:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2104_08378_amd import sp24, synth
+    from util import OUT_DT, TORCH_DT, to_gpu
+
+    name = args.workload
+    w = synth.WORKLOADS[name]
+    dt, M, K, N = w["dtype"], w["M"], w["K"], w["N"]
+    es = 1 if dt == "i8" else 2
+    out_dt = OUT_DT[w["out"]]
+    os_ = torch.empty((), dtype=out_dt).element_size()
+    torch.cuda.set_device(0)
+    A, Bt = synth.make(name)
+    # rotating input sets: footprint beyond the last-level cache
+    per_set = A.nbytes + Bt.nbytes
+    R = max(2, min(16, int(600e6 // per_set) + 1))
+    As = [to_gpu(A, dt) for _ in range(R)]
+    Bs = [to_gpu(Bt, dt) for _ in range(R)]
+    P = torch.empty_like(As[0])
+    P2 = torch.empty_like(As[0])
+    D = torch.empty((M, N), dtype=out_dt, device="cuda")
+    Dd = torch.empty((M, N), dtype=out_dt, device="cuda")
+    ops = ["prune", "compress", "decompress", "spmm", "dense"]
+    only = [o for o in args.only.split(",") if o] or ops
+    V, meta = sp24.sp24_compress(As[0], layout="tiled")
+    sp24.sp24_prune(As[0], out=P)
+
+    def step(i, ev=None):
+        a, b = As[i % R], Bs[i % R]
+        k = 0
+
+        def mark():
+            nonlocal k
+            if ev is not None:
+                ev[k].record()
+            k += 1
+        mark()
+        if "prune" in only:
+            sp24.sp24_prune(a, out=P)
+        mark()
+        if "compress" in only:
+            sp24.sp24_compress(a, layout="tiled", out=(V, meta))
+        mark()
+        if "decompress" in only:
+            sp24.sp24_decompress(V, meta, layout="tiled", out=P2)
+        mark()
+        if "spmm" in only:
+            sp24.sp24_spmm(V, meta, b, out_dt, layout="tiled", out=D)
+        mark()
+        if "dense" in only:
+            sp24.sp24_gemm_dense(P, b, out_dt, out=Dd)
+        mark()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = {o: float(np.mean([events[i][j].elapsed_time(events[i][j + 1]) for i in range(args.steps)])) for j, o in enumerate(ops)}
+    ms_per_step = wall * 1e3 / args.steps
+
+    flops_equiv = 2.0 * M * N * K
+    t_sp, t_dn = ms["spmm"] * 1e-3, ms["dense"] * 1e-3
+    value = flops_equiv / t_sp / 1e12 if "spmm" in only else 0.0
+    bytes_pc = M * K * es * (1 + 0.5) + M * K / 8            # fused prune+compress: read A, write V + meta
+    bytes_prune = 2.0 * M * K * es
+    bytes_spmm = M * K * es / 2 + M * K / 8 + K * N * es + M * N * os_
+    compute_bound = (flops_equiv / 2 / PEAK_DENSE[dt]) >= (bytes_spmm / PEAK_HBM)
+    if compute_bound:
+        roof = {"bound": "mfma", "achieved": flops_equiv / 2 / t_sp / 1e12, "peak": PEAK_DENSE[dt] / 1e12, "unit": "TFLOP/s",
+                "kernel": "sparse product", "note": "algorithmic math = the kept half, M*N*K flops per launch, against the dense matrix-core peak"}
+    else:
+        roof = {"bound": "hbm", "achieved": bytes_spmm / t_sp / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "kernel": "sparse product",
+                "note": "V + meta + B + D bytes per launch"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    line = {
+        "metric": "2:4 SpGEMM dense-equiv TFLOP/s on 1 MI355X; speedup vs same-shape dense GEMM",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f16": "f16", "bf16": "bf16", "i8": "int8"}[dt], "data": "synthetic",
+        "config": {"workload": name, "M": M, "N": N, "K": K, "out": w["out"], "layout": "tiled", "b_order": "k-major",
+                   "rotating_input_sets": R},
+        "step_ms": ms,
+        "speedup_vs_dense": (t_dn / t_sp) if ("dense" in only and "spmm" in only) else None,
+        "dense_tflops": flops_equiv / t_dn / 1e12 if "dense" in only else None,
+        "prune_GBps": bytes_prune / (ms["prune"] * 1e-3) / 1e9 if "prune" in only else None,
+        "compress_GBps": bytes_pc / (ms["compress"] * 1e-3) / 1e9 if "compress" in only else None,
+        "decompress_GBps": bytes_pc / (ms["decompress"] * 1e-3) / 1e9 if "decompress" in only else None,
+        "roofline": roof,
+    }
+    if args.cpu_seconds > 0:
+        line["cpu_baseline"] = cpu_baseline(name, A, Bt, args.cpu_seconds)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -20,6 +20,7 @@ _SRC = os.path.join(_HERE, "sp24_oracle.c")
 _LIB = os.path.join(_HERE, "libsp24_oracle.so")
 _TYPES = {"f16": 0, "bf16": 1, "i8": 2}
 _lib = None
+_decode_tables = {}
 
 
 def build(force=False):
@@ -134,9 +135,10 @@ def to_double(bits, dtype):
     """Exact value of 16-bit patterns (or int8) as float64, element by element."""
     if dtype == "i8":
         return bits.astype(np.float64)
-    fn = _load().sp24o_f16_to_double if dtype == "f16" else _load().sp24o_bf16_to_double
-    flat = np.ascontiguousarray(bits).reshape(-1)
-    return np.array([fn(int(b)) for b in flat], dtype=np.float64).reshape(bits.shape)
+    if dtype not in _decode_tables:   # the C decoder applied once to each of the 65536 patterns
+        fn = _load().sp24o_f16_to_double if dtype == "f16" else _load().sp24o_bf16_to_double
+        _decode_tables[dtype] = np.array([fn(b) for b in range(65536)], dtype=np.float64)
+    return _decode_tables[dtype][np.asarray(bits, dtype=np.uint16)]
 
 
 def threads():

@@ -98,12 +98,17 @@ def sp24_prune(A, out=None):
     return P
 
 
-def sp24_compress(A, layout="canonical"):
+def sp24_compress(A, layout="canonical", out=None):
     """Return (V, meta): V [M, K/2] of A's dtype, meta uint8 [M, K/8] (both flat-permuted for "tiled")."""
     _rowmajor(A, "A")
     M, K = A.shape
-    V = torch.empty((M, K // 2), dtype=A.dtype, device=A.device)
-    meta = torch.empty((M, K // 8), dtype=torch.uint8, device=A.device)
+    if out is None:
+        V = torch.empty((M, K // 2), dtype=A.dtype, device=A.device)
+        meta = torch.empty((M, K // 8), dtype=torch.uint8, device=A.device)
+    else:
+        V, meta = _dev(out[0], "V"), _dev(out[1], "meta")
+        if V.numel() != M * (K // 2) or V.dtype != A.dtype or meta.numel() * meta.element_size() != M * (K // 8):
+            raise ValueError("out buffers have the wrong size")
     _check(lib().sp24_compress(A.data_ptr(), V.data_ptr(), meta.data_ptr(), M, K, A.stride(0), _DT[A.dtype],
                                _LAYOUT[layout], _stream()), "sp24_compress")
     return V, meta
