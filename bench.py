@@ -33,6 +33,7 @@ def parse():
     p.add_argument("--warmup", type=int, default=3)
     p.add_argument("--workload", default="ffn_bf16")
     p.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
+    p.add_argument("--b-pad", type=int, default=0, help="extra elements in B's leading dimension (experiment)")
     p.add_argument("--only", default="", help="comma list of ops to run in a step (profiling aid); default all")
     return p.parse_args()
 
@@ -89,6 +90,8 @@ def main():
     R = max(2, min(16, int(600e6 // per_set) + 1))
     As = [to_gpu(A, dt) for _ in range(R)]
     Bs = [to_gpu(Bt, dt) for _ in range(R)]
+    if args.b_pad:
+        Bs = [torch.cat([b, b[:, :args.b_pad]], dim=1)[:, :K] for b in Bs]
     P = torch.empty_like(As[0])
     P2 = torch.empty_like(As[0])
     D = torch.empty((M, N), dtype=out_dt, device="cuda")

@@ -147,12 +147,20 @@ TILED_CASES = [
     ("i8", "i32", 4096, 3300, 128),
     ("bf16", "f32", 3520, 4100, 64),
     ("f16", "f16", 4096, 3328, 128),
+    ("i8", "i32", 4096, 3328, 640),       # whole 256x256 tiles: pipelined kernel, 5 steps
+    ("bf16", "bf16", 3328, 4096, 448),    # 7 steps
+    ("f16", "f32", 4096, 3328, 64),       # a single step
 ]
 
 
 @pytest.mark.parametrize("case", TILED_CASES)
 def test_spmm_tiled_kernels_match_oracle(case):
     run_mm_case(*case, layout="tiled", b_order="k", sparse=True, seed=2)
+
+
+@pytest.mark.parametrize("case", TILED_CASES)
+def test_dense_tiled_kernels_match_oracle(case):
+    run_mm_case(*case, layout="canonical", b_order="k", sparse=False, seed=3)
 
 
 @pytest.mark.parametrize("case", MM_CASES)
