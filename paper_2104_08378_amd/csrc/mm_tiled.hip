@@ -1,28 +1,26 @@
 // Tiled, software-pipelined matrix-multiply kernels for large shapes.
 //
 // Sparse product (Sec. 3.2, Fig. 2) on the 32x32 sparse matrix-core
-// instructions, and the same-shape dense product on the dense ones.  One
-// workgroup of four wavefronts (2 x 2) computes a (64*TM) x (64*TN) tile of D;
-// each wavefront owns TM x TN accumulator tiles of 32x32 and, in the 4 x 4
-// configuration, the whole register file of its SIMD (256 accumulator
-// registers), so nothing but the instruction order hides latencies:
+// instructions, and the same-shape dense product on the dense ones.  A
+// workgroup of WM x WN wavefronts computes a (32*TM*WM) x (32*TN*WN) tile of D;
+// each wavefront owns TM x TN accumulator tiles of 32x32.  The large
+// configuration is 4 x 2 wavefronts of 64 x 128 each: a 256 x 256 tile, half of
+// the compute unit's register file in accumulators, two wavefronts per SIMD.
 //
 //   - a step consumes 128 bytes of every B row (128 int8 / 64 16-bit values of K);
-//   - B (and, in the dense kernel, A) travels global -> LDS without passing
-//     through registers (global_load_lds, 16 bytes per lane) into a ring of
-//     stages, several steps ahead of its use;
-//   - the compressed A operand of the sparse kernel (tiled layout) goes
-//     straight from global memory into registers, two steps ahead: one
-//     contiguous 1 KiB run of values and one 256-byte run of metadata words
-//     per 32-row tile (Sec. 3.1: no indirection, full-width reads);
+//   - every operand travels global -> LDS without passing through registers
+//     (global_load_lds) into a ring of stages, ahead of its use.  For the
+//     sparse kernel that is B plus the compressed A in its tiled layout, whose
+//     32-row tiles are contiguous 1 KiB runs of values and 256-byte runs of
+//     metadata words already in lane order (Sec. 3.1: no indirection,
+//     full-width reads), so a wavefront reads its A operands back with one
+//     conflict-free 16-byte and one 4-byte LDS read per lane;
 //   - one s_barrier per step and no fence: a wavefront awaits its own
-//     transfers with s_waitcnt vmcnt, the barrier then makes all four
-//     wavefronts' transfers visible;
+//     transfers with s_waitcnt vmcnt, the barrier then makes everybody's visible;
 //   - memory instructions are dealt out between the matrix-core instructions
-//     (sched_group_barrier), because with one wavefront per SIMD their issue
-//     time is otherwise not overlapped with arithmetic;
-//   - LDS rows are 128 bytes, unpadded (a transfer instruction fills 1 KiB =
-//     8 rows contiguously); the 16-byte piece c of row n sits at slot
+//     (sched_group_barrier) so that their issue time overlaps the arithmetic;
+//   - B rows in LDS are 128 bytes, unpadded (a transfer instruction fills
+//     1 KiB = 8 rows contiguously); the 16-byte piece c of row n sits at slot
 //     c ^ ((n >> 1) & 7), so that the fragment reads of 16 neighbouring rows
 //     hit 16 different 16-byte columns of the 256-byte-wide bank array;
 //   - workgroup ids are remapped so that the workgroups resident on one XCD
@@ -64,13 +62,13 @@ __device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int&
 }
 
 // Transfer ROWS rows x 128 bytes (row r of the stage = global row min(row0 + r, limit - 1)) into a stage.
-// Offsets of the NJ = ROWS/32 transfer instructions of this wavefront, relative to the first row.
-template <int ROWS>
-__device__ __forceinline__ void dma_offsets(int64_t row0, int64_t limit, int64_t ld_bytes, int wave, int lane, uint32_t (&off)[ROWS / 32])
+// Offsets of the ROWS/8/NW transfer instructions (8 rows each) of one of NW wavefronts, relative to the first row.
+template <int ROWS, int NW>
+__device__ __forceinline__ void dma_offsets(int64_t row0, int64_t limit, int64_t ld_bytes, int wave, int lane, uint32_t (&off)[ROWS / 8 / NW])
 {
 #pragma unroll
-    for (int j = 0; j < ROWS / 32; ++j) {
-        const int row = (wave * (ROWS / 32) + j) * 8 + (lane >> 3);
+    for (int j = 0; j < ROWS / 8 / NW; ++j) {
+        const int row = (wave * (ROWS / 8 / NW) + j) * 8 + (lane >> 3);
         int64_t g = row0 + row;
         if (g >= limit) g = limit - 1;                       // ragged edge: fetch a valid row, never stored
         const int piece = (lane & 7) ^ ((row >> 1) & 7);
@@ -78,60 +76,106 @@ __device__ __forceinline__ void dma_offsets(int64_t row0, int64_t limit, int64_t
     }
 }
 
-template <int ROWS>
-__device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&off)[ROWS / 32], uint8_t* stage, int wave)
+template <int ROWS, int NW>
+__device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&off)[ROWS / 8 / NW], uint8_t* stage, int wave)
 {
 #pragma unroll
-    for (int j = 0; j < ROWS / 32; ++j)
-        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint4v*>(base + off[j]), (lds_ptr)(stage + (wave * (ROWS / 32) + j) * 1024), 16, 0, 0);
+    for (int j = 0; j < ROWS / 8 / NW; ++j)
+        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint4v*>(base + off[j]), (lds_ptr)(stage + (wave * (ROWS / 8 / NW) + j) * 1024), 16, 0, 0);
+}
+
+// Issue order of one sparse step after its first operand reads, as a compile-time recursion (the sizes of
+// sched_group_barrier must be constants): matrix-core instruction M of NMFMA is preceded, at the start of a
+// fragment, by the two reads of the next fragment (and, in fragment 0, by the DSA1 reads of the second
+// instruction's A operands) and followed by its share of the NV transfers.
+template <int M, int NMFMA, int NV, int TM, int TN, int DSA1>
+__device__ __forceinline__ void sparse_issue_order()
+{
+    if constexpr (M < NMFMA) {
+        constexpr int t = M / TM, i = M % TM;
+        if constexpr (i == 0 && t + 1 < 2 * TN) __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
+        if constexpr (i == 0 && t == 0 && DSA1 > 0) __builtin_amdgcn_sched_group_barrier(kSgDsRead, DSA1, 0);
+        __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
+        constexpr int nv = (M + 1) * NV / NMFMA - M * NV / NMFMA;
+        if constexpr (nv > 0) __builtin_amdgcn_sched_group_barrier(kSgVmem, nv, 0);
+        sparse_issue_order<M + 1, NMFMA, NV, TM, TN, DSA1>();
+    }
 }
 
 // ---------------------------------------------------------------------------
-// Sparse kernel.
+// Sparse kernel.  Stage layout: [B: BN rows x 128 B, swizzled][V: 2 KiB per
+// 32-row block, in the tiled layout's own order][meta: 256 B per 32x64 tile].
+// Three stages; the transfers for step s+2 are issued during step s.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int TM, int TN>
-__global__ __launch_bounds__(256, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int tiles_n)
+template <int DT, int OUT, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr int ES = (DT == SP24_I8) ? 1 : 2;
     constexpr int BK = kRowBytes / ES;        // K elements per step
     constexpr int T64 = BK / 64;              // 32x64 A tiles per step and row block (2 for int8, 1 for 16-bit)
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int NJ = BN / 32;               // B transfer instructions per wavefront and step
-    constexpr int NA = TM * (2 + T64);        // A load instructions per wavefront and step
+    constexpr int NW = WM * WN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    constexpr int RB = BM / 32;               // row blocks per workgroup tile
+    constexpr int NJB = BN / 8 / NW;          // B transfers per wavefront and step (1 KiB each)
+    constexpr int NJV = RB * 2 / NW;          // V transfers (1 KiB each)
+    constexpr int NJM = RB * T64 / NW;        // metadata transfers (256 B each)
+    static_assert(RB * T64 % NW == 0 && BN % (8 * NW) == 0, "transfers must divide evenly over the wavefronts");
+    constexpr int NV = NJB + NJV + NJM;
     constexpr int NMFMA = 2 * TM * TN;
-    constexpr int kStageBytes = BN * kRowBytes;
+    constexpr int kVOff = BN * kRowBytes, kMOff = kVOff + RB * 2048;
+    constexpr int kStageBytes = kMOff + RB * T64 * 256;
     using acc_t = typename acc_of<DT>::type;
     __shared__ __attribute__((aligned(1024))) uint8_t st0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t st1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t st2[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t st3[kStageBytes];
 
     int tm, tn;
     tile_of_workgroup(tiles_m, tiles_n, tm, tn);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, q = lane >> 5;
     const int64_t KB64 = a.K / 64;
     const int nsteps = (int)(a.K / BK);
     const int64_t rb_total = a.M / 32;
 
-    // A operand (tiled layout): first tile of each of this wavefront's row blocks
-    const uint4v* __restrict__ Vp = reinterpret_cast<const uint4v*>(a.A);
-    const uint32_t* __restrict__ Mp = reinterpret_cast<const uint32_t*>(a.meta);
-    int64_t a_tile0[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        int64_t rb = (int64_t)tm * (BM / 32) + wm * TM + i;
-        if (rb >= rb_total) rb = rb_total - 1;               // ragged M: compute on a valid row block, never stored
-        a_tile0[i] = rb * KB64;
-    }
-
-    // B transfers
+    // ---- transfers of this wavefront ----
     const int64_t ldb_bytes = a.ldb * ES;
     const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
-    uint32_t b_off[NJ];
-    dma_offsets<BN>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+    uint32_t b_off[NJB];
+    dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+    // V: transfer x of this wavefront is 1 KiB number (wave*NJV + x) of the RB*2 of a step: row block /2, half %2
+    const uint8_t* v_src[NJV];
+#pragma unroll
+    for (int x = 0; x < NJV; ++x) {
+        const int id = wave * NJV + x;
+        int64_t rb = (int64_t)tm * RB + (id >> 1);
+        if (rb >= rb_total) rb = rb_total - 1;             // ragged M: compute on a valid row block, never stored
+        v_src[x] = reinterpret_cast<const uint8_t*>(a.A) + rb * KB64 * (1024 * ES) + (id & 1) * 1024 + lane * 16;
+    }
+    // metadata: transfer x is 256-byte tile number (wave*NJM + x) of the RB*T64 of a step
+    const uint8_t* m_src[NJM];
+#pragma unroll
+    for (int x = 0; x < NJM; ++x) {
+        const int id = wave * NJM + x;
+        int64_t rb = (int64_t)tm * RB + id / T64;
+        if (rb >= rb_total) rb = rb_total - 1;
+        m_src[x] = reinterpret_cast<const uint8_t*>(a.meta) + (rb * KB64 + id % T64) * 256 + lane * 4;
+    }
+
+    auto stage_ptr = [&](int u) -> uint8_t* { return u == 0 ? st0 : u == 1 ? st1 : st2; };
+    auto dma = [&](int step, int u) {
+        uint8_t* stg = stage_ptr(u);
+        dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stg, wave);
+#pragma unroll
+        for (int x = 0; x < NJV; ++x)
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint4v*>(v_src[x] + (int64_t)step * 2048),
+                                             (lds_ptr)(stg + kVOff + (wave * NJV + x) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int x = 0; x < NJM; ++x)
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(m_src[x] + (int64_t)step * (T64 * 256)),
+                                             (lds_ptr)(stg + kMOff + (wave * NJM + x) * 256), 4, 0, 0);
+    };
 
     acc_t acc[TM][TN];
 #pragma unroll
@@ -139,38 +183,27 @@ __global__ __launch_bounds__(256, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = acc_t{};
 
-    uint4v a_reg[4][TM][2];
-    uint32_t m_reg[4][TM][T64];
-
-    auto stage_ptr = [&](int u) -> uint8_t* { return u == 0 ? st0 : u == 1 ? st1 : u == 2 ? st2 : st3; };
-    auto load_a = [&](int step, int set) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if constexpr (DT == SP24_I8) {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int64_t tile = a_tile0[i] + (int64_t)step * 2 + j;
-                    a_reg[set][i][j] = (Vp + tile * 64)[lane];
-                    m_reg[set][i][j] = (Mp + tile * 64)[lane];
-                }
-            } else {
-                const int64_t tile = a_tile0[i] + step;
-#pragma unroll
-                for (int j = 0; j < 2; ++j) a_reg[set][i][j] = (Vp + (tile * 2 + j) * 64)[lane];
-                m_reg[set][i][0] = (Mp + tile * 64)[lane];
-            }
-        }
-    };
-    auto dma_b = [&](int step, int u) { dma_rows<BN>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u), wave); };
-
-    // fragment read offsets inside a stage: row (wn*32*TN + nj*32 + r), piece c at slot c ^ ((r >> 1) & 7);
-    // c = 2*c2 + q
+    // B fragment read offsets: row (wn*32*TN + nj*32 + r), piece c = 2*c2 + q at slot c ^ ((r >> 1) & 7)
     int frag_off[4];
 #pragma unroll
     for (int c2 = 0; c2 < 4; ++c2) frag_off[c2] = (wn * 32 * TN + r) * kRowBytes + ((((2 * c2) | q) ^ ((r >> 1) & 7)) << 4);
+    const int va_off = kVOff + wm * TM * 2048 + lane * 16;
+    const int ma_off = kMOff + wm * TM * T64 * 256 + lane * 4;
 
-    auto compute = [&](int u, int set) {
+    auto compute = [&](int u) {
         const uint8_t* base = stage_ptr(u);
+        int4v av[2][TM];
+        int mv[2][TM];
+        int8v f[2];
+        // operands of matrix-core instruction j of the step: values (row block i, half j), codes (int8: tile j;
+        // 16-bit: the one tile, the instruction picks its half through abid)
+        auto read_a = [&](int j, int4v (&xa)[TM], int (&xm)[TM]) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                xa[i] = *reinterpret_cast<const int4v*>(base + va_off + (i * 2 + j) * 1024);
+                if (DT == SP24_I8 || j == 0) xm[i] = *reinterpret_cast<const int*>(base + ma_off + (i * T64 + (DT == SP24_I8 ? j : 0)) * 256);
+            }
+        };
         auto read_frag = [&](int t, int8v& bv) {
             const int j = t / TN, nj = t % TN;
             // K-byte offset of the two pieces of instruction j: (int8) 64j + 32h + 16q, (16-bit) 64h + 32j + 16q
@@ -180,69 +213,53 @@ __global__ __launch_bounds__(256, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int
             bv[0] = lo[0]; bv[1] = lo[1]; bv[2] = lo[2]; bv[3] = lo[3];
             bv[4] = hi[0]; bv[5] = hi[1]; bv[6] = hi[2]; bv[7] = hi[3];
         };
-        int8v f[2];
+        read_a(0, av[0], mv[0]);
         read_frag(0, f[0]);
 #pragma unroll
         for (int t = 0; t < 2 * TN; ++t) {
-            // the next fragment is requested before, and awaited after, this fragment's TM instructions
-            if (t + 1 < 2 * TN) read_frag(t + 1, f[(t + 1) & 1]);
             const int j = t / TN, nj = t % TN;
+            // operands of what follows are requested before, and awaited after, this fragment's TM instructions
+            if (t + 1 < 2 * TN) read_frag(t + 1, f[(t + 1) & 1]);
+            if (t == 0) read_a(1, av[1], mv[DT == SP24_I8 ? 1 : 0]);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                int4v av = __builtin_bit_cast(int4v, a_reg[set][i][j]);
-                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av, f[t & 1], acc[i][nj], (int)m_reg[set][i][j]);
-                else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av, f[t & 1], acc[i][nj], (int)m_reg[set][i][0]);
-                else acc[i][nj] = smfmac32<DT, 1>(av, f[t & 1], acc[i][nj], (int)m_reg[set][i][0]);
+                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t & 1], acc[i][nj], mv[j][i]);
+                else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], f[t & 1], acc[i][nj], mv[0][i]);
+                else acc[i][nj] = smfmac32<DT, 1>(av[1][i], f[t & 1], acc[i][nj], mv[0][i]);
             }
         }
     };
 
-    // One step.  Transfers issued during step s: A(s+2) into the register set two ahead and B(s+3) into the
-    // stage three ahead.  vmcnt counts in order, so letting only the NA + NJ transfers of the previous step stay
-    // in flight on entry means that everything issued up to two steps ago -- A(s) and B(s) among it -- has landed.
-    constexpr int kWait = waitcnt_vm(NA + NJ);
-    constexpr int kVmemPerMfma = (NA + NJ + NMFMA - 1) / NMFMA;
-    auto do_step = [&](int step, int u, int as) {
+    // One step.  vmcnt counts in order: letting only the NV transfers issued during the previous step stay in
+    // flight on entry means that the ones issued two steps ago -- stage u -- have landed.
+    constexpr int kWait = waitcnt_vm(NV);
+    auto do_step = [&](int step, int u) {
         __builtin_amdgcn_s_waitcnt(kWait);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        // past the end the same addresses are fetched again into stages nobody reads: keeps the counts uniform
-        load_a(min(step + 2, nsteps - 1), (as + 2) & 3);
-        dma_b(min(step + 3, nsteps - 1), (u + 3) & 3);
-        compute(u, as);
-        // issue order of this region: two fragment reads, then TM x { matrix-core instruction, transfers }
-        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
-#pragma unroll
-        for (int t = 0; t < 2 * TN; ++t) {
-            if (t + 1 < 2 * TN) __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(kSgVmem, kVmemPerMfma, 0);
-            }
-        }
+        // past the end the last step is fetched again into a stage nobody reads: keeps the counts uniform
+        dma(min(step + 2, nsteps - 1), (u + 2) % 3);
+        compute(u);
+        // issue order of this region: operand reads, then per fragment TM x { matrix-core instruction, transfers }
+        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2 * TM + 2, 0);
+        sparse_issue_order<0, NMFMA, NV, TM, TN, TM + ((DT == SP24_I8) ? TM : 0)>();
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // prologue, in the steady-state order: B(0) A(0) B(1) A(1) B(2)
-    dma_b(0, 0);
-    load_a(0, 0);
-    dma_b(min(1, nsteps - 1), 1);
-    load_a(min(1, nsteps - 1), 1);
-    dma_b(min(2, nsteps - 1), 2);
+    // prologue: stages 0 and 1
+    dma(0, 0);
+    dma(min(1, nsteps - 1), 1);
     __builtin_amdgcn_sched_barrier(0);
-    // four steps per iteration in one basic block, so that stage and register-set indices are static and the
-    // compiler's wait-count bookkeeping stays exact; the remainder runs after the loop
+    // three steps per iteration in one basic block, so that stage indices are static and the compiler's
+    // wait-count bookkeeping stays exact; the remainder runs after the loop
     int step = 0;
-    for (; step + 4 <= nsteps; step += 4) {
-        do_step(step, 0, 0);
-        do_step(step + 1, 1, 1);
-        do_step(step + 2, 2, 2);
-        do_step(step + 3, 3, 3);
+    for (; step + 3 <= nsteps; step += 3) {
+        do_step(step, 0);
+        do_step(step + 1, 1);
+        do_step(step + 2, 2);
     }
-    if (step < nsteps) do_step(step, 0, 0);
-    if (step + 1 < nsteps) do_step(step + 1, 1, 1);
-    if (step + 2 < nsteps) do_step(step + 2, 2, 2);
+    if (step < nsteps) do_step(step, 0);
+    if (step + 1 < nsteps) do_step(step + 1, 1);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // drain the surplus transfers before the stages go away
 
 #pragma unroll
@@ -261,13 +278,14 @@ __global__ __launch_bounds__(256, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int
 // memory); two stages, transfers one step ahead -- a dense step holds twice
 // the arithmetic of a sparse one, which is what hides the latency here.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int TM, int TN>
-__global__ __launch_bounds__(256, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int tiles_n)
+template <int DT, int OUT, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr int ES = (DT == SP24_I8) ? 1 : 2;
     constexpr int BK = kRowBytes / ES;
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int NJA = BM / 32, NJB = BN / 32;
+    constexpr int NW = WM * WN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    constexpr int NJA = BM / 8 / NW, NJB = BN / 8 / NW;
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
     using acc_t = typename acc_of<DT>::type;
     __shared__ __attribute__((aligned(1024))) uint8_t st0[kStageBytes];
@@ -277,7 +295,7 @@ __global__ __launch_bounds__(256, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int
     tile_of_workgroup(tiles_m, tiles_n, tm, tn);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, q = lane >> 5;
     const int nsteps = (int)(a.K / BK);
 
@@ -285,8 +303,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int
     const uint8_t* a_blk = reinterpret_cast<const uint8_t*>(a.A) + (int64_t)tm * BM * lda_bytes;
     const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
     uint32_t a_off[NJA], b_off[NJB];
-    dma_offsets<BM>((int64_t)tm * BM, a.M, lda_bytes, wave, lane, a_off);
-    dma_offsets<BN>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+    dma_offsets<BM, NW>((int64_t)tm * BM, a.M, lda_bytes, wave, lane, a_off);
+    dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
 
     acc_t acc[TM][TN];
 #pragma unroll
@@ -296,8 +314,8 @@ __global__ __launch_bounds__(256, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int
 
     auto stage_ptr = [&](int u) -> uint8_t* { return u == 0 ? st0 : st1; };
     auto dma = [&](int step, int u) {
-        dma_rows<BM>(a_blk + (int64_t)step * kRowBytes, a_off, stage_ptr(u), wave);
-        dma_rows<BN>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u) + BM * kRowBytes, wave);
+        dma_rows<BM, NW>(a_blk + (int64_t)step * kRowBytes, a_off, stage_ptr(u), wave);
+        dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u) + BM * kRowBytes, wave);
     };
 
     // fragment of instruction jj (k-bytes 32*jj .. +31 of the step): lane reads piece 2*jj + q of its row
@@ -372,14 +390,14 @@ __global__ __launch_bounds__(256, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int
 // ---------------------------------------------------------------------------
 // Host side.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int TM, int TN>
+template <int DT, int OUT, int WM, int WN, int TM, int TN>
 static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-    if (a.sparse) k_spmm_pipe<DT, OUT, TM, TN><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
-    else k_gemm_pipe<DT, OUT, TM, TN><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WM * WN);
+    if (a.sparse) k_spmm_pipe<DT, OUT, WM, WN, TM, TN><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    else k_gemm_pipe<DT, OUT, WM, WN, TM, TN><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
     return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;
 }
 
@@ -388,8 +406,10 @@ static sp24_status pick_tile(const MmArgs& a, hipStream_t st)
 {
     // 256x256 tiles when they still fill the 256 compute units, else 128x128
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big >= 200) return run_pipe<DT, OUT, 4, 4>(a, st);
-    return run_pipe<DT, OUT, 2, 2>(a, st);
+    // eight wavefronts of 64x128 each (two per SIMD, so that one computes while the other waits); measured
+    // faster than four of 128x128 on the short-K transformer shape and equal on the long-K square one
+    if (big >= 200) return run_pipe<DT, OUT, 4, 2, 2, 4>(a, st);
+    return run_pipe<DT, OUT, 2, 2, 2, 2>(a, st);
 }
 
 sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
