@@ -13,7 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsp24.so")
-SOURCES = ["api.hip", "prune_compress.hip", "mm_simple.hip", "mm_tiled.hip"]
+SOURCES = ["api.hip", "prune_compress.hip", "mm_simple.hip", "mm_tiled.hip", "mm_skinny.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # hipcc must not form packed-fp32 instructions by itself on this target

@@ -143,6 +143,8 @@ static sp24_status mm_common(MmArgs& a, hipStream_t st)
     if (ranges_overlap(a.D, nd, a.B, nb) || ranges_overlap(a.D, nd, a.A, nA)) return SP24_ERR_SHAPE;
     if (a.sparse && ranges_overlap(a.D, nd, a.meta, sp24_meta_bytes(a.M, a.K, a.in, a.layout))) return SP24_ERR_SHAPE;
     bool handled = false;
+    s = launch_mm_skinny(a, st, &handled);
+    if (handled) return s;
     s = launch_mm_tiled(a, st, &handled);
     if (handled) return s;
     return launch_mm_simple(a, st);

@@ -28,6 +28,9 @@ struct MmArgs {
 // General kernel: any M, N; both layouts; both B orders.  One wavefront per 32x32 tile of D.
 sp24_status launch_mm_simple(const MmArgs& a, hipStream_t st);
 
+// Streaming kernel for N <= 32; returns false in *handled when the problem does not fit it.
+sp24_status launch_mm_skinny(const MmArgs& a, hipStream_t st, bool* handled);
+
 // Tiled kernels for large shapes; return false in *handled when the shape does not fit them.
 sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled);
 

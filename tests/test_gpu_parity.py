@@ -163,6 +163,20 @@ def test_dense_tiled_kernels_match_oracle(case):
     run_mm_case(*case, layout="canonical", b_order="k", sparse=False, seed=3)
 
 
+SKINNY_CASES = [
+    ("bf16", "bf16", 256, 16, 1024),
+    ("f16", "f32", 96, 7, 576),       # ragged N, K split unevenly over the wavefronts
+    ("i8", "i32", 128, 32, 2112),
+    ("bf16", "f32", 64, 1, 64),
+]
+
+
+@pytest.mark.parametrize("case", SKINNY_CASES)
+def test_skinny_kernels_match_oracle(case):
+    run_mm_case(*case, layout="tiled", b_order="k", sparse=True, seed=4)
+    run_mm_case(*case, layout="canonical", b_order="k", sparse=False, seed=5)
+
+
 @pytest.mark.parametrize("case", MM_CASES)
 def test_dense_gemm_matches_oracle(case):
     run_mm_case(*case, layout="canonical", b_order="k", sparse=False)
