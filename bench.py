@@ -7,10 +7,11 @@ dense product.  All inputs are resident in HBM before the timed region; every
 step works on the next of several rotating copies of the inputs so that the
 footprint of the loop exceeds the 256 MB last-level cache.
 
-Prints one JSON line:  metric = dense-equivalent TFLOP/s of the sparse product
-(2*M*N*K / its mean duration, measured with HIP events on the launch stream
-inside the timed region), plus the roofline of that kernel and the CPU oracle
-timed on a bounded sample of the same workload.
+Prints one JSON line.  `value` is the metric: dense-equivalent TFLOP/s of the
+sparse product, 2*M*N*K divided by its mean duration, measured with HIP events
+on the launch stream inside the timed region.  `ms_per_step` is the wall time of
+a whole step.  `roofline` describes the sparse product kernel, `cpu_baseline`
+the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -22,8 +23,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
-PEAK_DENSE = {"f16": 2.5e15, "bf16": 2.5e15, "i8": 5.0e15}   # MI355X published dense matrix-core peaks
+# MI355X published peaks: dense matrix cores per input type, and HBM3E
+PEAK_DENSE = {"f16": 2.5e15, "bf16": 2.5e15, "i8": 5.0e15}
 PEAK_HBM = 8.0e12
+
+# HBM bytes per launch of the sparse product kernel from rocprofv3 counter runs of this file
+# (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a 1 GiB device copy;
+# summaries under profiles/).  None where not measured.
+MEASURED_TRAFFIC = {
+    "ffn_bf16": (2.0 * 34985.9 + 65807.8) * 1024,      # profiles/ffn_bf16_path_rocprofv3.txt   (algorithmic: 88.6 MB)
+    "square_i8": (2.0 * 295212.6 + 262144.0) * 1024,   # profiles/square_i8_path_rocprofv3.txt  (algorithmic: 377.5 MB)
+    "skinny_bf16": (2.0 * 37917.1 + 256.0) * 1024,     # profiles/skinny_bf16_path_rocprofv3.txt (algorithmic: 76.0 MB)
+}
 
 
 def parse():
@@ -31,22 +42,23 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=3)
-    p.add_argument("--workload", default="ffn_bf16")
+    p.add_argument("--workload", default="ffn_bf16", help="tiny_f16 | ffn_bf16 | conv3x3_f16 | square_i8 | skinny_bf16")
     p.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
-    p.add_argument("--b-pad", type=int, default=0, help="extra elements in B's leading dimension (experiment)")
     p.add_argument("--only", default="", help="comma list of ops to run in a step (profiling aid); default all")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run one 1 GiB device copy, so that a counter profile of this run holds a kernel of known traffic")
     return p.parse_args()
 
 
 def cpu_baseline(name, A, Bt, budget_s):
-    """The oracle as it stands on a bounded sample: prune + compress + decompress + triple-loop
-    product on the first rows of A against the first columns of B."""
+    """The oracle as it stands, on a bounded sample: compress + decompress + triple-loop product of the first
+    rows of A with the first columns of B (all of K)."""
     import numpy as np
     import oracle
     from paper_2104_08378_amd import synth
     w = synth.WORKLOADS[name]
     dt, K = w["dtype"], w["K"]
-    rows, cols = 16, min(w["N"], 1024)
+    rows, cols = 32, min(w["N"], 1024)
     Bs = np.ascontiguousarray(Bt[:cols].T)
 
     def run(r):
@@ -58,13 +70,12 @@ def cpu_baseline(name, A, Bt, budget_s):
         return time.perf_counter() - t0
 
     t = run(rows)
-    # scale the row count so that the sample takes about the budget
-    rows = int(max(rows, min(w["M"], rows * budget_s / max(t, 1e-3))))
-    rows -= rows % 16
+    rows = int(max(rows, min(w["M"], rows * budget_s / max(t, 1e-3))))   # scale the sample to the budget
+    rows -= rows % 32
     t = run(rows)
-    flops = 2.0 * rows * cols * K
-    return {"value": flops / t / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"first {rows} rows of A x first {cols} columns of B, K={K}: compress + decompress + fp64/int32 triple loop, {t:.1f} s"}
+    return {"value": 2.0 * rows * cols * K / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {rows} rows of A x first {cols} columns of B, K={K}: compress + decompress + "
+                      f"{'int32' if dt == 'i8' else 'fp64'} triple loop, {t:.1f} s"}
 
 
 def main():
@@ -75,7 +86,7 @@ def main():
     import numpy as np
     import torch
     from paper_2104_08378_amd import sp24, synth
-    from util import OUT_DT, TORCH_DT, to_gpu
+    from util import OUT_DT, to_gpu
 
     name = args.workload
     w = synth.WORKLOADS[name]
@@ -85,13 +96,10 @@ def main():
     os_ = torch.empty((), dtype=out_dt).element_size()
     torch.cuda.set_device(0)
     A, Bt = synth.make(name)
-    # rotating input sets: footprint beyond the last-level cache
     per_set = A.nbytes + Bt.nbytes
-    R = max(2, min(16, int(600e6 // per_set) + 1))
+    R = max(2, min(16, int(600e6 // per_set) + 1))          # rotating input sets: footprint beyond the last-level cache
     As = [to_gpu(A, dt) for _ in range(R)]
     Bs = [to_gpu(Bt, dt) for _ in range(R)]
-    if args.b_pad:
-        Bs = [torch.cat([b, b[:, :args.b_pad]], dim=1)[:, :K] for b in Bs]
     P = torch.empty_like(As[0])
     P2 = torch.empty_like(As[0])
     D = torch.empty((M, N), dtype=out_dt, device="cuda")
@@ -136,24 +144,32 @@ def main():
         step(i, events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     ms = {o: float(np.mean([events[i][j].elapsed_time(events[i][j + 1]) for i in range(args.steps)])) for j, o in enumerate(ops)}
     ms_per_step = wall * 1e3 / args.steps
 
     flops_equiv = 2.0 * M * N * K
     t_sp, t_dn = ms["spmm"] * 1e-3, ms["dense"] * 1e-3
     value = flops_equiv / t_sp / 1e12 if "spmm" in only else 0.0
-    bytes_pc = M * K * es * (1 + 0.5) + M * K / 8            # fused prune+compress: read A, write V + meta
-    bytes_prune = 2.0 * M * K * es
+    bytes_pc = M * K * es * 1.5 + M * K / 8                  # fused prune+compress: read A, write V + meta
     bytes_spmm = M * K * es / 2 + M * K / 8 + K * N * es + M * N * os_
+    bytes_dense = M * K * es + K * N * es + M * N * os_
+    # the bound is whichever of the two algorithmic minima is longer at the published peaks
     compute_bound = (flops_equiv / 2 / PEAK_DENSE[dt]) >= (bytes_spmm / PEAK_HBM)
     if compute_bound:
         roof = {"bound": "mfma", "achieved": flops_equiv / 2 / t_sp / 1e12, "peak": PEAK_DENSE[dt] / 1e12, "unit": "TFLOP/s",
-                "kernel": "sparse product", "note": "algorithmic math = the kept half, M*N*K flops per launch, against the dense matrix-core peak"}
+                "kernel": "sparse product",
+                "note": "algorithmic math = the kept half of the products, M*N*K flops per launch, against the dense "
+                        "matrix-core peak (equivalently 2*M*N*K against the 2x sparse peak)"}
     else:
-        roof = {"bound": "hbm", "achieved": bytes_spmm / t_sp / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "kernel": "sparse product",
-                "note": "V + meta + B + D bytes per launch"}
+        roof = {"bound": "hbm", "achieved": bytes_spmm / t_sp / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                "kernel": "sparse product", "note": "algorithmic bytes = V + meta + B + D per launch"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC.get(name)
     line = {
         "metric": "2:4 SpGEMM dense-equiv TFLOP/s on 1 MI355X; speedup vs same-shape dense GEMM",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -164,7 +180,9 @@ def main():
         "step_ms": ms,
         "speedup_vs_dense": (t_dn / t_sp) if ("dense" in only and "spmm" in only) else None,
         "dense_tflops": flops_equiv / t_dn / 1e12 if "dense" in only else None,
-        "prune_GBps": bytes_prune / (ms["prune"] * 1e-3) / 1e9 if "prune" in only else None,
+        "spmm_GBps": bytes_spmm / t_sp / 1e9 if "spmm" in only else None,
+        "dense_GBps": bytes_dense / t_dn / 1e9 if "dense" in only else None,
+        "prune_GBps": 2.0 * M * K * es / (ms["prune"] * 1e-3) / 1e9 if "prune" in only else None,
         "compress_GBps": bytes_pc / (ms["compress"] * 1e-3) / 1e9 if "compress" in only else None,
         "decompress_GBps": bytes_pc / (ms["decompress"] * 1e-3) / 1e9 if "decompress" in only else None,
         "roofline": roof,
