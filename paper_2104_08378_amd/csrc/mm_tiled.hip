@@ -84,28 +84,29 @@ __device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&o
         __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint4v*>(base + off[j]), (lds_ptr)(stage + (wave * (ROWS / 8 / NW) + j) * 1024), 16, 0, 0);
 }
 
-// Issue order of one sparse step after its first operand reads, as a compile-time recursion (the sizes of
+// Issue order of the first part of a sparse step, as a compile-time recursion (the sizes of
 // sched_group_barrier must be constants): matrix-core instruction M of NMFMA is preceded, at the start of a
 // fragment, by the two reads of the next fragment (and, in fragment 0, by the DSA1 reads of the second
 // instruction's A operands) and followed by its share of the NV transfers.
-template <int M, int NMFMA, int NV, int TM, int TN, int DSA1>
+template <int M, int NMFMA, int NV, int TM, int DSA1>
 __device__ __forceinline__ void sparse_issue_order()
 {
     if constexpr (M < NMFMA) {
         constexpr int t = M / TM, i = M % TM;
-        if constexpr (i == 0 && t + 1 < 2 * TN) __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
+        if constexpr (i == 0) __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
         if constexpr (i == 0 && t == 0 && DSA1 > 0) __builtin_amdgcn_sched_group_barrier(kSgDsRead, DSA1, 0);
         __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
         constexpr int nv = (M + 1) * NV / NMFMA - M * NV / NMFMA;
         if constexpr (nv > 0) __builtin_amdgcn_sched_group_barrier(kSgVmem, nv, 0);
-        sparse_issue_order<M + 1, NMFMA, NV, TM, TN, DSA1>();
+        sparse_issue_order<M + 1, NMFMA, NV, TM, DSA1>();
     }
 }
 
 // ---------------------------------------------------------------------------
 // Sparse kernel.  Stage layout: [B: BN rows x 128 B, swizzled][V: 2 KiB per
 // 32-row block, in the tiled layout's own order][meta: 256 B per 32x64 tile].
-// Three stages; the transfers for step s+2 are issued during step s.
+// Three stages; the transfers for step s+2 are issued during step s, and the
+// first operands of step s+1 are read from LDS during the tail of step s.
 // ---------------------------------------------------------------------------
 template <int DT, int OUT, int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int tiles_n)
@@ -121,7 +122,6 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     constexpr int NJM = RB * T64 / NW;        // metadata transfers (256 B each)
     static_assert(RB * T64 % NW == 0 && BN % (8 * NW) == 0, "transfers must divide evenly over the wavefronts");
     constexpr int NV = NJB + NJV + NJM;
-    constexpr int NMFMA = 2 * TM * TN;
     constexpr int kVOff = BN * kRowBytes, kMOff = kVOff + RB * 2048;
     constexpr int kStageBytes = kMOff + RB * T64 * 256;
     using acc_t = typename acc_of<DT>::type;
@@ -190,65 +190,96 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     const int va_off = kVOff + wm * TM * 2048 + lane * 16;
     const int ma_off = kMOff + wm * TM * T64 * 256 + lane * 4;
 
-    auto compute = [&](int u) {
-        const uint8_t* base = stage_ptr(u);
+    // Operand reads from a stage.  A operands of matrix-core instruction j of the step: values (row block i,
+    // half j), codes (int8: tile j; 16-bit: the one tile, the instruction picks its half through abid).
+    auto read_a = [&](const uint8_t* base, int j, int4v (&xa)[TM], int (&xm)[TM], bool with_codes) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            xa[i] = *reinterpret_cast<const int4v*>(base + va_off + (i * 2 + j) * 1024);
+            if (with_codes) xm[i] = *reinterpret_cast<const int*>(base + ma_off + (i * T64 + (DT == SP24_I8 ? j : 0)) * 256);
+        }
+    };
+    auto read_frag = [&](const uint8_t* base, int t, int8v& bv) {
+        const int j = t / TN, nj = t % TN;
+        // K-byte offset of the two pieces of instruction j: (int8) 64j + 32h + 16q, (16-bit) 64h + 32j + 16q
+        const int c2lo = (DT == SP24_I8) ? 2 * j : j, c2hi = (DT == SP24_I8) ? 2 * j + 1 : 2 + j;
+        uint4v lo = *reinterpret_cast<const uint4v*>(base + frag_off[c2lo] + nj * 32 * kRowBytes);
+        uint4v hi = *reinterpret_cast<const uint4v*>(base + frag_off[c2hi] + nj * 32 * kRowBytes);
+        bv[0] = lo[0]; bv[1] = lo[1]; bv[2] = lo[2]; bv[3] = lo[3];
+        bv[4] = hi[0]; bv[5] = hi[1]; bv[6] = hi[2]; bv[7] = hi[3];
+    };
+
+    // Operands carried from the tail of one step into the next: A operands of instruction 0 and fragment 0.
+    int4v a_first[TM];
+    int m_first[TM];
+    int8v f_first;
+
+    // One step (stage u holds its operands; fragments t = 0 .. 2*TN-1, TM instructions each).
+    //   barrier 0: every wavefront has finished the previous step, so the stage it read is free:
+    //              the transfers for step s+2 go there, dealt out between the instructions of t < T1;
+    //   barrier 1 (before t = T1): this wavefront's transfers for step s+1 have landed (vmcnt counts in order:
+    //              only the NV just issued may still be in flight), the barrier makes everybody's visible;
+    //   t >= T1:   the first operands of step s+1 are read while the last instructions of step s run, so that
+    //              no wavefront starts a step waiting for LDS.
+    constexpr int NF = 2 * TN, T1 = NF - 2;
+    constexpr int kWait = waitcnt_vm(NV);
+    constexpr int kCodeReads = (DT == SP24_I8) ? TM : 0;    // LDS reads of the codes of instruction 1
+    auto do_step = [&](int step, int u) {
+        const uint8_t* cur = stage_ptr(u);
+        const uint8_t* nxt = stage_ptr((u + 1) % 3);
         int4v av[2][TM];
         int mv[2][TM];
         int8v f[2];
-        // operands of matrix-core instruction j of the step: values (row block i, half j), codes (int8: tile j;
-        // 16-bit: the one tile, the instruction picks its half through abid)
-        auto read_a = [&](int j, int4v (&xa)[TM], int (&xm)[TM]) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                xa[i] = *reinterpret_cast<const int4v*>(base + va_off + (i * 2 + j) * 1024);
-                if (DT == SP24_I8 || j == 0) xm[i] = *reinterpret_cast<const int*>(base + ma_off + (i * T64 + (DT == SP24_I8 ? j : 0)) * 256);
-            }
-        };
-        auto read_frag = [&](int t, int8v& bv) {
+        for (int i = 0; i < TM; ++i) { av[0][i] = a_first[i]; mv[0][i] = m_first[i]; }
+        f[0] = f_first;
+        auto mfmas = [&](int t) {
             const int j = t / TN, nj = t % TN;
-            // K-byte offset of the two pieces of instruction j: (int8) 64j + 32h + 16q, (16-bit) 64h + 32j + 16q
-            const int c2lo = (DT == SP24_I8) ? 2 * j : j, c2hi = (DT == SP24_I8) ? 2 * j + 1 : 2 + j;
-            uint4v lo = *reinterpret_cast<const uint4v*>(base + frag_off[c2lo] + nj * 32 * kRowBytes);
-            uint4v hi = *reinterpret_cast<const uint4v*>(base + frag_off[c2hi] + nj * 32 * kRowBytes);
-            bv[0] = lo[0]; bv[1] = lo[1]; bv[2] = lo[2]; bv[3] = lo[3];
-            bv[4] = hi[0]; bv[5] = hi[1]; bv[6] = hi[2]; bv[7] = hi[3];
-        };
-        read_a(0, av[0], mv[0]);
-        read_frag(0, f[0]);
-#pragma unroll
-        for (int t = 0; t < 2 * TN; ++t) {
-            const int j = t / TN, nj = t % TN;
-            // operands of what follows are requested before, and awaited after, this fragment's TM instructions
-            if (t + 1 < 2 * TN) read_frag(t + 1, f[(t + 1) & 1]);
-            if (t == 0) read_a(1, av[1], mv[DT == SP24_I8 ? 1 : 0]);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t & 1], acc[i][nj], mv[j][i]);
                 else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], f[t & 1], acc[i][nj], mv[0][i]);
                 else acc[i][nj] = smfmac32<DT, 1>(av[1][i], f[t & 1], acc[i][nj], mv[0][i]);
             }
-        }
-    };
-
-    // One step.  vmcnt counts in order: letting only the NV transfers issued during the previous step stay in
-    // flight on entry means that the ones issued two steps ago -- stage u -- have landed.
-    constexpr int kWait = waitcnt_vm(NV);
-    auto do_step = [&](int step, int u) {
-        __builtin_amdgcn_s_waitcnt(kWait);
+        };
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         // past the end the last step is fetched again into a stage nobody reads: keeps the counts uniform
         dma(min(step + 2, nsteps - 1), (u + 2) % 3);
-        compute(u);
-        // issue order of this region: operand reads, then per fragment TM x { matrix-core instruction, transfers }
-        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2 * TM + 2, 0);
-        sparse_issue_order<0, NMFMA, NV, TM, TN, TM + ((DT == SP24_I8) ? TM : 0)>();
+#pragma unroll
+        for (int t = 0; t < T1; ++t) {
+            read_frag(cur, t + 1, f[(t + 1) & 1]);
+            if (t == 0) read_a(cur, 1, av[1], mv[1], DT == SP24_I8);
+            mfmas(t);
+        }
+        sparse_issue_order<0, T1 * TM, NV, TM, TM + kCodeReads>();
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(kWait);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frag(cur, T1 + 1, f[(T1 + 1) & 1]);
+        read_a(nxt, 0, a_first, m_first, true);
+        mfmas(T1);
+        read_frag(nxt, 0, f_first);
+        mfmas(T1 + 1);
+        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2 * TM, 0);
+        __builtin_amdgcn_sched_group_barrier(kSgMfma, TM - 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(kSgMfma, TM, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // prologue: stages 0 and 1
+    // prologue: stages 0 and 1 on their way; first operands of step 0 once stage 0 has landed
     dma(0, 0);
     dma(min(1, nsteps - 1), 1);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWait);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    read_a(st0, 0, a_first, m_first, true);
+    read_frag(st0, 0, f_first);
     __builtin_amdgcn_sched_barrier(0);
     // three steps per iteration in one basic block, so that stage indices are static and the compiler's
     // wait-count bookkeeping stays exact; the remainder runs after the loop
