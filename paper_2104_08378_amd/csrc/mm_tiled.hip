@@ -15,7 +15,7 @@
 //     metadata words already in lane order (Sec. 3.1: no indirection,
 //     full-width reads), so a wavefront reads its A operands back with one
 //     conflict-free 16-byte and one 4-byte LDS read per lane;
-//   - one s_barrier per step and no fence: a wavefront awaits its own
+//   - two s_barriers per step and no fence: a wavefront awaits its own
 //     transfers with s_waitcnt vmcnt, the barrier then makes everybody's visible;
 //   - memory instructions are dealt out between the matrix-core instructions
 //     (sched_group_barrier) so that their issue time overlaps the arithmetic;

@@ -1,0 +1,52 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times (tiled
+layout, K-major B, the workload's output type): compress is compared bit for bit on the whole matrix, the
+sparse and dense products on sampled rows x columns that the oracle computes one by one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2104_08378_amd import sp24, synth
+from util import OUT_DT, out_to_f64, tiled_from_canonical, to_bits, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_err(got, ref, rms):
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-3 * rms + 1e-300)))
+
+
+@pytest.mark.parametrize("name", ["tiny_f16", "ffn_bf16", "conv3x3_f16", "square_i8", "skinny_bf16"])
+def test_full_size_workload(name):
+    w = synth.WORKLOADS[name]
+    dt, M, K, N = w["dtype"], w["M"], w["K"], w["N"]
+    A, Bt = synth.make(name)
+    Ad, Bd = to_gpu(A, dt), to_gpu(Bt, dt)
+    V, meta = sp24.sp24_compress(Ad, layout="tiled")
+    P = sp24.sp24_prune(Ad)
+    D = sp24.sp24_spmm(V, meta, Bd, OUT_DT[w["out"]], layout="tiled")
+    Dd = sp24.sp24_gemm_dense(P, Bd, OUT_DT[w["out"]])
+    torch.cuda.synchronize()
+
+    # compression of the whole matrix, bit for bit (through the documented permutation)
+    oV, ometa = oracle.compress(A, dt)
+    wantV, wantmeta = tiled_from_canonical(oV, ometa, dt)
+    assert np.array_equal(to_bits(V), wantV)
+    assert np.array_equal(to_bits(meta), wantmeta)
+    del wantV, wantmeta, oV, ometa
+
+    # sampled outputs: corners, tile edges and random picks
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 255, 256 % M, M - 1], rng.integers(0, M, 40)])) % M
+    cols = np.unique(np.concatenate([[0, 1, 31, 32 % N, 255 % N, 256 % N, N - 1], rng.integers(0, N, 56)])) % N
+    rows, cols = np.unique(rows), np.unique(cols)
+    Prows = oracle.prune(np.ascontiguousarray(A[rows]), dt)
+    assert np.array_equal(to_bits(P)[rows], Prows)
+    ref = oracle.gemm(Prows, np.ascontiguousarray(Bt[cols].T), dt)
+    for got_t in (D, Dd):
+        got = got_t[torch.as_tensor(rows, device="cuda")][:, torch.as_tensor(cols, device="cuda")]
+        if dt == "i8":
+            assert np.array_equal(got.cpu().numpy(), ref), name
+        else:
+            rms = float(np.sqrt(np.mean(ref * ref)))
+            assert rel_err(out_to_f64(got), ref, rms) <= 1e-2, name
