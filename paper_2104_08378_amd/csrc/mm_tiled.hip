@@ -76,29 +76,79 @@ __device__ __forceinline__ void dma_offsets(int64_t row0, int64_t limit, int64_t
     }
 }
 
+// One global -> LDS transfer instruction: lane l moves 16 (or 4) bytes from base + off to lds + 16*l (4*l).
+// `base` and `lds` must be wavefront-uniform.  Written as inline assembly on purpose: with the compiler's own
+// builtin in a loop, its wait-count pass treats the LDS counter as out of order and turns every wait for an
+// LDS read into lgkmcnt(0), which serialises the operand reads with the arithmetic.  The price is that the
+// compiler does not count these transfers in vmcnt: every wait for them below is written by hand.
+__device__ __forceinline__ void lds_dma16(const uint8_t* base, uint32_t off, const uint8_t* lds)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(l) : "m0");
+}
+__device__ __forceinline__ void lds_dma4(const uint8_t* base, uint32_t off, const uint8_t* lds)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(l) : "m0");
+}
+
 template <int ROWS, int NW>
 __device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&off)[ROWS / 8 / NW], uint8_t* stage, int wave)
 {
 #pragma unroll
-    for (int j = 0; j < ROWS / 8 / NW; ++j)
-        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint4v*>(base + off[j]), (lds_ptr)(stage + (wave * (ROWS / 8 / NW) + j) * 1024), 16, 0, 0);
+    for (int j = 0; j < ROWS / 8 / NW; ++j) lds_dma16(base, off[j], stage + (wave * (ROWS / 8 / NW) + j) * 1024);
 }
 
-// Issue order of the first part of a sparse step, as a compile-time recursion (the sizes of
-// sched_group_barrier must be constants): matrix-core instruction M of NMFMA is preceded, at the start of a
-// fragment, by the two reads of the next fragment (and, in fragment 0, by the DSA1 reads of the second
-// instruction's A operands) and followed by its share of the NV transfers.
-template <int M, int NMFMA, int NV, int TM, int DSA1>
-__device__ __forceinline__ void sparse_issue_order()
+// Epilogue of the tiled kernels.  A wavefront's accumulators hold, per 32x32 tile, 32 consecutive columns of
+// one row per register -- 64- or 128-byte pieces when stored directly.  Instead each 32-row block of the
+// wavefront's tile is written to LDS as a row-major image in the output type and read back 16 bytes per lane,
+// so that a store instruction covers whole rows of the wavefront's tile (256 or 512 contiguous bytes each).
+// `scratch` is this wavefront's own 32 x kPitch bytes; the direct path serves outputs that are not 16-byte tileable.
+template <int OUT, int TN>
+struct epilogue_geometry {
+    static constexpr int kOsz = (OUT == SP24_F32 || OUT == SP24_I32) ? 4 : 2;
+    static constexpr int kRowBytesOut = 32 * TN * kOsz;
+    static constexpr int kPitch = kRowBytesOut + (kOsz == 4 ? 32 : 16);   // 4 rows apart = half a bank row apart
+    static constexpr int kWaveBytes = 32 * kPitch;
+};
+
+template <int DT, int OUT, int TM, int TN>
+__device__ __forceinline__ void store_wave_tile(const MmArgs& a, typename acc_of<DT>::type (&acc)[TM][TN], uint8_t* scratch,
+                                                int64_t row_base, int64_t col_base, int lane)
 {
-    if constexpr (M < NMFMA) {
-        constexpr int t = M / TM, i = M % TM;
-        if constexpr (i == 0) __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
-        if constexpr (i == 0 && t == 0 && DSA1 > 0) __builtin_amdgcn_sched_group_barrier(kSgDsRead, DSA1, 0);
-        __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
-        constexpr int nv = (M + 1) * NV / NMFMA - M * NV / NMFMA;
-        if constexpr (nv > 0) __builtin_amdgcn_sched_group_barrier(kSgVmem, nv, 0);
-        sparse_issue_order<M + 1, NMFMA, NV, TM, DSA1>();
+    using G = epilogue_geometry<OUT, TN>;
+    constexpr int kOsz = G::kOsz, kPitch = G::kPitch;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(a.D) & 15u) == 0 && (a.ldd * kOsz) % 16 == 0 && a.N % (16 / kOsz) == 0;
+    if (!vec_ok) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) store_tile<DT, OUT>(a.D, a.ldd, row_base + i * 32, col_base + j * 32, a.M, a.N, acc[i][j], lane);
+        return;
+    }
+    const int r = lane & 31, q = lane >> 5;
+    constexpr int kChunksPerRow = G::kRowBytesOut / 16;
+    uint8_t* Dp = reinterpret_cast<uint8_t*>(a.D);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                uint8_t* p = scratch + (8 * (e / 4) + 4 * q + (e % 4)) * kPitch + (j * 32 + r) * kOsz;
+                if constexpr (DT == SP24_I8) *reinterpret_cast<int32_t*>(p) = acc[i][j][e];
+                else if constexpr (OUT == SP24_F32) *reinterpret_cast<float*>(p) = acc[i][j][e];
+                else if constexpr (OUT == SP24_F16) *reinterpret_cast<uint16_t*>(p) = f32_to_f16_bits(acc[i][j][e]);
+                else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16_bits(acc[i][j][e]);
+            }
+#pragma unroll
+        for (int it = 0; it < 32 * kChunksPerRow / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int row = idx / kChunksPerRow, c = idx % kChunksPerRow;
+            const uint4v v = *reinterpret_cast<const uint4v*>(scratch + row * kPitch + c * 16);
+            const int64_t grow = row_base + i * 32 + row, gcol = col_base + c * (16 / kOsz);
+            if (grow < a.M && gcol < a.N) *reinterpret_cast<uint4v*>(Dp + (grow * a.ldd + gcol) * kOsz) = v;
+        }
     }
 }
 
@@ -125,9 +175,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     constexpr int kVOff = BN * kRowBytes, kMOff = kVOff + RB * 2048;
     constexpr int kStageBytes = kMOff + RB * T64 * 256;
     using acc_t = typename acc_of<DT>::type;
-    __shared__ __attribute__((aligned(1024))) uint8_t st0[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t st1[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t st2[kStageBytes];
+    constexpr int kEpiBytes = NW * epilogue_geometry<OUT, TN>::kWaveBytes;
+    constexpr int kLdsBytes = 3 * kStageBytes > kEpiBytes ? 3 * kStageBytes : kEpiBytes;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_all[kLdsBytes];
 
     int tm, tn;
     tile_of_workgroup(tiles_m, tiles_n, tm, tn);
@@ -145,36 +195,36 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     uint32_t b_off[NJB];
     dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
     // V: transfer x of this wavefront is 1 KiB number (wave*NJV + x) of the RB*2 of a step: row block /2, half %2
-    const uint8_t* v_src[NJV];
+    const uint8_t* v_base[NJV];                            // wavefront-uniform; lane l adds 16*l
 #pragma unroll
     for (int x = 0; x < NJV; ++x) {
         const int id = wave * NJV + x;
         int64_t rb = (int64_t)tm * RB + (id >> 1);
         if (rb >= rb_total) rb = rb_total - 1;             // ragged M: compute on a valid row block, never stored
-        v_src[x] = reinterpret_cast<const uint8_t*>(a.A) + rb * KB64 * (1024 * ES) + (id & 1) * 1024 + lane * 16;
+        v_base[x] = reinterpret_cast<const uint8_t*>(a.A) + rb * KB64 * (1024 * ES) + (id & 1) * 1024;
     }
     // metadata: transfer x is 256-byte tile number (wave*NJM + x) of the RB*T64 of a step
-    const uint8_t* m_src[NJM];
+    const uint8_t* m_base[NJM];                            // wavefront-uniform; lane l adds 4*l
 #pragma unroll
     for (int x = 0; x < NJM; ++x) {
         const int id = wave * NJM + x;
         int64_t rb = (int64_t)tm * RB + id / T64;
         if (rb >= rb_total) rb = rb_total - 1;
-        m_src[x] = reinterpret_cast<const uint8_t*>(a.meta) + (rb * KB64 + id % T64) * 256 + lane * 4;
+        m_base[x] = reinterpret_cast<const uint8_t*>(a.meta) + (rb * KB64 + id % T64) * 256;
     }
+    const uint32_t lane16 = lane * 16, lane4 = lane * 4;
 
-    auto stage_ptr = [&](int u) -> uint8_t* { return u == 0 ? st0 : u == 1 ? st1 : st2; };
-    auto dma = [&](int step, int u) {
+    auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
+    // transfer number x (0 .. NV-1) of this wavefront for a step: B rows, then values, then codes
+    auto dma_one = [&](int step, int u, int x) {
         uint8_t* stg = stage_ptr(u);
-        dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stg, wave);
+        if (x < NJB) lds_dma16(b_blk + (int64_t)step * kRowBytes, b_off[x], stg + (wave * NJB + x) * 1024);
+        else if (x < NJB + NJV) lds_dma16(v_base[x - NJB] + (int64_t)step * 2048, lane16, stg + kVOff + (wave * NJV + x - NJB) * 1024);
+        else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * (T64 * 256), lane4, stg + kMOff + (wave * NJM + x - NJB - NJV) * 256);
+    };
+    auto dma = [&](int step, int u) {
 #pragma unroll
-        for (int x = 0; x < NJV; ++x)
-            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint4v*>(v_src[x] + (int64_t)step * 2048),
-                                             (lds_ptr)(stg + kVOff + (wave * NJV + x) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int x = 0; x < NJM; ++x)
-            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(m_src[x] + (int64_t)step * (T64 * 256)),
-                                             (lds_ptr)(stg + kMOff + (wave * NJM + x) * 256), 4, 0, 0);
+        for (int x = 0; x < NV; ++x) dma_one(step, u, x);
     };
 
     acc_t acc[TM][TN];
@@ -209,12 +259,13 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
         bv[4] = hi[0]; bv[5] = hi[1]; bv[6] = hi[2]; bv[7] = hi[3];
     };
 
-    // Operands carried from the tail of one step into the next: A operands of instruction 0 and fragment 0.
+    // Operands carried from the tail of one step into the next: A operands of instruction 0, fragments 0 and 1.
     int4v a_first[TM];
     int m_first[TM];
-    int8v f_first;
+    int8v f_first[2];
 
-    // One step (stage u holds its operands; fragments t = 0 .. 2*TN-1, TM instructions each).
+    // One step (stage u holds its operands; fragments t = 0 .. NF-1, TM instructions each).  LDS reads run two
+    // fragments ahead of the arithmetic.
     //   barrier 0: every wavefront has finished the previous step, so the stage it read is free:
     //              the transfers for step s+2 go there, dealt out between the instructions of t < T1;
     //   barrier 1 (before t = T1): this wavefront's transfers for step s+1 have landed (vmcnt counts in order:
@@ -223,51 +274,45 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     //              no wavefront starts a step waiting for LDS.
     constexpr int NF = 2 * TN, T1 = NF - 2;
     constexpr int kWait = waitcnt_vm(NV);
-    constexpr int kCodeReads = (DT == SP24_I8) ? TM : 0;    // LDS reads of the codes of instruction 1
     auto do_step = [&](int step, int u) {
         const uint8_t* cur = stage_ptr(u);
         const uint8_t* nxt = stage_ptr((u + 1) % 3);
+        const int fetch = min(step + 2, nsteps - 1);   // past the end the last step is fetched again into a stage
+                                                       // nobody reads: keeps the counts uniform
         int4v av[2][TM];
         int mv[2][TM];
-        int8v f[2];
+        int8v f[3];
 #pragma unroll
         for (int i = 0; i < TM; ++i) { av[0][i] = a_first[i]; mv[0][i] = m_first[i]; }
-        f[0] = f_first;
-        auto mfmas = [&](int t) {
+        f[0] = f_first[0];
+        f[1] = f_first[1];
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NF; ++t) {
             const int j = t / TN, nj = t % TN;
+            if (t == T1) {
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(kWait);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (t + 2 < NF) read_frag(cur, t + 2, f[(t + 2) % 3]);
+            else read_frag(nxt, t + 2 - NF, f_first[t + 2 - NF]);
+            if (t == 0) read_a(cur, 1, av[1], mv[1], DT == SP24_I8);
+            if (t == T1) read_a(nxt, 0, a_first, m_first, true);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t & 1], acc[i][nj], mv[j][i]);
-                else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], f[t & 1], acc[i][nj], mv[0][i]);
-                else acc[i][nj] = smfmac32<DT, 1>(av[1][i], f[t & 1], acc[i][nj], mv[0][i]);
-            }
-        };
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        // past the end the last step is fetched again into a stage nobody reads: keeps the counts uniform
-        dma(min(step + 2, nsteps - 1), (u + 2) % 3);
+                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t % 3], acc[i][nj], mv[j][i]);
+                else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], f[t % 3], acc[i][nj], mv[0][i]);
+                else acc[i][nj] = smfmac32<DT, 1>(av[1][i], f[t % 3], acc[i][nj], mv[0][i]);
+                if (t < T1) {
+                    const int m = t * TM + i;
 #pragma unroll
-        for (int t = 0; t < T1; ++t) {
-            read_frag(cur, t + 1, f[(t + 1) & 1]);
-            if (t == 0) read_a(cur, 1, av[1], mv[1], DT == SP24_I8);
-            mfmas(t);
+                    for (int x = m * NV / (T1 * TM); x < (m + 1) * NV / (T1 * TM); ++x) dma_one(fetch, (u + 2) % 3, x);
+                }
+            }
         }
-        sparse_issue_order<0, T1 * TM, NV, TM, TM + kCodeReads>();
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(kWait);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frag(cur, T1 + 1, f[(T1 + 1) & 1]);
-        read_a(nxt, 0, a_first, m_first, true);
-        mfmas(T1);
-        read_frag(nxt, 0, f_first);
-        mfmas(T1 + 1);
-        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2 * TM, 0);
-        __builtin_amdgcn_sched_group_barrier(kSgMfma, TM - 1, 0);
-        __builtin_amdgcn_sched_group_barrier(kSgDsRead, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(kSgMfma, TM, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
 
@@ -278,8 +323,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     __builtin_amdgcn_s_waitcnt(kWait);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    read_a(st0, 0, a_first, m_first, true);
-    read_frag(st0, 0, f_first);
+    read_a(lds_all, 0, a_first, m_first, true);
+    read_frag(lds_all, 0, f_first[0]);
+    read_frag(lds_all, 1, f_first[1]);
     __builtin_amdgcn_sched_barrier(0);
     // three steps per iteration in one basic block, so that stage indices are static and the compiler's
     // wait-count bookkeeping stays exact; the remainder runs after the loop
@@ -291,16 +337,12 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     }
     if (step < nsteps) do_step(step, 0);
     if (step + 1 < nsteps) do_step(step + 1, 1);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // drain the surplus transfers before the stages go away
-
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int64_t row0 = (int64_t)tm * BM + (wm * TM + i) * 32;
-            int64_t col0 = (int64_t)tn * BN + (wn * TN + j) * 32;
-            store_tile<DT, OUT>(a.D, a.ldd, row0, col0, a.M, a.N, acc[i][j], lane);
-        }
+    // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    store_wave_tile<DT, OUT, TM, TN>(a, acc, lds_all + wave * epilogue_geometry<OUT, TN>::kWaveBytes,
+                                     (int64_t)tm * BM + wm * TM * 32, (int64_t)tn * BN + wn * TN * 32, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -319,8 +361,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
     constexpr int NJA = BM / 8 / NW, NJB = BN / 8 / NW;
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
     using acc_t = typename acc_of<DT>::type;
-    __shared__ __attribute__((aligned(1024))) uint8_t st0[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t st1[kStageBytes];
+    constexpr int kEpiBytes = NW * epilogue_geometry<OUT, TN>::kWaveBytes;
+    constexpr int kLdsBytes = 2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_all[kLdsBytes];
 
     int tm, tn;
     tile_of_workgroup(tiles_m, tiles_n, tm, tn);
@@ -343,7 +386,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = acc_t{};
 
-    auto stage_ptr = [&](int u) -> uint8_t* { return u == 0 ? st0 : st1; };
+    auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
     auto dma = [&](int step, int u) {
         dma_rows<BM, NW>(a_blk + (int64_t)step * kRowBytes, a_off, stage_ptr(u), wave);
         dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u) + BM * kRowBytes, wave);
@@ -406,16 +449,12 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
         do_step(step + 1, 1);
     }
     if (step < nsteps) do_step(step, 0);
+    // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int64_t row0 = (int64_t)tm * BM + (wm * TM + i) * 32;
-            int64_t col0 = (int64_t)tn * BN + (wn * TN + j) * 32;
-            store_tile<DT, OUT>(a.D, a.ldd, row0, col0, a.M, a.N, acc[i][j], lane);
-        }
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    store_wave_tile<DT, OUT, TM, TN>(a, acc, lds_all + wave * epilogue_geometry<OUT, TN>::kWaveBytes,
+                                     (int64_t)tm * BM + wm * TM * 32, (int64_t)tn * BN + wn * TN * 32, lane);
 }
 
 // ---------------------------------------------------------------------------
