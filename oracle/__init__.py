@@ -43,6 +43,8 @@ def _load():
         lib.sp24o_decompress.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_gemm_f64.argtypes = [vp, vp, vp, i64, i64, i64, i32]
         lib.sp24o_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64]
+        lib.sp24o_conv2d_f64.argtypes = [vp, vp, vp] + [i64] * 11 + [i32]
+        lib.sp24o_conv2d_i32.argtypes = [vp, vp, vp] + [i64] * 11
         lib.sp24o_f16_to_double.argtypes = [ctypes.c_uint16]
         lib.sp24o_f16_to_double.restype = ctypes.c_double
         lib.sp24o_bf16_to_double.argtypes = [ctypes.c_uint16]
@@ -122,6 +124,32 @@ def gemm(P, B, dtype):
     else:
         D = np.empty((M, N), dtype=np.float64)
         lib.sp24o_gemm_f64(_ptr(P), _ptr(B), _ptr(D), M, N, K, _TYPES[dtype])
+    return D
+
+
+def conv2d(P, X, dtype, R, S, pad=(0, 0), stride=(1, 1)):
+    """Convolution of the NHWC input X [n_img,H,W,C] with the filter bank P [M, R*S*C] (column
+    k = (r*S + s)*C + c; Sec. 4.2: inner dimension C x R x S), written out directly with zero padding.
+    Returns [M, n_img*OH*OW]: float64 for f16/bf16, int32 for i8."""
+    _check(P, dtype)
+    if X.ndim != 4 or not X.flags.c_contiguous or X.dtype != P.dtype:
+        raise ValueError("X must be a C-contiguous [n_img,H,W,C] array of the filter's storage type")
+    n_img, H, W, C = X.shape
+    M, K = P.shape
+    if K != R * S * C:
+        raise ValueError("filter columns must number R*S*C")
+    (ph, pw), (sh, sw) = pad, stride
+    OH, OW = (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1
+    lib = _load()
+    geom = (M, n_img, H, W, C, R, S, ph, pw, sh, sw)
+    if dtype == "i8":
+        D = np.empty((M, n_img * OH * OW), dtype=np.int32)
+        rc = lib.sp24o_conv2d_i32(_ptr(P), _ptr(X), _ptr(D), *geom)
+    else:
+        D = np.empty((M, n_img * OH * OW), dtype=np.float64)
+        rc = lib.sp24o_conv2d_f64(_ptr(P), _ptr(X), _ptr(D), *geom, _TYPES[dtype])
+    if rc:
+        raise ValueError("oracle conv2d: illegal geometry")
     return D
 
 

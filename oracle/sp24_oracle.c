@@ -249,6 +249,65 @@ int sp24o_gemm_i32(const int8_t *P, const int8_t *B, int32_t *D,
     return 0;
 }
 
+/*
+ * ---- O5: convolution with the pruned filter bank, by definition ----------
+ * The paper treats a convolution as a GEMM-like operation whose first
+ * argument is the sparse tensor (Sec. 3.2) with inner dimension C x R x S
+ * (Sec. 4.2); the group of four runs over consecutive input channels of one
+ * filter tap, k = (r*S + s)*C + c.  Written out directly on the NHWC input
+ * X[n_img][H][W][C], no matrix is formed:
+ *   D[m][(img*OH + oy)*OW + ox] =
+ *       sum_{r,s,c} P[m][(r*S + s)*C + c] * X[img][oy*sh - ph + r][ox*sw - pw + s][c]
+ * where taps that fall outside the image contribute nothing (zero padding),
+ * OH = (H + 2*ph - R)/sh + 1, OW = (W + 2*pw - S)/sw + 1.  D is M x N
+ * row-major with N = n_img*OH*OW.  Same arithmetic as O4.
+ */
+#define CONV_LOOP(ACC_T, LOAD_P, LOAD_X)                                                     \
+    long OH = (H + 2 * ph - R) / sh + 1, OW = (W + 2 * pw - S) / sw + 1;                     \
+    long N = n_img * OH * OW, K = R * S * C;                                                 \
+    if (H + 2 * ph < R || W + 2 * pw < S || sh < 1 || sw < 1)                                \
+        return 1;                                                                            \
+    _Pragma("omp parallel for schedule(static)")                                            \
+    for (long m = 0; m < M; ++m)                                                             \
+        for (long img = 0; img < n_img; ++img)                                               \
+            for (long oy = 0; oy < OH; ++oy)                                                 \
+                for (long ox = 0; ox < OW; ++ox) {                                           \
+                    ACC_T acc = 0;                                                           \
+                    for (long r = 0; r < R; ++r)                                             \
+                        for (long s = 0; s < S; ++s) {                                       \
+                            long iy = oy * sh - ph + r, ix = ox * sw - pw + s;               \
+                            if (iy < 0 || iy >= H || ix < 0 || ix >= W)                      \
+                                continue;                                                    \
+                            for (long c = 0; c < C; ++c)                                     \
+                                acc += LOAD_P(m * K + (r * S + s) * C + c) *                 \
+                                       LOAD_X(((img * H + iy) * W + ix) * C + c);            \
+                        }                                                                    \
+                    D[m * N + (img * OH + oy) * OW + ox] = acc;                              \
+                }                                                                            \
+    return 0;
+
+int sp24o_conv2d_f64(const uint16_t *P, const uint16_t *X, double *D, long M, long n_img,
+                     long H, long W, long C, long R, long S, long ph, long pw, long sh, long sw, int t)
+{
+    if (t != T_F16 && t != T_BF16)
+        return 1;
+#define LP(i) elem_to_double(P, (i), t)
+#define LX(i) elem_to_double(X, (i), t)
+    CONV_LOOP(double, LP, LX)
+#undef LP
+#undef LX
+}
+
+int sp24o_conv2d_i32(const int8_t *P, const int8_t *X, int32_t *D, long M, long n_img,
+                     long H, long W, long C, long R, long S, long ph, long pw, long sh, long sw)
+{
+#define LP(i) (int32_t) P[(i)]
+#define LX(i) (int32_t) X[(i)]
+    CONV_LOOP(int32_t, LP, LX)
+#undef LP
+#undef LX
+}
+
 int sp24o_threads(void)
 {
 #ifdef _OPENMP

@@ -67,6 +67,13 @@ def im2col_nhwc(x, R=3, S=3, pad=1):
     return cols.reshape(b * H * W, R * S * C)
 
 
+def conv_activations(seed=0, n_img=64, C=256):
+    """NHWC activations of the conv3x3_f16 workload, [n_img, 14, 14, C] fp16 bits: ReLU of a standard
+    normal draw (about half exact zeros)."""
+    cid = WORKLOADS["conv3x3_f16"]["id"]
+    return f64_to_f16_bits(np.maximum(_rng(seed, cid, 1).standard_normal((n_img, 14, 14, C)), 0.0))
+
+
 def make(name, seed=0, M=None, N=None, K=None):
     """Return (A [M,K], Bt [N,K]) for a named workload; Bt is the second operand
     stored K-contiguous (one row per token / output pixel).  M, N, K may be
@@ -87,8 +94,7 @@ def make(name, seed=0, M=None, N=None, K=None):
         if C * 9 != K or N % 196:
             raise ValueError("conv workload needs K = 9*C and N = batch*14*14")
         A = normal_bits((M, K), 0.05, dt, seed, cid, 0)
-        act = np.maximum(_rng(seed, cid, 1).standard_normal((N // 196, 14, 14, C)), 0.0)
-        Bt = im2col_nhwc(f64_to_f16_bits(act))
+        Bt = im2col_nhwc(conv_activations(seed, N // 196, C))
     elif name == "square_i8":
         A = int8_uniform((M, K), seed, cid, 0)
         Bt = int8_uniform((N, K), seed, cid, 1)

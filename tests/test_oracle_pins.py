@@ -371,3 +371,97 @@ def test_im2col_matches_a_direct_convolution():
             patch = xp[:, oy:oy + 3, ox:ox + 3, :]
             want[:, oy, ox, :] = np.einsum("brsc,orsc->bo", patch, w)
     assert np.array_equal(got.reshape(2, 14, 14, 5), want)
+
+
+# ---- direct convolution (the implicit-GEMM path's oracle) --------------------------------------------------
+
+def _im2col_general(x, R, S, pad, stride):
+    """[n_img,H,W,C] -> [n_img*OH*OW, R*S*C] with k = (r*S + s)*C + c, by padding and slicing."""
+    n, H, W, C = x.shape
+    (ph, pw), (sh, sw) = pad, stride
+    OH, OW = (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1
+    xp = np.pad(x, ((0, 0), (ph, ph), (pw, pw), (0, 0)))
+    cols = np.empty((n, OH, OW, R * S, C), dtype=x.dtype)
+    for r in range(R):
+        for s in range(S):
+            cols[:, :, :, r * S + s, :] = xp[:, r:r + (OH - 1) * sh + 1:sh, s:s + (OW - 1) * sw + 1:sw, :]
+    return cols.reshape(n * OH * OW, R * S * C)
+
+
+CONV_GEOMS = [
+    # n_img, H, W, C, M, R, S, pad, stride
+    (2, 6, 5, 8, 3, 3, 3, (1, 1), (1, 1)),
+    (1, 7, 9, 4, 5, 1, 1, (0, 0), (1, 1)),
+    (2, 8, 7, 8, 4, 3, 2, (0, 1), (2, 1)),
+    (1, 9, 9, 4, 2, 5, 5, (2, 2), (2, 2)),
+    (3, 4, 4, 8, 2, 2, 3, (1, 0), (1, 2)),
+]
+
+
+@pytest.mark.parametrize("geom", CONV_GEOMS)
+def test_conv2d_int8_equals_integer_im2col_product_and_torch(geom):
+    n, H, W, C, M, R, S, pad, stride = geom
+    rng = np.random.default_rng(11)
+    x = rng.integers(-128, 128, size=(n, H, W, C)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(M, R * S * C)).astype(np.int8)
+    got = oracle.conv2d(w, x, "i8", R, S, pad, stride)
+    want = w.astype(np.int64) @ _im2col_general(x.astype(np.int64), R, S, pad, stride).T
+    assert np.array_equal(got.astype(np.int64), want)
+    # library routine: torch's CPU convolution in float64 (exact for these magnitudes)
+    import torch
+    xt = torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(w.astype(np.float64).reshape(M, R, S, C)).permute(0, 3, 1, 2)
+    ref = torch.nn.functional.conv2d(xt, wt, padding=pad, stride=stride)        # [n, M, OH, OW]
+    ref = ref.permute(1, 0, 2, 3).reshape(M, -1).numpy()
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+def test_conv2d_float_equals_pinned_product_of_im2col(dt):
+    n, H, W, C, M, R, S, pad, stride = CONV_GEOMS[2]
+    rng = np.random.default_rng(12)
+    x = synth.to_bits(rng.standard_normal((n, H, W, C)), dt)
+    w = synth.to_bits(rng.standard_normal((M, R * S * C)) * 0.1, dt)
+    got = oracle.conv2d(w, x, dt, R, S, pad, stride)
+    cols = _im2col_general(x, R, S, pad, stride)                 # bit patterns; padding 0 is +0.0
+    want = oracle.gemm(w, np.ascontiguousarray(cols.T), dt)
+    # same products, same ascending-k order apart from the skipped zero taps: equal to the last bit or nearly
+    assert np.allclose(got, want, rtol=0, atol=1e-12 * np.abs(want).max())
+    ref = oracle.to_double(w, dt) @ oracle.to_double(cols, dt).T
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_conv2d_pointwise_is_the_plain_product():
+    rng = np.random.default_rng(13)
+    x = rng.integers(-5, 6, size=(2, 3, 4, 8)).astype(np.int8)
+    w = rng.integers(-5, 6, size=(6, 8)).astype(np.int8)
+    got = oracle.conv2d(w, x, "i8", 1, 1)
+    assert np.array_equal(got, oracle.gemm(w, np.ascontiguousarray(x.reshape(-1, 8).T), "i8"))
+
+
+def test_conv2d_one_hot_filter_shifts_the_image():
+    # filter m = 1 at tap (r, s), channel c: the output is the input channel c shifted by (r - pad, s - pad)
+    n, H, W, C, R, S = 1, 5, 6, 4, 3, 3
+    rng = np.random.default_rng(14)
+    x = rng.integers(1, 100, size=(n, H, W, C)).astype(np.int8)
+    for (r, s, c) in [(0, 0, 1), (1, 1, 0), (2, 0, 3), (1, 2, 2)]:
+        w = np.zeros((1, R * S * C), dtype=np.int8)
+        w[0, (r * S + s) * C + c] = 1
+        got = oracle.conv2d(w, x, "i8", R, S, (1, 1), (1, 1)).reshape(H, W)
+        want = np.zeros((H, W), dtype=np.int32)
+        for oy in range(H):
+            for ox in range(W):
+                iy, ix = oy - 1 + r, ox - 1 + s
+                if 0 <= iy < H and 0 <= ix < W:
+                    want[oy, ox] = x[0, iy, ix, c]
+        assert np.array_equal(got, want)
+
+
+def test_conv_workload_matrix_is_the_im2col_of_its_activations():
+    A, Bt = synth.make("conv3x3_f16", M=32, N=196 * 2, K=9 * 16)
+    X = synth.conv_activations(0, 2, 16)
+    assert np.array_equal(Bt, _im2col_general(X, 3, 3, (1, 1), (1, 1)))
+    P = oracle.prune(A, "f16")
+    d1 = oracle.conv2d(P, X, "f16", 3, 3, (1, 1), (1, 1))
+    d2 = oracle.gemm(P, np.ascontiguousarray(Bt.T), "f16")
+    assert np.allclose(d1, d2, rtol=1e-12, atol=1e-12)
