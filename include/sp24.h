@@ -153,6 +153,39 @@ sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, in
                             int64_t lda, int64_t ldb, int64_t ldd, sp24_dtype in, sp24_dtype out,
                             sp24_border bo, void* stream);
 
+/*
+ * Convolution as a GEMM-like operation whose first argument is the sparse
+ * tensor (Sec. 3.2; inner dimension C x R x S, Sec. 4.2), computed as an
+ * implicit GEMM: the second operand is never formed in memory.
+ *   D[m][(img*OH + oy)*OW + ox] = sum over r, s, c of
+ *       W[m][(r*S + s)*C + c] * X[img][oy*stride_h - pad_h + r][ox*stride_w - pad_w + s][c]
+ * with W = decompress(V, meta), M filters of K = R*S*C columns (input channel
+ * innermost, so a group of four is four consecutive channels of one filter
+ * tap); taps outside the image contribute zero; OH = (H + 2*pad_h - R) /
+ * stride_h + 1, OW likewise; N = n_img*OH*OW.
+ * X: device, NHWC [n_img][H][W][C], dense, element-aligned (16-byte aligned
+ * for the fast kernels).  D: device, M x N, ldd >= N.  Types, accumulation,
+ * rounding and layouts as for sp24_spmm.
+ * SP24_ERR_SHAPE unless H, W, C, R, S >= 1, pads >= 0, strides >= 1,
+ * H + 2*pad_h >= R, W + 2*pad_w >= S, C * element size is a multiple of 16
+ * bytes (16 bytes of K never straddle a filter tap), K is legal, and the
+ * sizes stay below 2^20 (H, W, C), 4096 (R, S, pads, strides), 2^31 (N).
+ */
+sp24_status sp24_spmm_conv2d(const void* V, const void* meta, const void* X, void* D, int64_t M,
+                             int64_t n_img, int64_t H, int64_t W, int64_t C, int R, int S,
+                             int pad_h, int pad_w, int stride_h, int stride_w, int64_t ldd,
+                             sp24_dtype in, sp24_dtype out, sp24_layout l, void* stream);
+
+/*
+ * The same convolution with the dense filter matrix A (M x R*S*C, row stride
+ * lda) on the dense matrix cores: the denominator of the speedup for
+ * convolution layers (Sec. 3.2, Fig. 3).
+ */
+sp24_status sp24_conv2d_dense(const void* A, const void* X, void* D, int64_t M, int64_t n_img,
+                              int64_t H, int64_t W, int64_t C, int R, int S, int pad_h, int pad_w,
+                              int stride_h, int stride_w, int64_t lda, int64_t ldd, sp24_dtype in,
+                              sp24_dtype out, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* sp24_status_string(sp24_status s);
 

@@ -114,7 +114,8 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
     return launch_decompress(V, meta, P, M, K, ldp, t, l, static_cast<hipStream_t>(stream));
 }
 
-static sp24_status mm_common(MmArgs& a, hipStream_t st)
+// x_bytes: extent of the NHWC input when a.conv.on (a.B then points at it), else unused
+static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
 {
     if (!is_input_type(a.in) || !out_legal(a.in, a.out)) return SP24_ERR_DTYPE;
     if (a.bo != SP24_B_KMAJOR && a.bo != SP24_B_NMAJOR) return SP24_ERR_LAYOUT;
@@ -133,18 +134,26 @@ static sp24_status mm_common(MmArgs& a, hipStream_t st)
         s = check_matrix(a.A, a.M, a.K, a.lda, es);
         if (s != SP24_OK) return s;
     }
-    s = (a.bo == SP24_B_KMAJOR) ? check_matrix(a.B, a.N, a.K, a.ldb, es, false) : check_matrix(a.B, a.K, a.N, a.ldb, es, false);
-    if (s != SP24_OK) return s;
+    if (a.conv.on) {
+        if (!a.B) return SP24_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(a.B) % es != 0) return SP24_ERR_ALIGN;
+    } else {
+        s = (a.bo == SP24_B_KMAJOR) ? check_matrix(a.B, a.N, a.K, a.ldb, es, false) : check_matrix(a.B, a.K, a.N, a.ldb, es, false);
+        if (s != SP24_OK) return s;
+    }
     s = check_matrix(a.D, a.M, a.N, a.ldd, os, false);
     if (s != SP24_OK) return s;
     size_t nd = ((size_t)(a.M - 1) * a.ldd + a.N) * os;
-    size_t nb = (a.bo == SP24_B_KMAJOR) ? ((size_t)(a.N - 1) * a.ldb + a.K) * es : ((size_t)(a.K - 1) * a.ldb + a.N) * es;
+    size_t nb = a.conv.on ? x_bytes
+                          : (a.bo == SP24_B_KMAJOR) ? ((size_t)(a.N - 1) * a.ldb + a.K) * es : ((size_t)(a.K - 1) * a.ldb + a.N) * es;
     size_t nA = a.sparse ? sp24_values_bytes(a.M, a.K, a.in) : ((size_t)(a.M - 1) * a.lda + a.K) * es;
     if (ranges_overlap(a.D, nd, a.B, nb) || ranges_overlap(a.D, nd, a.A, nA)) return SP24_ERR_SHAPE;
     if (a.sparse && ranges_overlap(a.D, nd, a.meta, sp24_meta_bytes(a.M, a.K, a.in, a.layout))) return SP24_ERR_SHAPE;
     bool handled = false;
-    s = launch_mm_skinny(a, st, &handled);
-    if (handled) return s;
+    if (!a.conv.on) {
+        s = launch_mm_skinny(a, st, &handled);
+        if (handled) return s;
+    }
     s = launch_mm_tiled(a, st, &handled);
     if (handled) return s;
     return launch_mm_simple(a, st);
@@ -162,6 +171,46 @@ sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, in
 {
     MmArgs a{A, nullptr, B, D, M, N, K, lda, ldb, ldd, in, out, bo, SP24_LAYOUT_CANONICAL, false};
     return mm_common(a, static_cast<hipStream_t>(stream));
+}
+
+// Shared front end of the two convolution entry points: geometry checks, then the product path with B = X.
+static sp24_status conv_common(MmArgs& a, int64_t n_img, int64_t H, int64_t W, int64_t C, int R, int S, int pad_h, int pad_w,
+                               int stride_h, int stride_w, hipStream_t st)
+{
+    if (!is_input_type(a.in) || !out_legal(a.in, a.out)) return SP24_ERR_DTYPE;
+    const int64_t lim = (int64_t)1 << 20;
+    if (a.M < 0 || n_img < 0 || H < 1 || W < 1 || C < 1 || R < 1 || S < 1 || pad_h < 0 || pad_w < 0 || stride_h < 1 || stride_w < 1 ||
+        H > lim || W > lim || C > lim || R > 4096 || S > 4096 || pad_h > 4096 || pad_w > 4096 || stride_h > 4096 || stride_w > 4096 ||
+        H + 2 * pad_h < R || W + 2 * pad_w < S)
+        return SP24_ERR_SHAPE;
+    const int es = esize_of(a.in);
+    if ((C * es) % 16 != 0) return SP24_ERR_SHAPE;      // 16 consecutive bytes of K never straddle a filter tap
+    const int64_t OH = (H + 2 * pad_h - R) / stride_h + 1, OW = (W + 2 * pad_w - S) / stride_w + 1;
+    const int64_t K = (int64_t)R * S * C;
+    if (K > ((int64_t)1 << 30) || (n_img > 0 && OH * OW > (((int64_t)1 << 31) - 1) / n_img)) return SP24_ERR_SHAPE;
+    if (n_img > 0 && H * W * C > (((int64_t)1 << 46) / n_img)) return SP24_ERR_SHAPE;
+    a.N = n_img * OH * OW;
+    a.K = K;
+    a.bo = SP24_B_KMAJOR;
+    a.ldb = K;
+    a.conv = ConvGeom{1, (int)H, (int)W, (int)C, R, S, pad_h, pad_w, stride_h, stride_w, (int)OH, (int)OW};
+    return mm_common(a, st, (size_t)n_img * H * W * C * es);
+}
+
+sp24_status sp24_spmm_conv2d(const void* V, const void* meta, const void* X, void* D, int64_t M, int64_t n_img, int64_t H,
+                             int64_t W, int64_t C, int R, int S, int pad_h, int pad_w, int stride_h, int stride_w, int64_t ldd,
+                             sp24_dtype in, sp24_dtype out, sp24_layout l, void* stream)
+{
+    MmArgs a{V, meta, X, D, M, 0, 0, 0, 0, ldd, in, out, SP24_B_KMAJOR, l, true};
+    return conv_common(a, n_img, H, W, C, R, S, pad_h, pad_w, stride_h, stride_w, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_conv2d_dense(const void* A, const void* X, void* D, int64_t M, int64_t n_img, int64_t H, int64_t W, int64_t C,
+                              int R, int S, int pad_h, int pad_w, int stride_h, int stride_w, int64_t lda, int64_t ldd,
+                              sp24_dtype in, sp24_dtype out, void* stream)
+{
+    MmArgs a{A, nullptr, X, D, M, 0, 0, lda, 0, ldd, in, out, SP24_B_KMAJOR, SP24_LAYOUT_CANONICAL, false};
+    return conv_common(a, n_img, H, W, C, R, S, pad_h, pad_w, stride_h, stride_w, static_cast<hipStream_t>(stream));
 }
 
 const char* sp24_status_string(sp24_status s)

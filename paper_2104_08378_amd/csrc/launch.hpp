@@ -10,6 +10,15 @@ sp24_status launch_prune(const void* A, void* P, int64_t M, int64_t K, int64_t l
 sp24_status launch_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_dtype t, sp24_layout l, hipStream_t st);
 sp24_status launch_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp, sp24_dtype t, sp24_layout l, hipStream_t st);
 
+// Geometry of a convolution read as an implicit GEMM (Sec. 3.2: convolutions are GEMM-like operations; Sec. 4.2:
+// inner dimension C x R x S): the second operand is never formed, element (k, n) of it is
+//   X[img][oy*stride_h - pad_h + r][ox*stride_w - pad_w + s][c]   (zero outside the image)
+// with k = (r*S + s)*C + c and n = (img*OH + oy)*OW + ox, X being NHWC.
+struct ConvGeom {
+    int on;                 // 0: plain matrix B
+    int H, W, C, R, S, pad_h, pad_w, stride_h, stride_w, OH, OW;
+};
+
 // Problem description for the matrix-multiply kernels.  For the sparse product
 // A = V and lda is unused; for the dense product meta is null.
 struct MmArgs {
@@ -23,6 +32,7 @@ struct MmArgs {
     sp24_border bo;
     sp24_layout layout;    // sparse only
     bool sparse;
+    ConvGeom conv;         // conv.on: B is the NHWC input X, N = n_img*OH*OW, K = R*S*C, bo / ldb unused
 };
 
 // General kernel: any M, N; both layouts; both B orders.  One wavefront per 32x32 tile of D.

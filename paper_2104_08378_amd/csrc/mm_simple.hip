@@ -8,6 +8,8 @@
 #include "launch.hpp"
 #include "mfma.hpp"
 
+#include <type_traits>
+
 namespace sp24 {
 
 template <int ES>
@@ -37,6 +39,27 @@ __device__ __forceinline__ void gather(const void* p, int64_t k0, int64_t kmax, 
     }
 }
 
+// Output pixel of a convolution column n: image and the input coordinates of filter tap (0, 0).
+struct ConvPixel {
+    int64_t img;
+    int iy0, ix0;
+};
+
+// The same gather for a convolution read as an implicit GEMM: COUNT consecutive k (16 bytes, starting at a
+// multiple of 16 bytes) lie inside one filter tap because C * element size is a multiple of 16 bytes.
+template <int ES, int COUNT>
+__device__ __forceinline__ void gather_conv(const MmArgs& a, int64_t k0, int64_t kmax, bool n_ok, const ConvPixel& px, int* dst)
+{
+    const ConvGeom& g = a.conv;
+    const int64_t tap = k0 / g.C;
+    const int c = (int)(k0 - tap * g.C);
+    const int r = (int)(tap / g.S), s = (int)(tap - (int64_t)r * g.S);
+    const int iy = px.iy0 + r, ix = px.ix0 + s;
+    const bool ok = n_ok && k0 < kmax && (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
+    const int64_t base = ((px.img * g.H + iy) * g.W + ix) * g.C + c;
+    gather<ES, COUNT>(a.B, 0, COUNT, ok, base, 1, dst);
+}
+
 template <int DT, int OUT, bool SPARSE>
 __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
 {
@@ -50,6 +73,23 @@ __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
     // element (k, n) of B
     const int64_t b_stride_k = (a.bo == SP24_B_KMAJOR) ? 1 : a.ldb;
     const int64_t b_base = (a.bo == SP24_B_KMAJOR) ? n * a.ldb : n;
+    ConvPixel px = {0, 0, 0};
+    if (a.conv.on && n_ok) {
+        const int64_t t = n / a.conv.OW;
+        px.img = t / a.conv.OH;
+        px.iy0 = (int)(t - px.img * a.conv.OH) * a.conv.stride_h - a.conv.pad_h;
+        px.ix0 = (int)(n - t * a.conv.OW) * a.conv.stride_w - a.conv.pad_w;
+    }
+    // COUNT values of column n of B starting at row k0, packed into dwords
+    auto load_b = [&](auto es_tag, auto count_tag, int64_t k0, int* dst) {
+        constexpr int E = decltype(es_tag)::value, CNT = decltype(count_tag)::value;
+        if (a.conv.on) gather_conv<E, CNT>(a, k0, K, n_ok, px, dst);
+        else gather<E, CNT>(a.B, k0, K, n_ok, b_base, b_stride_k, dst);
+    };
+    using i1 = std::integral_constant<int, 1>;
+    using i2 = std::integral_constant<int, 2>;
+    using i8c = std::integral_constant<int, 8>;
+    using i16c = std::integral_constant<int, 16>;
     acc_t acc = {};
     const int64_t KB = (K + 63) / 64;
     for (int64_t kb = 0; kb < KB; ++kb) {
@@ -76,8 +116,8 @@ __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
                     gather<1, 16>(a.A, kb * 32 + 16 * q, K2, m_ok, m * K2, 1, tmp);
                     for (int i = 0; i < 4; ++i) av[i] = tmp[i];
                 }
-                gather<1, 16>(a.B, kb * 64 + 16 * q, K, n_ok, b_base, b_stride_k, tmp);
-                gather<1, 16>(a.B, kb * 64 + 32 + 16 * q, K, n_ok, b_base, b_stride_k, tmp + 4);
+                load_b(i1{}, i16c{}, kb * 64 + 16 * q, tmp);
+                load_b(i1{}, i16c{}, kb * 64 + 32 + 16 * q, tmp + 4);
                 for (int i = 0; i < 8; ++i) bv[i] = tmp[i];
                 acc = smfmac32<DT, 0>(av, bv, acc, (int)codes);
             } else {
@@ -92,8 +132,8 @@ __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
                         gather<2, 8>(a.A, kb * 32 + 16 * q + 8 * s, K2, m_ok, m * K2, 1, tmp);
                         for (int i = 0; i < 4; ++i) av[i] = tmp[i];
                     }
-                    gather<2, 8>(a.B, kb * 64 + 16 * s + 8 * q, K, n_ok, b_base, b_stride_k, tmp);
-                    gather<2, 8>(a.B, kb * 64 + 32 + 16 * s + 8 * q, K, n_ok, b_base, b_stride_k, tmp + 4);
+                    load_b(i2{}, i8c{}, kb * 64 + 16 * s + 8 * q, tmp);
+                    load_b(i2{}, i8c{}, kb * 64 + 32 + 16 * s + 8 * q, tmp + 4);
                     for (int i = 0; i < 8; ++i) bv[i] = tmp[i];
                     if (s == 0) acc = smfmac32<DT, 0>(av, bv, acc, (int)codes);
                     else acc = smfmac32<DT, 1>(av, bv, acc, (int)codes);
@@ -107,7 +147,7 @@ __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
                 int ta[4], tb[4];
                 int64_t k0 = kb * 64 + j * PERK + (PERK / 2) * q;
                 gather<ES, PERK / 2>(a.A, k0, K, m_ok, m * a.lda, 1, ta);
-                gather<ES, PERK / 2>(a.B, k0, K, n_ok, b_base, b_stride_k, tb);
+                load_b(std::integral_constant<int, ES>{}, std::integral_constant<int, PERK / 2>{}, k0, tb);
                 for (int i = 0; i < 4; ++i) { av[i] = ta[i]; bv[i] = tb[i]; }
                 acc = mfma32<DT>(av, bv, acc);
             }

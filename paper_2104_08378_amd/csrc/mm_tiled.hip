@@ -92,6 +92,72 @@ __device__ __forceinline__ void lds_dma4(const uint8_t* base, uint32_t off, cons
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(l) : "m0");
 }
 
+// The same transfer with a full 64-bit address per lane (for gathers that a base + 32-bit offset cannot express).
+__device__ __forceinline__ void lds_dma16_addr(const uint8_t* addr, const uint8_t* lds)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(l) : "m0");
+}
+
+// 128 zero bytes: the source of B rows that fall into a convolution's padding or past the last output pixel.
+__device__ __attribute__((aligned(128))) const uint8_t k_zero_row[128] = {};
+
+// Position of a K step inside a convolution's inner dimension k = (r*S + s)*C + c: a step (128 bytes of K) lies
+// inside one filter tap when C * element size is a multiple of 128 bytes.
+struct ConvTap {
+    int r, s, c0;
+    __device__ __forceinline__ void next(const ConvGeom& g, int bk)
+    {
+        c0 += bk;
+        if (c0 == g.C) {
+            c0 = 0;
+            if (++s == g.S) { s = 0; ++r; }
+        }
+    }
+};
+
+// B rows of a convolution read as an implicit GEMM (Sec. 3.2; inner dimension C x R x S, Sec. 4.2): row n of the
+// operand is output pixel n, and its 128 bytes of a step are 128 contiguous bytes of the NHWC input at the
+// pixel that filter tap (r, s) meets -- or zeros when that pixel is padding.  Per lane and transfer: the input
+// coordinates of tap (0, 0) and the byte offset of that (possibly virtual) pixel, swizzle piece included.
+template <int ROWS, int NW, int ES>
+struct conv_rows {
+    static constexpr int NJ = ROWS / 8 / NW;
+    int iy0[NJ], ix0[NJ];
+    int32_t off[NJ];
+    __device__ __forceinline__ void init(const ConvGeom& g, int64_t n0, int64_t N, int wave, int lane)
+    {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int row = (wave * NJ + j) * 8 + (lane >> 3);
+            const int piece = (lane & 7) ^ ((row >> 1) & 7);
+            const int64_t n = n0 + row;
+            if (n < N) {
+                const int t = (int)(n / g.OW), ox = (int)(n - (int64_t)t * g.OW);
+                const int img = t / g.OH, oy = t - img * g.OH;
+                iy0[j] = oy * g.stride_h - g.pad_h;
+                ix0[j] = ox * g.stride_w - g.pad_w;
+                off[j] = (((img * g.H + iy0[j]) * g.W + ix0[j]) * g.C) * ES + piece * 16;
+            } else {                                       // past the last pixel: always zeros, never stored
+                iy0[j] = -(1 << 24);
+                ix0[j] = 0;
+                off[j] = 0;
+            }
+        }
+    }
+    // transfer j of this wavefront for the step at tap t
+    __device__ __forceinline__ void issue(int j, const uint8_t* X, const ConvGeom& g, const ConvTap& t, uint8_t* stage, int wave) const
+    {
+        const int tap_off = ((t.r * g.W + t.s) * g.C + t.c0) * ES;
+        // branch-free select between the pixel and the zero row (a divergent branch per transfer costs far more)
+        const uint64_t inside = (uint64_t)((unsigned)(iy0[j] + t.r) < (unsigned)g.H) & (uint64_t)((unsigned)(ix0[j] + t.s) < (unsigned)g.W);
+        const uint64_t mask = (uint64_t)0 - inside;
+        const uint64_t pixel = reinterpret_cast<uint64_t>(X) + (uint32_t)(off[j] + tap_off);
+        const uint64_t src = (pixel & mask) | (reinterpret_cast<uint64_t>(k_zero_row) & ~mask);
+        lds_dma16_addr(reinterpret_cast<const uint8_t*>(src), stage + (wave * NJ + j) * 1024);
+    }
+};
+
 template <int ROWS, int NW>
 __device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&off)[ROWS / 8 / NW], uint8_t* stage, int wave)
 {
@@ -155,10 +221,10 @@ __device__ __forceinline__ void store_wave_tile(const MmArgs& a, typename acc_of
 // ---------------------------------------------------------------------------
 // Sparse kernel.  Stage layout: [B: BN rows x 128 B, swizzled][V: 2 KiB per
 // 32-row block, in the tiled layout's own order][meta: 256 B per 32x64 tile].
-// Three stages; the transfers for step s+2 are issued during step s, and the
+// NS stages; the transfers for step s+NS-1 are issued during step s, and the
 // first operands of step s+1 are read from LDS during the tail of step s.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int WM, int WN, int TM, int TN>
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, bool CONV>
 __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr int ES = (DT == SP24_I8) ? 1 : 2;
@@ -176,7 +242,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     constexpr int kStageBytes = kMOff + RB * T64 * 256;
     using acc_t = typename acc_of<DT>::type;
     constexpr int kEpiBytes = NW * epilogue_geometry<OUT, TN>::kWaveBytes;
-    constexpr int kLdsBytes = 3 * kStageBytes > kEpiBytes ? 3 * kStageBytes : kEpiBytes;
+    static_assert(NS >= 3 && (NS - 2) * NV <= 63, "at least three stages; vmcnt is a 6-bit counter");
+    constexpr int kLdsBytes = NS * kStageBytes > kEpiBytes ? NS * kStageBytes : kEpiBytes;
     __shared__ __attribute__((aligned(1024))) uint8_t lds_all[kLdsBytes];
 
     int tm, tn;
@@ -193,7 +260,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     const int64_t ldb_bytes = a.ldb * ES;
     const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
     uint32_t b_off[NJB];
-    dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+    conv_rows<BN, NW, ES> b_conv;
+    if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
+    else dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
     // V: transfer x of this wavefront is 1 KiB number (wave*NJV + x) of the RB*2 of a step: row block /2, half %2
     const uint8_t* v_base[NJV];                            // wavefront-uniform; lane l adds 16*l
 #pragma unroll
@@ -216,15 +285,29 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
 
     auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
     // transfer number x (0 .. NV-1) of this wavefront for a step: B rows, then values, then codes
-    auto dma_one = [&](int step, int u, int x) {
+    // (convolution: `tap` is the position of `step` in the inner dimension)
+    auto dma_one = [&](int step, const ConvTap& tap, int u, int x) {
         uint8_t* stg = stage_ptr(u);
-        if (x < NJB) lds_dma16(b_blk + (int64_t)step * kRowBytes, b_off[x], stg + (wave * NJB + x) * 1024);
+        if (x < NJB) {
+            if constexpr (CONV) b_conv.issue(x, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stg, wave);
+            else lds_dma16(b_blk + (int64_t)step * kRowBytes, b_off[x], stg + (wave * NJB + x) * 1024);
+        }
         else if (x < NJB + NJV) lds_dma16(v_base[x - NJB] + (int64_t)step * 2048, lane16, stg + kVOff + (wave * NJV + x - NJB) * 1024);
         else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * (T64 * 256), lane4, stg + kMOff + (wave * NJM + x - NJB - NJV) * 256);
     };
-    auto dma = [&](int step, int u) {
+    auto dma = [&](int step, const ConvTap& tap, int u) {
 #pragma unroll
-        for (int x = 0; x < NV; ++x) dma_one(step, u, x);
+        for (int x = 0; x < NV; ++x) dma_one(step, tap, u, x);
+    };
+    // the step whose transfers are issued next, kept NS - 1 ahead of the arithmetic.  It stops at the last step:
+    // past the end that step is fetched again into a stage nobody reads, which keeps the counts uniform.
+    int f_step = 0;
+    ConvTap f_tap = {0, 0, 0};
+    auto advance_fetch = [&]() {
+        if (f_step + 1 < nsteps) {
+            ++f_step;
+            if constexpr (CONV) f_tap.next(a.conv, BK);
+        }
     };
 
     acc_t acc[TM][TN];
@@ -273,12 +356,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     //   t >= T1:   the first operands of step s+1 are read while the last instructions of step s run, so that
     //              no wavefront starts a step waiting for LDS.
     constexpr int NF = 2 * TN, T1 = NF - 2;
-    constexpr int kWait = waitcnt_vm(NV);
-    auto do_step = [&](int step, int u) {
+    constexpr int kWait = waitcnt_vm((NS - 2) * NV);
+    auto do_step = [&](int u) {
         const uint8_t* cur = stage_ptr(u);
-        const uint8_t* nxt = stage_ptr((u + 1) % 3);
-        const int fetch = min(step + 2, nsteps - 1);   // past the end the last step is fetched again into a stage
-                                                       // nobody reads: keeps the counts uniform
+        const uint8_t* nxt = stage_ptr((u + 1) % NS);
         int4v av[2][TM];
         int mv[2][TM];
         int8v f[3];
@@ -309,16 +390,20 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
                 if (t < T1) {
                     const int m = t * TM + i;
 #pragma unroll
-                    for (int x = m * NV / (T1 * TM); x < (m + 1) * NV / (T1 * TM); ++x) dma_one(fetch, (u + 2) % 3, x);
+                    for (int x = m * NV / (T1 * TM); x < (m + 1) * NV / (T1 * TM); ++x) dma_one(f_step, f_tap, (u + NS - 1) % NS, x);
                 }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        advance_fetch();
     };
 
-    // prologue: stages 0 and 1 on their way; first operands of step 0 once stage 0 has landed
-    dma(0, 0);
-    dma(min(1, nsteps - 1), 1);
+    // prologue: the first NS - 1 stages on their way; first operands of step 0 once stage 0 has landed
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u) {
+        dma(f_step, f_tap, u);
+        advance_fetch();
+    }
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(kWait);
     __builtin_amdgcn_s_barrier();
@@ -327,16 +412,15 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     read_frag(lds_all, 0, f_first[0]);
     read_frag(lds_all, 1, f_first[1]);
     __builtin_amdgcn_sched_barrier(0);
-    // three steps per iteration in one basic block, so that stage indices are static and the compiler's
-    // wait-count bookkeeping stays exact; the remainder runs after the loop
+    // NS steps per iteration, so that stage indices are compile-time constants; the remainder runs after the loop
     int step = 0;
-    for (; step + 3 <= nsteps; step += 3) {
-        do_step(step, 0);
-        do_step(step + 1, 1);
-        do_step(step + 2, 2);
+    for (; step + NS <= nsteps; step += NS) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) do_step(u);
     }
-    if (step < nsteps) do_step(step, 0);
-    if (step + 1 < nsteps) do_step(step + 1, 1);
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u)
+        if (step + u < nsteps) do_step(u);
     // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
@@ -348,10 +432,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
 // ---------------------------------------------------------------------------
 // Dense kernel: the speedup denominator (Sec. 3.2, Fig. 3).  A and B both go
 // through LDS (A is plain row-major, so its fragments are not contiguous in
-// memory); two stages, transfers one step ahead -- a dense step holds twice
-// the arithmetic of a sparse one, which is what hides the latency here.
+// memory); NS stages, transfers NS - 1 steps ahead.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int WM, int WN, int TM, int TN>
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, bool CONV>
 __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr int ES = (DT == SP24_I8) ? 1 : 2;
@@ -362,7 +445,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
     using acc_t = typename acc_of<DT>::type;
     constexpr int kEpiBytes = NW * epilogue_geometry<OUT, TN>::kWaveBytes;
-    constexpr int kLdsBytes = 2 * kStageBytes > kEpiBytes ? 2 * kStageBytes : kEpiBytes;
+    static_assert(NS >= 2 && (NS - 2) * (NJA + NJB) <= 63, "at least two stages; vmcnt is a 6-bit counter");
+    constexpr int kLdsBytes = NS * kStageBytes > kEpiBytes ? NS * kStageBytes : kEpiBytes;
     __shared__ __attribute__((aligned(1024))) uint8_t lds_all[kLdsBytes];
 
     int tm, tn;
@@ -378,7 +462,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
     const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
     uint32_t a_off[NJA], b_off[NJB];
     dma_offsets<BM, NW>((int64_t)tm * BM, a.M, lda_bytes, wave, lane, a_off);
-    dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+    conv_rows<BN, NW, ES> b_conv;
+    if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
+    else dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
 
     acc_t acc[TM][TN];
 #pragma unroll
@@ -387,9 +473,24 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
         for (int j = 0; j < TN; ++j) acc[i][j] = acc_t{};
 
     auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
-    auto dma = [&](int step, int u) {
+    // (convolution: `tap` is the position of `step` in the inner dimension)
+    auto dma = [&](int step, const ConvTap& tap, int u) {
         dma_rows<BM, NW>(a_blk + (int64_t)step * kRowBytes, a_off, stage_ptr(u), wave);
-        dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u) + BM * kRowBytes, wave);
+        if constexpr (CONV) {
+#pragma unroll
+            for (int j = 0; j < NJB; ++j)
+                b_conv.issue(j, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stage_ptr(u) + BM * kRowBytes, wave);
+        } else dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u) + BM * kRowBytes, wave);
+    };
+    // the step whose transfers are issued next, NS - 1 ahead of the arithmetic; it stops at the last step, which
+    // is then fetched again into stages nobody reads
+    int f_step = 0;
+    ConvTap f_tap = {0, 0, 0};
+    auto advance_fetch = [&]() {
+        if (f_step + 1 < nsteps) {
+            ++f_step;
+            if constexpr (CONV) f_tap.next(a.conv, BK);
+        }
     };
 
     // fragment of instruction jj (k-bytes 32*jj .. +31 of the step): lane reads piece 2*jj + q of its row
@@ -422,11 +523,14 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
     };
 
     constexpr int NMFMA = 4 * TM * TN, NV = NJA + NJB;
-    auto do_step = [&](int step, int u) {
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // this wavefront's share of stage u has landed
-        __builtin_amdgcn_s_barrier();                // ... and everybody's; stage u^1 is no longer being read
+    auto do_step = [&](int u) {
+        // this wavefront's share of stage u has landed (vmcnt counts in issue order: only the transfers of the
+        // NS - 2 later steps may still be in flight) ...
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 2) * NV));
+        __builtin_amdgcn_s_barrier();                // ... and everybody's; the stage read in the previous step is free
         __builtin_amdgcn_sched_barrier(0);
-        dma(min(step + 1, nsteps - 1), u ^ 1);
+        dma(f_step, f_tap, (u + NS - 1) % NS);
+        advance_fetch();
         compute(u);
         __builtin_amdgcn_sched_group_barrier(kSgDsRead, TM + TN, 0);
 #pragma unroll
@@ -441,14 +545,20 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    dma(0, 0);
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u) {
+        dma(f_step, f_tap, u);
+        advance_fetch();
+    }
     __builtin_amdgcn_sched_barrier(0);
     int step = 0;
-    for (; step + 2 <= nsteps; step += 2) {
-        do_step(step, 0);
-        do_step(step + 1, 1);
+    for (; step + NS <= nsteps; step += NS) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) do_step(u);
     }
-    if (step < nsteps) do_step(step, 0);
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u)
+        if (step + u < nsteps) do_step(u);
     // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
@@ -460,14 +570,20 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
 // ---------------------------------------------------------------------------
 // Host side.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int WM, int WN, int TM, int TN>
+// NSS / NSD: pipeline stages of the sparse / dense kernel
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NSS, int NSD>
 static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
 {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WM * WN);
-    if (a.sparse) k_spmm_pipe<DT, OUT, WM, WN, TM, TN><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
-    else k_gemm_pipe<DT, OUT, WM, WN, TM, TN><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    if (a.sparse) {
+        if (a.conv.on) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, true><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, false><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    } else {
+        if (a.conv.on) k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, true><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, false><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    }
     return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;
 }
 
@@ -478,8 +594,13 @@ static sp24_status pick_tile(const MmArgs& a, hipStream_t st)
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
     // eight wavefronts of 64x128 each (two per SIMD, so that one computes while the other waits); measured
     // faster than four of 128x128 on the short-K transformer shape and equal on the long-K square one
-    if (big >= 200) return run_pipe<DT, OUT, 4, 2, 2, 4>(a, st);
-    return run_pipe<DT, OUT, 2, 2, 2, 2>(a, st);
+    if (big >= 200) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
+    // 128x128 tiles, four wavefronts.  With few tiles one workgroup per compute unit is all there is, and a short
+    // step (a quarter of the large tile's arithmetic) hides little latency: six (dense: four) stages, transfers
+    // five (three) steps ahead.  With many tiles three (two) stages leave room for two workgroups per compute unit.
+    const int64_t small = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+    if (small <= 256) return run_pipe<DT, OUT, 2, 2, 2, 2, 6, 4>(a, st);
+    return run_pipe<DT, OUT, 2, 2, 2, 2, 3, 2>(a, st);
 }
 
 sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
@@ -489,6 +610,16 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
     bool ok = a.bo == SP24_B_KMAJOR && a.K % (kRowBytes / es) == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 &&
               (a.ldb * es) % 16 == 0 && a.N >= 32 && a.M >= 64 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
               a.ldb * es < ((int64_t)1 << 22) && ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
+    if (a.conv.on) {
+        // implicit GEMM: a step must lie inside one filter tap, and byte offsets into the input must fit 31 bits
+        // (N / (OH*OW) images of H*W*C elements, plus the virtual pixels of the padding)
+        const ConvGeom& g = a.conv;
+        const int64_t n_img = a.N / ((int64_t)g.OH * g.OW);
+        const int64_t span = ((n_img * g.H + g.pad_h + g.R) * (int64_t)g.W + g.pad_w + g.S) * g.C * es;
+        ok = (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 && a.N >= 32 && a.M >= 64 && a.M <= ((int64_t)1 << 30) &&
+             ((int64_t)g.C * es) % kRowBytes == 0 && span < ((int64_t)1 << 31) &&
+             ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
+    }
     if (a.sparse) ok = ok && a.layout == SP24_LAYOUT_TILED;
     else ok = ok && a.lda * es < ((int64_t)1 << 22);
     if (!ok) return SP24_OK;

@@ -46,9 +46,12 @@ def lib():
         L.sp24_decompress.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
         L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
+        L.sp24_spmm_conv2d.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i32, i32, i32, vp]
+        L.sp24_conv2d_dense.argtypes = [vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i64, i32, i32, vp]
         L.sp24_status_string.argtypes = [i32]
         L.sp24_status_string.restype = ctypes.c_char_p
-        for name in ("sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense"):
+        for name in ("sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
+                     "sp24_conv2d_dense"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -157,4 +160,39 @@ def sp24_gemm_dense(A, B, out_dtype, b_order="k", out=None):
     D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
     _check(lib().sp24_gemm_dense(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0),
                                  D.stride(0), _DT[A.dtype], _DT[D.dtype], bo, _stream()), "sp24_gemm_dense")
+    return D
+
+
+def _conv_args(X, K, R, S, pad, stride):
+    _dev(X, "X")
+    if X.dim() != 4 or not X.is_contiguous():
+        raise ValueError("X must be a contiguous NHWC tensor [n_img, H, W, C]")
+    n_img, H, W, C = X.shape
+    if K != R * S * C:
+        raise ValueError("the filter matrix must have R*S*C columns")
+    (ph, pw), (sh, sw) = pad, stride
+    OH, OW = (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1
+    return (n_img, H, W, C, R, S, ph, pw, sh, sw), n_img * max(OH, 0) * max(OW, 0)
+
+
+def sp24_spmm_conv2d(V, meta, X, out_dtype, R, S, pad=(0, 0), stride=(1, 1), layout="canonical", out=None):
+    """D [M, n_img*OH*OW] = decompress(V, meta) applied as a bank of M filters to the NHWC input X, with no
+    im2col matrix in memory.  Filter column k = (r*S + s)*C + c."""
+    _dev(V, "V"), _dev(meta, "meta")
+    M, K = V.shape[0], V.shape[1] * 2
+    geom, N = _conv_args(X, K, R, S, pad, stride)
+    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_spmm_conv2d(V.data_ptr(), meta.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, D.stride(0),
+                                  _DT[V.dtype], _DT[D.dtype], _LAYOUT[layout], _stream()), "sp24_spmm_conv2d")
+    return D
+
+
+def sp24_conv2d_dense(A, X, out_dtype, R, S, pad=(0, 0), stride=(1, 1), out=None):
+    """The same convolution with the dense filter matrix A [M, R*S*C] on the dense matrix cores."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    geom, N = _conv_args(X, K, R, S, pad, stride)
+    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_conv2d_dense(A.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, A.stride(0), D.stride(0),
+                                   _DT[A.dtype], _DT[D.dtype], _stream()), "sp24_conv2d_dense")
     return D

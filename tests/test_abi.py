@@ -99,3 +99,27 @@ def test_matmul_validation():
     assert L.sp24_gemm_dense(V, B, D, 64, 64, 64, 32, 64, 64, sp24.F16, sp24.F32, 0, None) == SHAPE
     assert L.sp24_gemm_dense(0, B, D, 64, 64, 64, 64, 64, 64, sp24.F16, sp24.F32, 0, None) == NULL
     assert L.sp24_gemm_dense(V, B, D, 64, 64, 64, 64, 64, 64, sp24.I8, sp24.F16, 0, None) == DTYPE
+
+
+def test_convolution_validation():
+    L = sp24.lib()
+    V, Mt, X, D = P, P + 0x1000000, P + 0x2000000, P + 0x3000000
+
+    def conv(M=64, n=2, H=8, W=8, C=16, R=3, S=3, ph=1, pw=1, sh=1, sw=1, ldd=128, i=sp24.F16, o=sp24.F32, lay=0, V=V, Mt=Mt, X=X, D=D):
+        return L.sp24_spmm_conv2d(V, Mt, X, D, M, n, H, W, C, R, S, ph, pw, sh, sw, ldd, i, o, lay, None)
+
+    assert conv(o=sp24.I32) == DTYPE and conv(i=sp24.I8, o=sp24.F16) == DTYPE
+    assert conv(C=12) == SHAPE                       # 24 bytes per pixel: a 16-byte run would straddle taps
+    assert conv(C=8, R=1, S=1, ph=0, pw=0) == SHAPE  # K = 8 is not a legal inner dimension for 16-bit types
+    assert conv(i=sp24.I8, o=sp24.I32, C=16, R=1, S=1, ph=0, pw=0) == SHAPE   # K = 16 for int8
+    assert conv(R=11, ph=1) == SHAPE and conv(sh=0) == SHAPE and conv(ph=-1) == SHAPE and conv(H=0) == SHAPE
+    assert conv(ldd=100) == SHAPE                    # N = 2*8*8 = 128 columns
+    assert conv(X=0) == NULL and conv(D=0) == NULL and conv(Mt=0) == NULL
+    assert conv(X=X + 1) == ALIGN and conv(D=D + 2) == ALIGN and conv(V=V + 8) == ALIGN
+    assert conv(D=X) == SHAPE                        # output aliases the input
+    assert conv(M=48, lay=sp24.TILED) == LAYOUT
+    assert conv(M=0) == OK and conv(n=0) == OK
+    dense = L.sp24_conv2d_dense
+    assert dense(V, X, D, 64, 2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 100, 128, sp24.F16, sp24.F32, None) == SHAPE   # lda < K = 144
+    assert dense(0, X, D, 64, 2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 144, 128, sp24.F16, sp24.F32, None) == NULL
+    assert dense(V, X, D, 0, 2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 144, 128, sp24.F16, sp24.F32, None) == OK

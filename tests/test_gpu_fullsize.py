@@ -50,3 +50,30 @@ def test_full_size_workload(name):
         else:
             rms = float(np.sqrt(np.mean(ref * ref)))
             assert rel_err(out_to_f64(got), ref, rms) <= 1e-2, name
+
+
+def test_full_size_convolution_without_im2col():
+    """conv3x3_f16 as its title says, an implicit GEMM on the NHWC activations: sampled filters x pixels against
+    the oracle's direct convolution of whole images (the images that hold the sampled pixels)."""
+    w = synth.WORKLOADS["conv3x3_f16"]
+    dt, M = w["dtype"], w["M"]
+    A, _ = synth.make("conv3x3_f16", N=196)            # the filter matrix depends on M and K only
+    X = synth.conv_activations()                       # [64, 14, 14, 256]
+    n_img = X.shape[0]
+    Ad, Xd = to_gpu(A, dt), to_gpu(X, dt)
+    V, meta = sp24.sp24_compress(Ad, layout="tiled")
+    P = sp24.sp24_prune(Ad)
+    D = sp24.sp24_spmm_conv2d(V, meta, Xd, OUT_DT[w["out"]], 3, 3, (1, 1), (1, 1), layout="tiled")
+    Dd = sp24.sp24_conv2d_dense(P, Xd, OUT_DT[w["out"]], 3, 3, (1, 1), (1, 1))
+    torch.cuda.synchronize()
+    assert tuple(D.shape) == (M, w["N"])
+    rng = np.random.default_rng(8)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 127, 128, M - 1], rng.integers(0, M, 30)]))
+    imgs = [0, 17, n_img - 1]
+    Prows = oracle.prune(np.ascontiguousarray(A[rows]), dt)
+    for img in imgs:
+        ref = oracle.conv2d(Prows, np.ascontiguousarray(X[img:img + 1]), dt, 3, 3, (1, 1), (1, 1))      # [rows, 196]
+        rms = float(np.sqrt(np.mean(ref * ref)))
+        for got_t in (D, Dd):
+            got = got_t[torch.as_tensor(rows, device="cuda")][:, img * 196:(img + 1) * 196]
+            assert rel_err(out_to_f64(got), ref, rms) <= 1e-2, img
