@@ -31,9 +31,10 @@ PEAK_HBM = 8.0e12
 # (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a 1 GiB device copy;
 # summaries under profiles/).  None where not measured.
 MEASURED_TRAFFIC = {
-    "ffn_bf16": (2.0 * 34985.9 + 65807.8) * 1024,      # profiles/ffn_bf16_path_rocprofv3.txt   (algorithmic: 88.6 MB)
-    "square_i8": (2.0 * 295212.6 + 262144.0) * 1024,   # profiles/square_i8_path_rocprofv3.txt  (algorithmic: 377.5 MB)
-    "skinny_bf16": (2.0 * 37917.1 + 256.0) * 1024,     # profiles/skinny_bf16_path_rocprofv3.txt (algorithmic: 76.0 MB)
+    "ffn_bf16": (2.0 * 34973.1 + 65536.0) * 1024,      # profiles/ffn_bf16_path_rocprofv3.txt    (algorithmic: 88.6 MB)
+    "square_i8": (2.0 * 295017.8 + 262144.0) * 1024,   # profiles/square_i8_path_rocprofv3.txt   (algorithmic: 377.5 MB)
+    "skinny_bf16": (2.0 * 37917.1 + 256.0) * 1024,     # profiles/skinny_bf16_path_rocprofv3.txt  (algorithmic: 76.0 MB)
+    "conv3x3_f16": (2.0 * 5986.0 + 6272.0) * 1024,     # profiles/conv3x3_f16_path_rocprofv3.txt  (algorithmic: 13.5 MB, implicit gather)
 }
 
 
@@ -182,7 +183,7 @@ def main():
         roof = {"bound": "hbm", "achieved": bytes_spmm / t_sp / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                 "kernel": "sparse product", "note": "algorithmic bytes = V + meta + B (the NHWC input for the convolution) + D per launch"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC.get(name)
+    roof["traffic"] = None if (name == "conv3x3_f16" and not conv) else MEASURED_TRAFFIC.get(name)
     line = {
         "metric": "2:4 SpGEMM dense-equiv TFLOP/s on 1 MI355X; speedup vs same-shape dense GEMM",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
