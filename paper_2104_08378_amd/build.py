@@ -13,6 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsp24.so")
+PROBE = os.path.join(HERE, "sp24_probe")        # stand-alone measurement of the chip's ceilings (csrc/probe.hip)
 SOURCES = ["api.hip", "prune_compress.hip", "mm_simple.hip", "mm_tiled.hip", "mm_skinny.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -32,6 +33,8 @@ def build(verbose=False):
             print(" ".join(cmd))
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    probe_cmd = ["hipcc", *[f for f in FLAGS if f != "-fPIC"], os.path.join(CSRC, "probe.hip"), "-o", PROBE]
+    procs.append(("probe.hip", subprocess.Popen(probe_cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
     for src, p in procs:
         out, _ = p.communicate()
