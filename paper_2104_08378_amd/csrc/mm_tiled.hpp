@@ -1,0 +1,609 @@
+// Tiled, software-pipelined matrix-multiply kernels for large shapes.
+//
+// Sparse product (Sec. 3.2, Fig. 2) on the 32x32 sparse matrix-core
+// instructions, and the same-shape dense product on the dense ones.  A
+// workgroup of WM x WN wavefronts computes a (32*TM*WM) x (32*TN*WN) tile of D;
+// each wavefront owns TM x TN accumulator tiles of 32x32.  The large
+// configuration is 4 x 2 wavefronts of 64 x 128 each: a 256 x 256 tile, half of
+// the compute unit's register file in accumulators, two wavefronts per SIMD.
+//
+//   - a step consumes 128 bytes of every B row (128 int8 / 64 16-bit values of K);
+//   - every operand travels global -> LDS without passing through registers
+//     (global_load_lds) into a ring of stages, ahead of its use.  For the
+//     sparse kernel that is B plus the compressed A in its tiled layout, whose
+//     32-row tiles are contiguous 1 KiB runs of values and 256-byte runs of
+//     metadata words already in lane order (Sec. 3.1: no indirection,
+//     full-width reads), so a wavefront reads its A operands back with one
+//     conflict-free 16-byte and one 4-byte LDS read per lane;
+//   - two s_barriers per step and no fence: a wavefront awaits its own
+//     transfers with s_waitcnt vmcnt, the barrier then makes everybody's visible;
+//   - memory instructions are dealt out between the matrix-core instructions
+//     (sched_group_barrier) so that their issue time overlaps the arithmetic;
+//   - B rows in LDS are 128 bytes, unpadded (a transfer instruction fills
+//     1 KiB = 8 rows contiguously); the 16-byte piece c of row n sits at slot
+//     c ^ ((n >> 1) & 7), so that the fragment reads of 16 neighbouring rows
+//     hit 16 different 16-byte columns of the 256-byte-wide bank array;
+//   - workgroup ids are remapped so that the workgroups resident on one XCD
+//     (ids congruent mod 8) cover a compact 8 x n block of tiles and share
+//     their A and B panels in that XCD's L2.
+#pragma once
+#include "common.hpp"
+#include "launch.hpp"
+#include "mfma.hpp"
+
+namespace sp24 {
+
+constexpr int kRowBytes = 128;   // bytes of one operand row consumed per step
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
+// s_waitcnt immediate (gfx9 encoding) that waits for vmcnt <= n and leaves expcnt / lgkmcnt alone
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// sched_group_barrier masks
+constexpr int kSgMfma = 0x008, kSgVmem = 0x010, kSgDsRead = 0x100;
+
+// Workgroup id -> tile coordinates.  The hardware deals consecutive ids round-robin over the 8 XCDs; each XCD
+// is given a contiguous range of tiles, swept in groups of 8 tile rows.
+__device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int& tm, int& tn)
+{
+    const int nwg = tiles_m * tiles_n;
+    int wg = blockIdx.x;
+    const int per = (nwg + 7) / 8;
+    const int xcd = wg & 7, idx = wg >> 3;
+    const int full = nwg - (per - 1) * 8;   // XCDs that own `per` ids (the rest own per - 1)
+    wg = (xcd < full) ? xcd * per + idx : full * per + (xcd - full) * (per - 1) + idx;
+    constexpr int GM = 8;
+    const int group = wg / (GM * tiles_n);
+    const int first_m = group * GM;
+    const int gsz = min(tiles_m - first_m, GM);
+    const int in_group = wg - group * GM * tiles_n;
+    tm = first_m + in_group % gsz;
+    tn = in_group / gsz;
+}
+
+// Transfer ROWS rows x 128 bytes (row r of the stage = global row min(row0 + r, limit - 1)) into a stage.
+// Offsets of the ROWS/8/NW transfer instructions (8 rows each) of one of NW wavefronts, relative to the first row.
+template <int ROWS, int NW>
+__device__ __forceinline__ void dma_offsets(int64_t row0, int64_t limit, int64_t ld_bytes, int wave, int lane, uint32_t (&off)[ROWS / 8 / NW])
+{
+#pragma unroll
+    for (int j = 0; j < ROWS / 8 / NW; ++j) {
+        const int row = (wave * (ROWS / 8 / NW) + j) * 8 + (lane >> 3);
+        int64_t g = row0 + row;
+        if (g >= limit) g = limit - 1;                       // ragged edge: fetch a valid row, never stored
+        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+        off[j] = (uint32_t)((g - row0) * ld_bytes + piece * 16);
+    }
+}
+
+// One global -> LDS transfer instruction: lane l moves 16 (or 4) bytes from base + off to lds + 16*l (4*l).
+// `base` and `lds` must be wavefront-uniform.  Written as inline assembly on purpose: with the compiler's own
+// builtin in a loop, its wait-count pass treats the LDS counter as out of order and turns every wait for an
+// LDS read into lgkmcnt(0), which serialises the operand reads with the arithmetic.  The price is that the
+// compiler does not count these transfers in vmcnt: every wait for them below is written by hand.
+__device__ __forceinline__ void lds_dma16(const uint8_t* base, uint32_t off, const uint8_t* lds)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(l) : "m0");
+}
+__device__ __forceinline__ void lds_dma4(const uint8_t* base, uint32_t off, const uint8_t* lds)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(l) : "m0");
+}
+
+// The same transfer with a full 64-bit address per lane (for gathers that a base + 32-bit offset cannot express).
+__device__ __forceinline__ void lds_dma16_addr(const uint8_t* addr, const uint8_t* lds)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(l) : "m0");
+}
+
+// 128 zero bytes: the source of B rows that fall into a convolution's padding or past the last output pixel.
+__device__ __attribute__((aligned(128))) const uint8_t k_zero_row[128] = {};
+
+// Position of a K step inside a convolution's inner dimension k = (r*S + s)*C + c: a step (128 bytes of K) lies
+// inside one filter tap when C * element size is a multiple of 128 bytes.
+struct ConvTap {
+    int r, s, c0;
+    __device__ __forceinline__ void next(const ConvGeom& g, int bk)
+    {
+        c0 += bk;
+        if (c0 == g.C) {
+            c0 = 0;
+            if (++s == g.S) { s = 0; ++r; }
+        }
+    }
+};
+
+// B rows of a convolution read as an implicit GEMM (Sec. 3.2; inner dimension C x R x S, Sec. 4.2): row n of the
+// operand is output pixel n, and its 128 bytes of a step are 128 contiguous bytes of the NHWC input at the
+// pixel that filter tap (r, s) meets -- or zeros when that pixel is padding.  Per lane and transfer: the input
+// coordinates of tap (0, 0) and the byte offset of that (possibly virtual) pixel, swizzle piece included.
+template <int ROWS, int NW, int ES>
+struct conv_rows {
+    static constexpr int NJ = ROWS / 8 / NW;
+    int iy0[NJ], ix0[NJ];
+    int32_t off[NJ];
+    __device__ __forceinline__ void init(const ConvGeom& g, int64_t n0, int64_t N, int wave, int lane)
+    {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int row = (wave * NJ + j) * 8 + (lane >> 3);
+            const int piece = (lane & 7) ^ ((row >> 1) & 7);
+            const int64_t n = n0 + row;
+            if (n < N) {
+                const int t = (int)(n / g.OW), ox = (int)(n - (int64_t)t * g.OW);
+                const int img = t / g.OH, oy = t - img * g.OH;
+                iy0[j] = oy * g.stride_h - g.pad_h;
+                ix0[j] = ox * g.stride_w - g.pad_w;
+                off[j] = (((img * g.H + iy0[j]) * g.W + ix0[j]) * g.C) * ES + piece * 16;
+            } else {                                       // past the last pixel: always zeros, never stored
+                iy0[j] = -(1 << 24);
+                ix0[j] = 0;
+                off[j] = 0;
+            }
+        }
+    }
+    // transfer j of this wavefront for the step at tap t
+    __device__ __forceinline__ void issue(int j, const uint8_t* X, const ConvGeom& g, const ConvTap& t, uint8_t* stage, int wave) const
+    {
+        const int tap_off = ((t.r * g.W + t.s) * g.C + t.c0) * ES;
+        // branch-free select between the pixel and the zero row (a divergent branch per transfer costs far more)
+        const uint64_t inside = (uint64_t)((unsigned)(iy0[j] + t.r) < (unsigned)g.H) & (uint64_t)((unsigned)(ix0[j] + t.s) < (unsigned)g.W);
+        const uint64_t mask = (uint64_t)0 - inside;
+        const uint64_t pixel = reinterpret_cast<uint64_t>(X) + (uint32_t)(off[j] + tap_off);
+        const uint64_t src = (pixel & mask) | (reinterpret_cast<uint64_t>(k_zero_row) & ~mask);
+        lds_dma16_addr(reinterpret_cast<const uint8_t*>(src), stage + (wave * NJ + j) * 1024);
+    }
+};
+
+template <int ROWS, int NW>
+__device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&off)[ROWS / 8 / NW], uint8_t* stage, int wave)
+{
+#pragma unroll
+    for (int j = 0; j < ROWS / 8 / NW; ++j) lds_dma16(base, off[j], stage + (wave * (ROWS / 8 / NW) + j) * 1024);
+}
+
+// Epilogue of the tiled kernels.  A wavefront's accumulators hold, per 32x32 tile, 32 consecutive columns of
+// one row per register -- 64- or 128-byte pieces when stored directly.  Instead each 32-row block of the
+// wavefront's tile is written to LDS as a row-major image in the output type and read back 16 bytes per lane,
+// so that a store instruction covers whole rows of the wavefront's tile (256 or 512 contiguous bytes each).
+// `scratch` is this wavefront's own 32 x kPitch bytes; the direct path serves outputs that are not 16-byte tileable.
+template <int OUT, int TN>
+struct epilogue_geometry {
+    static constexpr int kOsz = (OUT == SP24_F32 || OUT == SP24_I32) ? 4 : 2;
+    static constexpr int kRowBytesOut = 32 * TN * kOsz;
+    static constexpr int kPitch = kRowBytesOut + (kOsz == 4 ? 32 : 16);   // 4 rows apart = half a bank row apart
+    static constexpr int kWaveBytes = 32 * kPitch;
+};
+
+template <int DT, int OUT, int TM, int TN>
+__device__ __forceinline__ void store_wave_tile(const MmArgs& a, typename acc_of<DT>::type (&acc)[TM][TN], uint8_t* scratch,
+                                                int64_t row_base, int64_t col_base, int lane)
+{
+    using G = epilogue_geometry<OUT, TN>;
+    constexpr int kOsz = G::kOsz, kPitch = G::kPitch;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(a.D) & 15u) == 0 && (a.ldd * kOsz) % 16 == 0 && a.N % (16 / kOsz) == 0;
+    if (!vec_ok) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) store_tile<DT, OUT>(a.D, a.ldd, row_base + i * 32, col_base + j * 32, a.M, a.N, acc[i][j], lane);
+        return;
+    }
+    const int r = lane & 31, q = lane >> 5;
+    constexpr int kChunksPerRow = G::kRowBytesOut / 16;
+    uint8_t* Dp = reinterpret_cast<uint8_t*>(a.D);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                uint8_t* p = scratch + (8 * (e / 4) + 4 * q + (e % 4)) * kPitch + (j * 32 + r) * kOsz;
+                if constexpr (DT == SP24_I8) *reinterpret_cast<int32_t*>(p) = acc[i][j][e];
+                else if constexpr (OUT == SP24_F32) *reinterpret_cast<float*>(p) = acc[i][j][e];
+                else if constexpr (OUT == SP24_F16) *reinterpret_cast<uint16_t*>(p) = f32_to_f16_bits(acc[i][j][e]);
+                else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16_bits(acc[i][j][e]);
+            }
+#pragma unroll
+        for (int it = 0; it < 32 * kChunksPerRow / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int row = idx / kChunksPerRow, c = idx % kChunksPerRow;
+            const uint4v v = *reinterpret_cast<const uint4v*>(scratch + row * kPitch + c * 16);
+            const int64_t grow = row_base + i * 32 + row, gcol = col_base + c * (16 / kOsz);
+            // D is written once and not read again here: stores that bypass L2 allocation leave the L2 to the A and
+            // B panels that neighbouring tiles share
+            if (grow < a.M && gcol < a.N) __builtin_nontemporal_store(v, reinterpret_cast<uint4v*>(Dp + (grow * a.ldd + gcol) * kOsz));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Sparse kernel.  Stage layout: [B: BN rows x 128 B, swizzled][V: 2 KiB per
+// 32-row block, in the tiled layout's own order][meta: 256 B per 32x64 tile].
+// NS stages; the transfers for step s+NS-1 are issued during step s, and the
+// first operands of step s+1 are read from LDS during the tail of step s.
+// ---------------------------------------------------------------------------
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, bool CONV>
+__global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int tiles_n)
+{
+    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int BK = kRowBytes / ES;        // K elements per step
+    constexpr int T64 = BK / 64;              // 32x64 A tiles per step and row block (2 for int8, 1 for 16-bit)
+    constexpr int NW = WM * WN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    constexpr int RB = BM / 32;               // row blocks per workgroup tile
+    constexpr int NJB = BN / 8 / NW;          // B transfers per wavefront and step (1 KiB each)
+    constexpr int NJV = RB * 2 / NW;          // V transfers (1 KiB each)
+    constexpr int NJM = RB * T64 / NW;        // metadata transfers (256 B each)
+    static_assert(RB * T64 % NW == 0 && BN % (8 * NW) == 0, "transfers must divide evenly over the wavefronts");
+    constexpr int NV = NJB + NJV + NJM;
+    constexpr int kVOff = BN * kRowBytes, kMOff = kVOff + RB * 2048;
+    constexpr int kStageBytes = kMOff + RB * T64 * 256;
+    using acc_t = typename acc_of<DT>::type;
+    constexpr int kEpiBytes = NW * epilogue_geometry<OUT, TN>::kWaveBytes;
+    static_assert(NS >= 3 && (NS - 2) * NV <= 63, "at least three stages; vmcnt is a 6-bit counter");
+    constexpr int kLdsBytes = NS * kStageBytes > kEpiBytes ? NS * kStageBytes : kEpiBytes;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_all[kLdsBytes];
+
+    int tm, tn;
+    tile_of_workgroup(tiles_m, tiles_n, tm, tn);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int r = lane & 31, q = lane >> 5;
+    const int64_t KB64 = a.K / 64;
+    const int nsteps = (int)(a.K / BK);
+    const int64_t rb_total = a.M / 32;
+
+    // ---- transfers of this wavefront ----
+    const int64_t ldb_bytes = a.ldb * ES;
+    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
+    uint32_t b_off[NJB];
+    conv_rows<BN, NW, ES> b_conv;
+    if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
+    else dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+    // V: transfer x of this wavefront is 1 KiB number (wave*NJV + x) of the RB*2 of a step: row block /2, half %2
+    const uint8_t* v_base[NJV];                            // wavefront-uniform; lane l adds 16*l
+#pragma unroll
+    for (int x = 0; x < NJV; ++x) {
+        const int id = wave * NJV + x;
+        int64_t rb = (int64_t)tm * RB + (id >> 1);
+        if (rb >= rb_total) rb = rb_total - 1;             // ragged M: compute on a valid row block, never stored
+        v_base[x] = reinterpret_cast<const uint8_t*>(a.A) + rb * KB64 * (1024 * ES) + (id & 1) * 1024;
+    }
+    // metadata: transfer x is 256-byte tile number (wave*NJM + x) of the RB*T64 of a step
+    const uint8_t* m_base[NJM];                            // wavefront-uniform; lane l adds 4*l
+#pragma unroll
+    for (int x = 0; x < NJM; ++x) {
+        const int id = wave * NJM + x;
+        int64_t rb = (int64_t)tm * RB + id / T64;
+        if (rb >= rb_total) rb = rb_total - 1;
+        m_base[x] = reinterpret_cast<const uint8_t*>(a.meta) + (rb * KB64 + id % T64) * 256;
+    }
+    const uint32_t lane16 = lane * 16, lane4 = lane * 4;
+
+    auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
+    // transfer number x (0 .. NV-1) of this wavefront for a step: B rows, then values, then codes
+    // (convolution: `tap` is the position of `step` in the inner dimension)
+    auto dma_one = [&](int step, const ConvTap& tap, int u, int x) {
+        uint8_t* stg = stage_ptr(u);
+        if (x < NJB) {
+            if constexpr (CONV) b_conv.issue(x, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stg, wave);
+            else lds_dma16(b_blk + (int64_t)step * kRowBytes, b_off[x], stg + (wave * NJB + x) * 1024);
+        }
+        else if (x < NJB + NJV) lds_dma16(v_base[x - NJB] + (int64_t)step * 2048, lane16, stg + kVOff + (wave * NJV + x - NJB) * 1024);
+        else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * (T64 * 256), lane4, stg + kMOff + (wave * NJM + x - NJB - NJV) * 256);
+    };
+    auto dma = [&](int step, const ConvTap& tap, int u) {
+#pragma unroll
+        for (int x = 0; x < NV; ++x) dma_one(step, tap, u, x);
+    };
+    // the step whose transfers are issued next, kept NS - 1 ahead of the arithmetic.  It stops at the last step:
+    // past the end that step is fetched again into a stage nobody reads, which keeps the counts uniform.
+    int f_step = 0;
+    ConvTap f_tap = {0, 0, 0};
+    auto advance_fetch = [&]() {
+        if (f_step + 1 < nsteps) {
+            ++f_step;
+            if constexpr (CONV) f_tap.next(a.conv, BK);
+        }
+    };
+
+    acc_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = acc_t{};
+
+    // B fragment read offsets: row (wn*32*TN + nj*32 + r), piece c = 2*c2 + q at slot c ^ ((r >> 1) & 7)
+    int frag_off[4];
+#pragma unroll
+    for (int c2 = 0; c2 < 4; ++c2) frag_off[c2] = (wn * 32 * TN + r) * kRowBytes + ((((2 * c2) | q) ^ ((r >> 1) & 7)) << 4);
+    const int va_off = kVOff + wm * TM * 2048 + lane * 16;
+    const int ma_off = kMOff + wm * TM * T64 * 256 + lane * 4;
+
+    // Operand reads from a stage.  A operands of matrix-core instruction j of the step: values (row block i,
+    // half j), codes (int8: tile j; 16-bit: the one tile, the instruction picks its half through abid).
+    auto read_a = [&](const uint8_t* base, int j, int4v (&xa)[TM], int (&xm)[TM], bool with_codes) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            xa[i] = *reinterpret_cast<const int4v*>(base + va_off + (i * 2 + j) * 1024);
+            if (with_codes) xm[i] = *reinterpret_cast<const int*>(base + ma_off + (i * T64 + (DT == SP24_I8 ? j : 0)) * 256);
+        }
+    };
+    auto read_frag = [&](const uint8_t* base, int t, int8v& bv) {
+        const int j = t / TN, nj = t % TN;
+        // K-byte offset of the two pieces of instruction j: (int8) 64j + 32h + 16q, (16-bit) 64h + 32j + 16q
+        const int c2lo = (DT == SP24_I8) ? 2 * j : j, c2hi = (DT == SP24_I8) ? 2 * j + 1 : 2 + j;
+        uint4v lo = *reinterpret_cast<const uint4v*>(base + frag_off[c2lo] + nj * 32 * kRowBytes);
+        uint4v hi = *reinterpret_cast<const uint4v*>(base + frag_off[c2hi] + nj * 32 * kRowBytes);
+        bv[0] = lo[0]; bv[1] = lo[1]; bv[2] = lo[2]; bv[3] = lo[3];
+        bv[4] = hi[0]; bv[5] = hi[1]; bv[6] = hi[2]; bv[7] = hi[3];
+    };
+
+    // Operands carried from the tail of one step into the next: A operands of instruction 0, fragments 0 and 1.
+    int4v a_first[TM];
+    int m_first[TM];
+    int8v f_first[2];
+
+    // One step (stage u holds its operands; fragments t = 0 .. NF-1, TM instructions each).  LDS reads run two
+    // fragments ahead of the arithmetic.
+    //   barrier 0: every wavefront has finished the previous step, so the stage it read is free:
+    //              the transfers for step s+2 go there, dealt out between the instructions of t < T1;
+    //   barrier 1 (before t = T1): this wavefront's transfers for step s+1 have landed (vmcnt counts in order:
+    //              only the NV just issued may still be in flight), the barrier makes everybody's visible;
+    //   t >= T1:   the first operands of step s+1 are read while the last instructions of step s run, so that
+    //              no wavefront starts a step waiting for LDS.
+    constexpr int NF = 2 * TN, T1 = NF - 2;
+    constexpr int kWait = waitcnt_vm((NS - 2) * NV);
+    auto do_step = [&](int u) {
+        const uint8_t* cur = stage_ptr(u);
+        const uint8_t* nxt = stage_ptr((u + 1) % NS);
+        int4v av[2][TM];
+        int mv[2][TM];
+        int8v f[3];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) { av[0][i] = a_first[i]; mv[0][i] = m_first[i]; }
+        f[0] = f_first[0];
+        f[1] = f_first[1];
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NF; ++t) {
+            const int j = t / TN, nj = t % TN;
+            if (t == T1) {
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(kWait);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (t + 2 < NF) read_frag(cur, t + 2, f[(t + 2) % 3]);
+            else read_frag(nxt, t + 2 - NF, f_first[t + 2 - NF]);
+            if (t == 0) read_a(cur, 1, av[1], mv[1], DT == SP24_I8);
+            if (t == T1) read_a(nxt, 0, a_first, m_first, true);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t % 3], acc[i][nj], mv[j][i]);
+                else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], f[t % 3], acc[i][nj], mv[0][i]);
+                else acc[i][nj] = smfmac32<DT, 1>(av[1][i], f[t % 3], acc[i][nj], mv[0][i]);
+                if (t < T1) {
+                    const int m = t * TM + i;
+#pragma unroll
+                    for (int x = m * NV / (T1 * TM); x < (m + 1) * NV / (T1 * TM); ++x) dma_one(f_step, f_tap, (u + NS - 1) % NS, x);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        advance_fetch();
+    };
+
+    // prologue: the first NS - 1 stages on their way; first operands of step 0 once stage 0 has landed
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u) {
+        dma(f_step, f_tap, u);
+        advance_fetch();
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWait);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    read_a(lds_all, 0, a_first, m_first, true);
+    read_frag(lds_all, 0, f_first[0]);
+    read_frag(lds_all, 1, f_first[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    // NS steps per iteration, so that stage indices are compile-time constants; the remainder runs after the loop
+    int step = 0;
+    for (; step + NS <= nsteps; step += NS) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) do_step(u);
+    }
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u)
+        if (step + u < nsteps) do_step(u);
+    // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    store_wave_tile<DT, OUT, TM, TN>(a, acc, lds_all + wave * epilogue_geometry<OUT, TN>::kWaveBytes,
+                                     (int64_t)tm * BM + wm * TM * 32, (int64_t)tn * BN + wn * TN * 32, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Dense kernel: the speedup denominator (Sec. 3.2, Fig. 3).  A and B both go
+// through LDS (A is plain row-major, so its fragments are not contiguous in
+// memory); NS stages, transfers NS - 1 steps ahead.
+// ---------------------------------------------------------------------------
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, bool CONV>
+__global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int tiles_n)
+{
+    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int BK = kRowBytes / ES;
+    constexpr int NW = WM * WN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    constexpr int NJA = BM / 8 / NW, NJB = BN / 8 / NW;
+    constexpr int kStageBytes = (BM + BN) * kRowBytes;
+    using acc_t = typename acc_of<DT>::type;
+    constexpr int kEpiBytes = NW * epilogue_geometry<OUT, TN>::kWaveBytes;
+    static_assert(NS >= 2 && (NS - 2) * (NJA + NJB) <= 63, "at least two stages; vmcnt is a 6-bit counter");
+    constexpr int kLdsBytes = NS * kStageBytes > kEpiBytes ? NS * kStageBytes : kEpiBytes;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds_all[kLdsBytes];
+
+    int tm, tn;
+    tile_of_workgroup(tiles_m, tiles_n, tm, tn);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int r = lane & 31, q = lane >> 5;
+    const int nsteps = (int)(a.K / BK);
+
+    const int64_t lda_bytes = a.lda * ES, ldb_bytes = a.ldb * ES;
+    const uint8_t* a_blk = reinterpret_cast<const uint8_t*>(a.A) + (int64_t)tm * BM * lda_bytes;
+    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
+    uint32_t a_off[NJA], b_off[NJB];
+    dma_offsets<BM, NW>((int64_t)tm * BM, a.M, lda_bytes, wave, lane, a_off);
+    conv_rows<BN, NW, ES> b_conv;
+    if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
+    else dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+
+    acc_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = acc_t{};
+
+    auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
+    // (convolution: `tap` is the position of `step` in the inner dimension)
+    auto dma = [&](int step, const ConvTap& tap, int u) {
+        dma_rows<BM, NW>(a_blk + (int64_t)step * kRowBytes, a_off, stage_ptr(u), wave);
+        if constexpr (CONV) {
+#pragma unroll
+            for (int j = 0; j < NJB; ++j)
+                b_conv.issue(j, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stage_ptr(u) + BM * kRowBytes, wave);
+        } else dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u) + BM * kRowBytes, wave);
+    };
+    // the step whose transfers are issued next, NS - 1 ahead of the arithmetic; it stops at the last step, which
+    // is then fetched again into stages nobody reads
+    int f_step = 0;
+    ConvTap f_tap = {0, 0, 0};
+    auto advance_fetch = [&]() {
+        if (f_step + 1 < nsteps) {
+            ++f_step;
+            if constexpr (CONV) f_tap.next(a.conv, BK);
+        }
+    };
+
+    // fragment of instruction jj (k-bytes 32*jj .. +31 of the step): lane reads piece 2*jj + q of its row
+    int fa_off[4], fb_off[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        const int slot = (((2 * jj) | q) ^ ((r >> 1) & 7)) << 4;
+        fa_off[jj] = (wm * 32 * TM + r) * kRowBytes + slot;
+        fb_off[jj] = (BM + wn * 32 * TN + r) * kRowBytes + slot;
+    }
+
+    auto compute = [&](int u) {
+        const uint8_t* base = stage_ptr(u);
+        int4v fa[2][TM], fb[2][TN];
+        auto read_frags = [&](int jj, int4v (&xa)[TM], int4v (&xb)[TN]) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) xa[i] = *reinterpret_cast<const int4v*>(base + fa_off[jj] + i * 32 * kRowBytes);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) xb[j] = *reinterpret_cast<const int4v*>(base + fb_off[jj] + j * 32 * kRowBytes);
+        };
+        read_frags(0, fa[0], fb[0]);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            if (jj + 1 < 4) read_frags(jj + 1, fa[(jj + 1) & 1], fb[(jj + 1) & 1]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[i][j] = mfma32<DT>(fa[jj & 1][i], fb[jj & 1][j], acc[i][j]);
+        }
+    };
+
+    constexpr int NMFMA = 4 * TM * TN, NV = NJA + NJB;
+    auto do_step = [&](int u) {
+        // this wavefront's share of stage u has landed (vmcnt counts in issue order: only the transfers of the
+        // NS - 2 later steps may still be in flight) ...
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 2) * NV));
+        __builtin_amdgcn_s_barrier();                // ... and everybody's; the stage read in the previous step is free
+        __builtin_amdgcn_sched_barrier(0);
+        dma(f_step, f_tap, (u + NS - 1) % NS);
+        advance_fetch();
+        compute(u);
+        __builtin_amdgcn_sched_group_barrier(kSgDsRead, TM + TN, 0);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            if (jj + 1 < 4) __builtin_amdgcn_sched_group_barrier(kSgDsRead, TM + TN, 0);
+#pragma unroll
+            for (int i = 0; i < TM * TN; ++i) {
+                __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
+                if ((jj * TM * TN + i) % (NMFMA / NV) == 0) __builtin_amdgcn_sched_group_barrier(kSgVmem, 1, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u) {
+        dma(f_step, f_tap, u);
+        advance_fetch();
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    int step = 0;
+    for (; step + NS <= nsteps; step += NS) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) do_step(u);
+    }
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u)
+        if (step + u < nsteps) do_step(u);
+    // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    store_wave_tile<DT, OUT, TM, TN>(a, acc, lds_all + wave * epilogue_geometry<OUT, TN>::kWaveBytes,
+                                     (int64_t)tm * BM + wm * TM * 32, (int64_t)tn * BN + wn * TN * 32, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Host side.
+// ---------------------------------------------------------------------------
+// NSS / NSD: pipeline stages of the sparse / dense kernel
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NSS, int NSD>
+static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
+{
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WM * WN);
+    if (a.sparse) {
+        if (a.conv.on) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, true><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, false><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    } else {
+        if (a.conv.on) k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, true><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, false><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    }
+    return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;
+}
+
+template <int DT, int OUT>
+static sp24_status pick_tile(const MmArgs& a, hipStream_t st)
+{
+    // 256x256 tiles when they still fill the 256 compute units, else 128x128
+    const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+    // eight wavefronts of 64x128 each (two per SIMD, so that one computes while the other waits); measured
+    // faster than four of 128x128 on the short-K transformer shape and equal on the long-K square one
+    if (big >= 200) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
+    // 128x128 tiles, four wavefronts.  With few tiles one workgroup per compute unit is all there is, and a short
+    // step (a quarter of the large tile's arithmetic) hides little latency: six (dense: four) stages, transfers
+    // five (three) steps ahead.  With many tiles three (two) stages leave room for two workgroups per compute unit.
+    const int64_t small = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+    if (small <= 256) return run_pipe<DT, OUT, 2, 2, 2, 2, 6, 4>(a, st);
+    return run_pipe<DT, OUT, 2, 2, 2, 2, 3, 2>(a, st);
+}
+
+} // namespace sp24
