@@ -28,7 +28,7 @@ def build(force=False):
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-std=c11", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+            ["gcc", "-O2", "-fopenmp", "-std=c11", "-ffp-contract=off", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 
@@ -45,6 +45,9 @@ def _load():
         lib.sp24o_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64]
         lib.sp24o_conv2d_f64.argtypes = [vp, vp, vp] + [i64] * 11 + [i32]
         lib.sp24o_conv2d_i32.argtypes = [vp, vp, vp] + [i64] * 11
+        f32 = ctypes.c_float
+        lib.sp24o_dequant_f64.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32]
+        lib.sp24o_requant_i8.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32, f32]
         lib.sp24o_f16_to_double.argtypes = [ctypes.c_uint16]
         lib.sp24o_f16_to_double.restype = ctypes.c_double
         lib.sp24o_bf16_to_double.argtypes = [ctypes.c_uint16]
@@ -151,6 +154,38 @@ def conv2d(P, X, dtype, R, S, pad=(0, 0), stride=(1, 1)):
     if rc:
         raise ValueError("oracle conv2d: illegal geometry")
     return D
+
+
+def _scales(acc, w_scale, bias):
+    if acc.dtype != np.int32 or acc.ndim != 2 or not acc.flags.c_contiguous:
+        raise ValueError("acc must be a C-contiguous int32 matrix")
+    w = np.ascontiguousarray(w_scale, dtype=np.float32)
+    if w.shape != (acc.shape[0],):
+        raise ValueError("one weight scale per row")
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    if b is not None and b.shape != w.shape:
+        raise ValueError("one bias per row")
+    return w, b
+
+
+def dequant(acc, w_scale, x_scale, bias=None, relu=False):
+    """Epilogue of the quantised path in double: acc * (w_scale[m] * x_scale) + bias[m], optional ReLU (Sec. 5:
+    per-row weight scales, per-tensor activation scale)."""
+    w, b = _scales(acc, w_scale, bias)
+    Y = np.empty(acc.shape, dtype=np.float64)
+    _load().sp24o_dequant_f64(_ptr(acc), _ptr(Y), acc.shape[0], acc.shape[1], _ptr(w), float(np.float32(x_scale)),
+                              None if b is None else _ptr(b), int(bool(relu)))
+    return Y
+
+
+def requant(acc, w_scale, x_scale, inv_y_scale, bias=None, relu=False):
+    """The same epilogue re-quantised to int8 with a per-tensor output scale, the rounding decision taken in
+    binary32 (one product for the scale, one fused multiply-add, one product, round half to even, clamp)."""
+    w, b = _scales(acc, w_scale, bias)
+    Q = np.empty(acc.shape, dtype=np.int8)
+    _load().sp24o_requant_i8(_ptr(acc), _ptr(Q), acc.shape[0], acc.shape[1], _ptr(w), float(np.float32(x_scale)),
+                             None if b is None else _ptr(b), int(bool(relu)), float(np.float32(inv_y_scale)))
+    return Q
 
 
 def spmm(V, meta, B, dtype):

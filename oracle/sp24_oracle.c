@@ -308,6 +308,61 @@ int sp24o_conv2d_i32(const int8_t *P, const int8_t *X, int32_t *D, long M, long 
 #undef LX
 }
 
+/*
+ * ---- O6: epilogue of the quantised path ----------------------------------
+ * The paper's INT8 recipe (Sec. 5, image classification and translation
+ * paragraphs) fixes the granularity of the scaling factors: one per tensor
+ * for activations, one per row of the weight matrix (= per output channel of
+ * a convolution).  It prints no formula; the one used here is the plain
+ * de-quantisation of an integer product, optionally followed by bias, ReLU
+ * and re-quantisation with a per-tensor output scale:
+ *     s_m  = w_scale[m] * x_scale
+ *     y_mn = acc_mn * s_m + bias[m]          (bias = 0 when absent)
+ *     y_mn = max(y_mn, 0)                    (when relu)
+ *     q_mn = clamp(round_half_even(y_mn * inv_y_scale), -128, 127)
+ * sp24o_dequant_f64 evaluates y in double (the reference for floating-point
+ * outputs).  sp24o_requant_i8 produces q: a rounding decision, so it is taken
+ * in the arithmetic the device uses -- binary32, s_m by one multiplication,
+ * y by one fused multiply-add of float(acc), max, one multiplication by
+ * inv_y_scale, round to nearest even, clamp.
+ */
+#include <math.h>
+
+int sp24o_dequant_f64(const int32_t *acc, double *Y, long M, long N, const float *w_scale,
+                      float x_scale, const float *bias, int relu)
+{
+    for (long m = 0; m < M; ++m) {
+        double s = (double)w_scale[m] * (double)x_scale;
+        double b = bias ? (double)bias[m] : 0.0;
+        for (long n = 0; n < N; ++n) {
+            double y = (double)acc[m * N + n] * s + b;
+            if (relu && y < 0.0)
+                y = 0.0;
+            Y[m * N + n] = y;
+        }
+    }
+    return 0;
+}
+
+int sp24o_requant_i8(const int32_t *acc, int8_t *Q, long M, long N, const float *w_scale,
+                     float x_scale, const float *bias, int relu, float inv_y_scale)
+{
+    for (long m = 0; m < M; ++m) {
+        volatile float s = w_scale[m] * x_scale;       /* one binary32 product */
+        float b = bias ? bias[m] : 0.0f;
+        for (long n = 0; n < N; ++n) {
+            float y = fmaf((float)acc[m * N + n], s, b);
+            if (relu)
+                y = fmaxf(y, 0.0f);
+            volatile float t = y * inv_y_scale;        /* one binary32 product */
+            float r = nearbyintf(t);                   /* default rounding mode: to nearest even */
+            r = fminf(fmaxf(r, -128.0f), 127.0f);
+            Q[m * N + n] = (int8_t)(int)r;
+        }
+    }
+    return 0;
+}
+
 int sp24o_threads(void)
 {
 #ifdef _OPENMP

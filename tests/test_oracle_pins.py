@@ -465,3 +465,55 @@ def test_conv_workload_matrix_is_the_im2col_of_its_activations():
     d1 = oracle.conv2d(P, X, "f16", 3, 3, (1, 1), (1, 1))
     d2 = oracle.gemm(P, np.ascontiguousarray(Bt.T), "f16")
     assert np.allclose(d1, d2, rtol=1e-12, atol=1e-12)
+
+
+# ---- epilogue of the quantised path -------------------------------------------------------------------------
+
+def test_requant_with_unit_scales_is_a_saturating_copy():
+    acc = np.array([[-300, -129, -128, -1, 0, 1, 127, 128, 300]], dtype=np.int32)
+    q = oracle.requant(acc, [1.0], 1.0, 1.0)
+    assert q.tolist() == [[-128, -128, -128, -1, 0, 1, 127, 127, 127]]
+    assert oracle.requant(acc, [1.0], 1.0, 1.0, relu=True).tolist() == [[0, 0, 0, 0, 0, 1, 127, 127, 127]]
+
+
+def test_requant_power_of_two_scales_round_half_to_even():
+    # exact arithmetic: acc / 8 with ties at .5 -> even
+    acc = np.arange(-44, 45, 4, dtype=np.int32).reshape(1, -1)            # -5.5, -5.0, ... 5.5
+    q = oracle.requant(acc, [0.25], 0.5, 1.0)
+    want = [int(np.round(v / 8.0)) for v in acc[0]]                       # numpy rounds half to even
+    assert q[0].tolist() == want
+    assert oracle.requant(np.array([[4, 12, 20, 28]], dtype=np.int32), [0.125], 1.0, 1.0).tolist() == [[0, 2, 2, 4]]
+    # per-row scale and bias
+    acc2 = np.array([[10, 20], [10, 20]], dtype=np.int32)
+    q2 = oracle.requant(acc2, [1.0, 2.0], 0.5, 0.5, bias=[1.0, -4.0])     # row 0: (5+1)/2, (10+1)/2=5.5->6 ; row 1: (10-4)/2, (20-4)/2
+    assert q2.tolist() == [[3, 6], [3, 8]]
+
+
+def test_requant_agrees_with_the_double_formula_away_from_rounding_boundaries():
+    rng = np.random.default_rng(21)
+    M, N = 64, 300
+    acc = rng.integers(-2_000_000, 2_000_000, size=(M, N)).astype(np.int32)
+    w = rng.uniform(1e-5, 3e-4, size=M).astype(np.float32)
+    bias = rng.normal(0, 20, size=M).astype(np.float32)
+    x_scale, inv_y = np.float32(0.037), np.float32(1 / 0.9)
+    for relu in (False, True):
+        y = oracle.dequant(acc, w, x_scale, bias, relu)
+        # closed form of the double evaluation
+        ref = acc.astype(np.float64) * (w.astype(np.float64) * np.float64(x_scale))[:, None] + bias.astype(np.float64)[:, None]
+        if relu:
+            ref = np.maximum(ref, 0.0)
+        assert np.allclose(y, ref, rtol=1e-15, atol=0)
+        t = ref * np.float64(inv_y)
+        q = oracle.requant(acc, w, x_scale, inv_y, bias, relu)
+        safe = np.abs(t - np.floor(t) - 0.5) > 1e-3                       # binary32 error here is < 2e-4
+        want = np.clip(np.rint(t), -128, 127).astype(np.int8)
+        assert safe.mean() > 0.99
+        assert np.array_equal(q[safe], want[safe])
+        assert np.all(np.abs(q.astype(np.int32) - want.astype(np.int32)) <= 1)
+
+
+def test_requant_is_monotone_and_odd_without_bias():
+    acc = np.arange(-5000, 5001, dtype=np.int32).reshape(1, -1)
+    q = oracle.requant(acc, [0.0213], 1.7, 0.31).astype(np.int32)[0]
+    assert np.all(np.diff(q) >= 0)
+    assert np.array_equal(np.clip(q, -127, 127), -np.clip(q[::-1], -127, 127))
