@@ -63,7 +63,7 @@ typedef enum {
 typedef enum {
     SP24_F16 = 0,  /* IEEE binary16                                   */
     SP24_BF16 = 1, /* bfloat16                                        */
-    SP24_I8 = 2,   /* signed 8-bit integer                            */
+    SP24_I8 = 2,   /* signed 8-bit integer (as output: sp24_*_i8_scaled only) */
     SP24_F32 = 3,  /* output only                                     */
     SP24_I32 = 4   /* output only (required for SP24_I8 inputs)       */
 } sp24_dtype;
@@ -185,6 +185,33 @@ sp24_status sp24_conv2d_dense(const void* A, const void* X, void* D, int64_t M, 
                               int64_t H, int64_t W, int64_t C, int R, int S, int pad_h, int pad_w,
                               int stride_h, int stride_w, int64_t lda, int64_t ldd, sp24_dtype in,
                               sp24_dtype out, void* stream);
+
+/*
+ * The INT8 deployment path (Sec. 5: activations carry one scaling factor per
+ * tensor, weights one per row of the weight matrix, i.e. per output channel):
+ * the int8 sparse product with its de-quantisation fused into the store.
+ * For accumulator acc (int32, exact) of row m:
+ *     s = w_scale[m] * x_scale
+ *     y = fma(float(acc), s, bias[m])        bias = NULL means 0
+ *     y = max(y, 0)                          when relu != 0
+ * `out` = SP24_F32, SP24_F16 or SP24_BF16 stores y (one rounding to nearest
+ * even); `out` = SP24_I8 stores clamp(rint(y * inv_y_scale), -128, 127) with
+ * rint rounding half to even.  Every step is one binary32 operation, so the
+ * int8 result is uniquely defined.  Scales and bias must be finite.
+ * V, meta, B, D, shapes, layouts: as for sp24_spmm with int8 inputs.
+ * w_scale, bias: device, M floats each, 4-byte aligned, not overlapping D.
+ * inv_y_scale is ignored unless out = SP24_I8.
+ */
+sp24_status sp24_spmm_i8_scaled(const void* V, const void* meta, const void* B, void* D, int64_t M,
+                                int64_t N, int64_t K, int64_t ldb, int64_t ldd, const float* w_scale,
+                                float x_scale, const float* bias, int relu, float inv_y_scale,
+                                sp24_dtype out, sp24_border bo, sp24_layout l, void* stream);
+
+/* The same epilogue on the dense int8 product D = A x B (speedup denominator of the quantised path). */
+sp24_status sp24_gemm_dense_i8_scaled(const void* A, const void* B, void* D, int64_t M, int64_t N,
+                                      int64_t K, int64_t lda, int64_t ldb, int64_t ldd,
+                                      const float* w_scale, float x_scale, const float* bias, int relu,
+                                      float inv_y_scale, sp24_dtype out, sp24_border bo, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* sp24_status_string(sp24_status s);

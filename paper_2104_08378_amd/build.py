@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsp24.so")
 PROBE = os.path.join(HERE, "sp24_probe")        # stand-alone measurement of the chip's ceilings (csrc/probe.hip)
 SOURCES = ["api.hip", "prune_compress.hip", "mm_simple.hip", "mm_skinny.hip", "mm_tiled.hip", "mm_tiled_f16.hip", "mm_tiled_bf16.hip",
-           "mm_tiled_i8.hip"]
+           "mm_tiled_i8.hip", "mm_tiled_i8f.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # hipcc must not form packed-fp32 instructions by itself on this target

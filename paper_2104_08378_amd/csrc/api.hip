@@ -19,8 +19,9 @@ bool layout_fits(int64_t M, int64_t K, sp24_layout l)
     return l == SP24_LAYOUT_CANONICAL || (M % 32 == 0 && K % 64 == 0);
 }
 
-bool out_legal(sp24_dtype in, sp24_dtype out)
+bool out_legal(sp24_dtype in, sp24_dtype out, bool scaled)
 {
+    if (scaled) return in == SP24_I8 && (out == SP24_I8 || out == SP24_F32 || out == SP24_F16 || out == SP24_BF16);
     if (in == SP24_I8) return out == SP24_I32;
     return out == SP24_F32 || out == SP24_F16 || out == SP24_BF16;
 }
@@ -117,7 +118,7 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
 // x_bytes: extent of the NHWC input when a.conv.on (a.B then points at it), else unused
 static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
 {
-    if (!is_input_type(a.in) || !out_legal(a.in, a.out)) return SP24_ERR_DTYPE;
+    if (!is_input_type(a.in) || !out_legal(a.in, a.out, a.epi.on != 0)) return SP24_ERR_DTYPE;
     if (a.bo != SP24_B_KMAJOR && a.bo != SP24_B_NMAJOR) return SP24_ERR_LAYOUT;
     if (a.M < 0 || a.N < 0 || !k_legal(a.K, a.in)) return SP24_ERR_SHAPE;
     if (a.sparse) {
@@ -127,6 +128,10 @@ static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
     if (a.M == 0 || a.N == 0) return SP24_OK;
     int es = esize_of(a.in), os = esize_of(a.out);
     sp24_status s;
+    if (a.epi.on) {
+        if (!a.epi.w_scale) return SP24_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(a.epi.w_scale) % 4 != 0 || reinterpret_cast<uintptr_t>(a.epi.bias) % 4 != 0) return SP24_ERR_ALIGN;
+    }
     if (a.sparse) {
         if (!a.A || !a.meta) return SP24_ERR_NULL;
         if (!aligned16(a.A) || !aligned16(a.meta)) return SP24_ERR_ALIGN;
@@ -149,6 +154,9 @@ static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
     size_t nA = a.sparse ? sp24_values_bytes(a.M, a.K, a.in) : ((size_t)(a.M - 1) * a.lda + a.K) * es;
     if (ranges_overlap(a.D, nd, a.B, nb) || ranges_overlap(a.D, nd, a.A, nA)) return SP24_ERR_SHAPE;
     if (a.sparse && ranges_overlap(a.D, nd, a.meta, sp24_meta_bytes(a.M, a.K, a.in, a.layout))) return SP24_ERR_SHAPE;
+    if (a.epi.on && (ranges_overlap(a.D, nd, a.epi.w_scale, (size_t)a.M * 4) ||
+                     (a.epi.bias && ranges_overlap(a.D, nd, a.epi.bias, (size_t)a.M * 4))))
+        return SP24_ERR_SHAPE;
     bool handled = false;
     if (!a.conv.on) {
         s = launch_mm_skinny(a, st, &handled);
@@ -173,11 +181,29 @@ sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, in
     return mm_common(a, static_cast<hipStream_t>(stream));
 }
 
+sp24_status sp24_spmm_i8_scaled(const void* V, const void* meta, const void* B, void* D, int64_t M, int64_t N, int64_t K,
+                                int64_t ldb, int64_t ldd, const float* w_scale, float x_scale, const float* bias, int relu,
+                                float inv_y_scale, sp24_dtype out, sp24_border bo, sp24_layout l, void* stream)
+{
+    MmArgs a{V, meta, B, D, M, N, K, 0, ldb, ldd, SP24_I8, out, bo, l, true};
+    a.epi = Epilogue{w_scale, bias, x_scale, inv_y_scale, relu != 0, 1};
+    return mm_common(a, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_gemm_dense_i8_scaled(const void* A, const void* B, void* D, int64_t M, int64_t N, int64_t K, int64_t lda,
+                                      int64_t ldb, int64_t ldd, const float* w_scale, float x_scale, const float* bias, int relu,
+                                      float inv_y_scale, sp24_dtype out, sp24_border bo, void* stream)
+{
+    MmArgs a{A, nullptr, B, D, M, N, K, lda, ldb, ldd, SP24_I8, out, bo, SP24_LAYOUT_CANONICAL, false};
+    a.epi = Epilogue{w_scale, bias, x_scale, inv_y_scale, relu != 0, 1};
+    return mm_common(a, static_cast<hipStream_t>(stream));
+}
+
 // Shared front end of the two convolution entry points: geometry checks, then the product path with B = X.
 static sp24_status conv_common(MmArgs& a, int64_t n_img, int64_t H, int64_t W, int64_t C, int R, int S, int pad_h, int pad_w,
                                int stride_h, int stride_w, hipStream_t st)
 {
-    if (!is_input_type(a.in) || !out_legal(a.in, a.out)) return SP24_ERR_DTYPE;
+    if (!is_input_type(a.in) || !out_legal(a.in, a.out, false)) return SP24_ERR_DTYPE;
     const int64_t lim = (int64_t)1 << 20;
     if (a.M < 0 || n_img < 0 || H < 1 || W < 1 || C < 1 || R < 1 || S < 1 || pad_h < 0 || pad_w < 0 || stride_h < 1 || stride_w < 1 ||
         H > lim || W > lim || C > lim || R > 4096 || S > 4096 || pad_h > 4096 || pad_w > 4096 || stride_h > 4096 || stride_w > 4096 ||

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/sp24.h"
 
 namespace sp24 {
@@ -82,6 +84,77 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
 {
     _Float16 h = (_Float16)f; // v_cvt_f16_f32: round to nearest even
     return __builtin_bit_cast(uint16_t, h);
+}
+
+// ---------------------------------------------------------------------------
+// Epilogue of the quantised path (int8 inputs; Sec. 5: one scaling factor per
+// row of the weight matrix -- per output channel -- and one per activation
+// tensor).  For accumulator acc of row m:
+//     s = w_scale[m] * x_scale;  y = fma(float(acc), s, bias[m]);  y = max(y, 0) if relu
+// written as F32 / F16 / BF16 (one rounding), or re-quantised with a
+// per-tensor output scale: q = clamp(rint(y * inv_y_scale), -128, 127), every
+// step one binary32 operation (the rounding decision is defined in binary32).
+// ---------------------------------------------------------------------------
+struct Epilogue {
+    const float* w_scale;   // device, M values
+    const float* bias;      // device, M values, or null
+    float x_scale;
+    float inv_y_scale;      // used when the output type is SP24_I8
+    int relu;
+    int on;                 // 0: plain int32 / float output
+};
+
+// scale and bias of row m (m clamped by the caller to a valid row)
+__device__ __forceinline__ void epilogue_row(const Epilogue& e, int64_t m, float& s, float& b)
+{
+    s = e.w_scale[m] * e.x_scale;
+    b = e.bias ? e.bias[m] : 0.0f;
+}
+
+__device__ __forceinline__ float dequant_value(int acc, float s, float b, int relu)
+{
+    const float y = __builtin_fmaf((float)acc, s, b);
+    return relu ? fmaxf(y, 0.0f) : y;
+}
+
+__device__ __forceinline__ int quantise_i8(float y, float inv_y_scale)
+{
+    float r = __builtin_rintf(y * inv_y_scale);         // v_rndne_f32: ties to even
+    r = fminf(fmaxf(r, -128.0f), 127.0f);
+    return (int)r;
+}
+
+// Bits of one output element (in the low bytes of the result) for an accumulator value: the integer itself,
+// the float converted to the output type, or the quantised epilogue's result.  ACC is int (int8 inputs) or float.
+template <int OUT, typename ACC>
+__device__ __forceinline__ uint32_t output_bits(ACC acc, float s, float b, const Epilogue& e)
+{
+    if constexpr (std::is_same<ACC, int>::value) {
+        if constexpr (OUT == SP24_I32) return (uint32_t)acc;
+        else {
+            const float y = dequant_value(acc, s, b, e.relu);
+            if constexpr (OUT == SP24_I8) return (uint32_t)quantise_i8(y, e.inv_y_scale) & 0xFFu;
+            else if constexpr (OUT == SP24_F32) return __float_as_uint(y);
+            else if constexpr (OUT == SP24_F16) return f32_to_f16_bits(y);
+            else return f32_to_bf16_bits(y);
+        }
+    } else {
+        if constexpr (OUT == SP24_F32) return __float_as_uint(acc);
+        else if constexpr (OUT == SP24_F16) return f32_to_f16_bits(acc);
+        else return f32_to_bf16_bits(acc);
+    }
+}
+
+template <int OUT>
+constexpr int out_size() { return (OUT == SP24_F32 || OUT == SP24_I32) ? 4 : (OUT == SP24_I8) ? 1 : 2; }
+
+// store the low out_size<OUT>() bytes of `bits` at element idx of D
+template <int OUT>
+__device__ __forceinline__ void store_bits(void* D, int64_t idx, uint32_t bits)
+{
+    if constexpr (out_size<OUT>() == 4) reinterpret_cast<uint32_t*>(D)[idx] = bits;
+    else if constexpr (out_size<OUT>() == 2) reinterpret_cast<uint16_t*>(D)[idx] = (uint16_t)bits;
+    else reinterpret_cast<uint8_t*>(D)[idx] = (uint8_t)bits;
 }
 
 template <int OUT>

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include "../../include/sp24.h"
+#include "common.hpp"
 
 namespace sp24 {
 
@@ -33,6 +34,7 @@ struct MmArgs {
     sp24_layout layout;    // sparse only
     bool sparse;
     ConvGeom conv;         // conv.on: B is the NHWC input X, N = n_img*OH*OW, K = R*S*C, bo / ldb unused
+    Epilogue epi;          // epi.on: int8 inputs, scaled / re-quantised output (out = I8, F16, BF16 or F32)
 };
 
 // General kernel: any M, N; both layouts; both B orders.  One wavefront per 32x32 tile of D.

@@ -53,10 +53,11 @@ __device__ __forceinline__ typename acc_of<DT>::type mfma32(const int4v& a, cons
         return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 
-// Store one 32x32 accumulator tile, predicated on the matrix edge.
+// Store one 32x32 accumulator tile, predicated on the matrix edge; int8 inputs with a scaled output type go
+// through the quantised path's epilogue.
 template <int DT, int OUT>
 __device__ __forceinline__ void store_tile(void* D, int64_t ldd, int64_t row0, int64_t col0, int64_t M, int64_t N,
-                                           const typename acc_of<DT>::type& c, int lane)
+                                           const typename acc_of<DT>::type& c, int lane, const Epilogue& epi)
 {
     int r = lane & 31, q = lane >> 5;
     int64_t col = col0 + r;
@@ -65,8 +66,10 @@ __device__ __forceinline__ void store_tile(void* D, int64_t ldd, int64_t row0, i
     for (int i = 0; i < 16; ++i) {
         int64_t row = row0 + 8 * (i / 4) + 4 * q + (i % 4);
         if (row < M) {
-            if constexpr (DT == SP24_I8) reinterpret_cast<int32_t*>(D)[row * ldd + col] = c[i];
-            else store_out<OUT>(D, row * ldd + col, c[i]);
+            float s = 0.0f, b = 0.0f;
+            if constexpr (DT == SP24_I8 && OUT != SP24_I32) epilogue_row(epi, row, s, b);
+            auto v = c[i];
+            store_bits<OUT>(D, row * ldd + col, output_bits<OUT>(v, s, b, epi));
         }
     }
 }

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
             }
         }
     }
-    store_tile<DT, OUT>(a.D, a.ldd, row0, col0, a.M, a.N, acc, lane);
+    store_tile<DT, OUT>(a.D, a.ldd, row0, col0, a.M, a.N, acc, lane, a.epi);
 }
 
 template <int DT, int OUT>
@@ -169,7 +169,13 @@ sp24_status launch_mm_simple(const MmArgs& a, hipStream_t st)
 {
     if (a.M == 0 || a.N == 0) return SP24_OK;
     if ((a.M + 31) / 32 > 65535) return SP24_ERR_SHAPE;
-    if (a.in == SP24_I8) return launch_t<SP24_I8, SP24_I32>(a, st);
+    if (a.in == SP24_I8) {
+        if (a.out == SP24_I32) return launch_t<SP24_I8, SP24_I32>(a, st);
+        if (a.out == SP24_I8) return launch_t<SP24_I8, SP24_I8>(a, st);
+        if (a.out == SP24_F32) return launch_t<SP24_I8, SP24_F32>(a, st);
+        if (a.out == SP24_F16) return launch_t<SP24_I8, SP24_F16>(a, st);
+        return launch_t<SP24_I8, SP24_BF16>(a, st);
+    }
     if (a.in == SP24_F16) {
         if (a.out == SP24_F32) return launch_t<SP24_F16, SP24_F32>(a, st);
         if (a.out == SP24_F16) return launch_t<SP24_F16, SP24_F16>(a, st);

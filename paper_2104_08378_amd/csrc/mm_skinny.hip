@@ -113,7 +113,9 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
                 int s = 0;
 #pragma unroll
                 for (int w = 0; w < kSkinnyWaves; ++w) s += (int)red[w][i][lane];
-                reinterpret_cast<int32_t*>(a.D)[row * a.ldd + col] = s;
+                float es = 0.0f, eb = 0.0f;
+                if constexpr (OUT != SP24_I32) epilogue_row(a.epi, row, es, eb);
+                store_bits<OUT>(a.D, row * a.ldd + col, output_bits<OUT>(s, es, eb, a.epi));
             } else {
                 float s = 0.f;
 #pragma unroll
@@ -142,7 +144,13 @@ sp24_status launch_mm_skinny(const MmArgs& a, hipStream_t st, bool* handled)
     if (a.sparse) ok = ok && a.layout == SP24_LAYOUT_TILED;
     if (!ok) return SP24_OK;
     *handled = true;
-    if (a.in == SP24_I8) return run_skinny<SP24_I8, SP24_I32>(a, st);
+    if (a.in == SP24_I8) {
+        if (a.out == SP24_I32) return run_skinny<SP24_I8, SP24_I32>(a, st);
+        if (a.out == SP24_I8) return run_skinny<SP24_I8, SP24_I8>(a, st);
+        if (a.out == SP24_F32) return run_skinny<SP24_I8, SP24_F32>(a, st);
+        if (a.out == SP24_F16) return run_skinny<SP24_I8, SP24_F16>(a, st);
+        return run_skinny<SP24_I8, SP24_BF16>(a, st);
+    }
     if (a.in == SP24_F16) {
         if (a.out == SP24_F32) return run_skinny<SP24_F16, SP24_F32>(a, st);
         if (a.out == SP24_F16) return run_skinny<SP24_F16, SP24_F16>(a, st);

@@ -173,7 +173,7 @@ __device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&o
 // `scratch` is this wavefront's own 32 x kPitch bytes; the direct path serves outputs that are not 16-byte tileable.
 template <int OUT, int TN>
 struct epilogue_geometry {
-    static constexpr int kOsz = (OUT == SP24_F32 || OUT == SP24_I32) ? 4 : 2;
+    static constexpr int kOsz = out_size<OUT>();
     static constexpr int kRowBytesOut = 32 * TN * kOsz;
     static constexpr int kPitch = kRowBytesOut + (kOsz == 4 ? 32 : 16);   // 4 rows apart = half a bank row apart
     static constexpr int kWaveBytes = 32 * kPitch;
@@ -190,7 +190,8 @@ __device__ __forceinline__ void store_wave_tile(const MmArgs& a, typename acc_of
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) store_tile<DT, OUT>(a.D, a.ldd, row_base + i * 32, col_base + j * 32, a.M, a.N, acc[i][j], lane);
+            for (int j = 0; j < TN; ++j)
+                store_tile<DT, OUT>(a.D, a.ldd, row_base + i * 32, col_base + j * 32, a.M, a.N, acc[i][j], lane, a.epi);
         return;
     }
     const int r = lane & 31, q = lane >> 5;
@@ -198,15 +199,24 @@ __device__ __forceinline__ void store_wave_tile(const MmArgs& a, typename acc_of
     uint8_t* Dp = reinterpret_cast<uint8_t*>(a.D);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        // quantised path: scale and bias of this lane's 16 rows of the block (rows past M are never stored)
+        float es[16], eb[16];
+        if constexpr (DT == SP24_I8 && OUT != SP24_I32) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int64_t m = row_base + i * 32 + 8 * (e / 4) + 4 * q + (e % 4);
+                epilogue_row(a.epi, m < a.M ? m : a.M - 1, es[e], eb[e]);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 uint8_t* p = scratch + (8 * (e / 4) + 4 * q + (e % 4)) * kPitch + (j * 32 + r) * kOsz;
-                if constexpr (DT == SP24_I8) *reinterpret_cast<int32_t*>(p) = acc[i][j][e];
-                else if constexpr (OUT == SP24_F32) *reinterpret_cast<float*>(p) = acc[i][j][e];
-                else if constexpr (OUT == SP24_F16) *reinterpret_cast<uint16_t*>(p) = f32_to_f16_bits(acc[i][j][e]);
-                else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16_bits(acc[i][j][e]);
+                auto v = acc[i][j][e];
+                float s = 0.0f, b = 0.0f;
+                if constexpr (DT == SP24_I8 && OUT != SP24_I32) { s = es[e]; b = eb[e]; }
+                store_bits<OUT>(p, 0, output_bits<OUT>(v, s, b, a.epi));
             }
 #pragma unroll
         for (int it = 0; it < 32 * kChunksPerRow / 64; ++it) {

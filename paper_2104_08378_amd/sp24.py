@@ -48,10 +48,13 @@ def lib():
         L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
         L.sp24_spmm_conv2d.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i32, i32, i32, vp]
         L.sp24_conv2d_dense.argtypes = [vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i64, i32, i32, vp]
+        f32 = ctypes.c_float
+        L.sp24_spmm_i8_scaled.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, f32, vp, i32, f32, i32, i32, i32, vp]
+        L.sp24_gemm_dense_i8_scaled.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, f32, vp, i32, f32, i32, i32, vp]
         L.sp24_status_string.argtypes = [i32]
         L.sp24_status_string.restype = ctypes.c_char_p
         for name in ("sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
-                     "sp24_conv2d_dense"):
+                     "sp24_conv2d_dense", "sp24_spmm_i8_scaled", "sp24_gemm_dense_i8_scaled"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -195,4 +198,47 @@ def sp24_conv2d_dense(A, X, out_dtype, R, S, pad=(0, 0), stride=(1, 1), out=None
     D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
     _check(lib().sp24_conv2d_dense(A.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, A.stride(0), D.stride(0),
                                    _DT[A.dtype], _DT[D.dtype], _stream()), "sp24_conv2d_dense")
+    return D
+
+
+def _scale_args(M, w_scale, bias):
+    _dev(w_scale, "w_scale")
+    if w_scale.dtype != torch.float32 or w_scale.numel() != M or not w_scale.is_contiguous():
+        raise ValueError("w_scale must be a contiguous float32 vector with one entry per row")
+    if bias is not None:
+        _dev(bias, "bias")
+        if bias.dtype != torch.float32 or bias.numel() != M or not bias.is_contiguous():
+            raise ValueError("bias must be a contiguous float32 vector with one entry per row")
+    return w_scale.data_ptr(), (bias.data_ptr() if bias is not None else None)
+
+
+def sp24_spmm_i8_scaled(V, meta, B, out_dtype, w_scale, x_scale, bias=None, relu=False, inv_y_scale=1.0, b_order="k",
+                        layout="canonical", out=None):
+    """int8 sparse product with the quantised path's epilogue fused into the store: per-row weight scale,
+    per-tensor activation scale, optional bias and ReLU; out_dtype int8 (re-quantised by inv_y_scale) or a float type."""
+    _dev(V, "V"), _dev(meta, "meta")
+    M, K = V.shape[0], V.shape[1] * 2
+    N, Kb, bo = _b_args(B, b_order)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    ws, bs = _scale_args(M, w_scale, bias)
+    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_spmm_i8_scaled(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
+                                     ws, float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], bo, _LAYOUT[layout],
+                                     _stream()), "sp24_spmm_i8_scaled")
+    return D
+
+
+def sp24_gemm_dense_i8_scaled(A, B, out_dtype, w_scale, x_scale, bias=None, relu=False, inv_y_scale=1.0, b_order="k", out=None):
+    """The same epilogue on the dense int8 product."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    N, Kb, bo = _b_args(B, b_order)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    ws, bs = _scale_args(M, w_scale, bias)
+    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_gemm_dense_i8_scaled(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0), D.stride(0),
+                                           ws, float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], bo, _stream()),
+           "sp24_gemm_dense_i8_scaled")
     return D

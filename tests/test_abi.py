@@ -123,3 +123,19 @@ def test_convolution_validation():
     assert dense(V, X, D, 64, 2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 100, 128, sp24.F16, sp24.F32, None) == SHAPE   # lda < K = 144
     assert dense(0, X, D, 64, 2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 144, 128, sp24.F16, sp24.F32, None) == NULL
     assert dense(V, X, D, 0, 2, 8, 8, 16, 3, 3, 1, 1, 1, 1, 144, 128, sp24.F16, sp24.F32, None) == OK
+
+
+def test_scaled_product_validation():
+    L = sp24.lib()
+    V, Mt, B, D, W, Bi = P, P + 0x1000000, P + 0x2000000, P + 0x3000000, P + 0x4000000, P + 0x5000000
+    f = ctypes.c_float
+
+    def scaled(o=sp24.I8, W=W, Bi=Bi, D=D, M=64):
+        return L.sp24_spmm_i8_scaled(V, Mt, B, D, M, 64, 64, 64, 64, W, f(1.0), Bi, 0, f(1.0), o, 0, 0, None)
+
+    assert scaled(o=sp24.I32) == DTYPE
+    assert scaled(W=0) == NULL and scaled(W=W + 2) == ALIGN and scaled(Bi=Bi + 1) == ALIGN
+    assert scaled(D=W) == SHAPE              # output aliases the scales
+    assert scaled(M=0) == OK
+    assert L.sp24_gemm_dense_i8_scaled(V, B, D, 64, 64, 64, 64, 64, 64, 0, f(1.0), 0, 0, f(1.0), sp24.F16, 0, None) == NULL
+    assert L.sp24_gemm_dense_i8_scaled(V, B, D, 64, 64, 64, 64, 64, 64, W, f(1.0), 0, 0, f(1.0), sp24.I32, 0, None) == DTYPE
