@@ -213,6 +213,23 @@ sp24_status sp24_gemm_dense_i8_scaled(const void* A, const void* B, void* D, int
                                       const float* w_scale, float x_scale, const float* bias, int relu,
                                       float inv_y_scale, sp24_dtype out, sp24_border bo, void* stream);
 
+/*
+ * The same epilogue on the convolutions: w_scale holds one factor per output
+ * channel m (Sec. 5: per-channel scaling factors for convolution weights).
+ * Geometry as for sp24_spmm_conv2d / sp24_conv2d_dense with int8 inputs;
+ * scales, bias, relu, inv_y_scale and `out` as for sp24_spmm_i8_scaled.
+ */
+sp24_status sp24_spmm_conv2d_i8_scaled(const void* V, const void* meta, const void* X, void* D, int64_t M,
+                                       int64_t n_img, int64_t H, int64_t W, int64_t C, int R, int S,
+                                       int pad_h, int pad_w, int stride_h, int stride_w, int64_t ldd,
+                                       const float* w_scale, float x_scale, const float* bias, int relu,
+                                       float inv_y_scale, sp24_dtype out, sp24_layout l, void* stream);
+sp24_status sp24_conv2d_dense_i8_scaled(const void* A, const void* X, void* D, int64_t M, int64_t n_img,
+                                        int64_t H, int64_t W, int64_t C, int R, int S, int pad_h, int pad_w,
+                                        int stride_h, int stride_w, int64_t lda, int64_t ldd,
+                                        const float* w_scale, float x_scale, const float* bias, int relu,
+                                        float inv_y_scale, sp24_dtype out, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* sp24_status_string(sp24_status s);
 

@@ -203,7 +203,7 @@ sp24_status sp24_gemm_dense_i8_scaled(const void* A, const void* B, void* D, int
 static sp24_status conv_common(MmArgs& a, int64_t n_img, int64_t H, int64_t W, int64_t C, int R, int S, int pad_h, int pad_w,
                                int stride_h, int stride_w, hipStream_t st)
 {
-    if (!is_input_type(a.in) || !out_legal(a.in, a.out, false)) return SP24_ERR_DTYPE;
+    if (!is_input_type(a.in) || !out_legal(a.in, a.out, a.epi.on != 0)) return SP24_ERR_DTYPE;
     const int64_t lim = (int64_t)1 << 20;
     if (a.M < 0 || n_img < 0 || H < 1 || W < 1 || C < 1 || R < 1 || S < 1 || pad_h < 0 || pad_w < 0 || stride_h < 1 || stride_w < 1 ||
         H > lim || W > lim || C > lim || R > 4096 || S > 4096 || pad_h > 4096 || pad_w > 4096 || stride_h > 4096 || stride_w > 4096 ||
@@ -236,6 +236,26 @@ sp24_status sp24_conv2d_dense(const void* A, const void* X, void* D, int64_t M, 
                               sp24_dtype in, sp24_dtype out, void* stream)
 {
     MmArgs a{A, nullptr, X, D, M, 0, 0, lda, 0, ldd, in, out, SP24_B_KMAJOR, SP24_LAYOUT_CANONICAL, false};
+    return conv_common(a, n_img, H, W, C, R, S, pad_h, pad_w, stride_h, stride_w, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_spmm_conv2d_i8_scaled(const void* V, const void* meta, const void* X, void* D, int64_t M, int64_t n_img,
+                                       int64_t H, int64_t W, int64_t C, int R, int S, int pad_h, int pad_w, int stride_h,
+                                       int stride_w, int64_t ldd, const float* w_scale, float x_scale, const float* bias,
+                                       int relu, float inv_y_scale, sp24_dtype out, sp24_layout l, void* stream)
+{
+    MmArgs a{V, meta, X, D, M, 0, 0, 0, 0, ldd, SP24_I8, out, SP24_B_KMAJOR, l, true};
+    a.epi = Epilogue{w_scale, bias, x_scale, inv_y_scale, relu != 0, 1};
+    return conv_common(a, n_img, H, W, C, R, S, pad_h, pad_w, stride_h, stride_w, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_conv2d_dense_i8_scaled(const void* A, const void* X, void* D, int64_t M, int64_t n_img, int64_t H, int64_t W,
+                                        int64_t C, int R, int S, int pad_h, int pad_w, int stride_h, int stride_w, int64_t lda,
+                                        int64_t ldd, const float* w_scale, float x_scale, const float* bias, int relu,
+                                        float inv_y_scale, sp24_dtype out, void* stream)
+{
+    MmArgs a{A, nullptr, X, D, M, 0, 0, lda, 0, ldd, SP24_I8, out, SP24_B_KMAJOR, SP24_LAYOUT_CANONICAL, false};
+    a.epi = Epilogue{w_scale, bias, x_scale, inv_y_scale, relu != 0, 1};
     return conv_common(a, n_img, H, W, C, R, S, pad_h, pad_w, stride_h, stride_w, static_cast<hipStream_t>(stream));
 }
 

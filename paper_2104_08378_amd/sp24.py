@@ -51,10 +51,13 @@ def lib():
         f32 = ctypes.c_float
         L.sp24_spmm_i8_scaled.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, f32, vp, i32, f32, i32, i32, i32, vp]
         L.sp24_gemm_dense_i8_scaled.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, f32, vp, i32, f32, i32, i32, vp]
+        L.sp24_spmm_conv2d_i8_scaled.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, vp, f32, vp, i32, f32, i32, i32, vp]
+        L.sp24_conv2d_dense_i8_scaled.argtypes = [vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i64, vp, f32, vp, i32, f32, i32, vp]
         L.sp24_status_string.argtypes = [i32]
         L.sp24_status_string.restype = ctypes.c_char_p
         for name in ("sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
-                     "sp24_conv2d_dense", "sp24_spmm_i8_scaled", "sp24_gemm_dense_i8_scaled"):
+                     "sp24_conv2d_dense", "sp24_spmm_i8_scaled", "sp24_gemm_dense_i8_scaled",
+                     "sp24_spmm_conv2d_i8_scaled", "sp24_conv2d_dense_i8_scaled"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -241,4 +244,32 @@ def sp24_gemm_dense_i8_scaled(A, B, out_dtype, w_scale, x_scale, bias=None, relu
     _check(lib().sp24_gemm_dense_i8_scaled(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0), D.stride(0),
                                            ws, float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], bo, _stream()),
            "sp24_gemm_dense_i8_scaled")
+    return D
+
+
+def sp24_spmm_conv2d_i8_scaled(V, meta, X, out_dtype, R, S, w_scale, x_scale, bias=None, relu=False, inv_y_scale=1.0,
+                               pad=(0, 0), stride=(1, 1), layout="canonical", out=None):
+    """int8 sparse convolution (implicit GEMM) with the quantised path's epilogue; w_scale per output channel."""
+    _dev(V, "V"), _dev(meta, "meta")
+    M, K = V.shape[0], V.shape[1] * 2
+    geom, N = _conv_args(X, K, R, S, pad, stride)
+    ws, bs = _scale_args(M, w_scale, bias)
+    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_spmm_conv2d_i8_scaled(V.data_ptr(), meta.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, D.stride(0), ws,
+                                            float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], _LAYOUT[layout],
+                                            _stream()), "sp24_spmm_conv2d_i8_scaled")
+    return D
+
+
+def sp24_conv2d_dense_i8_scaled(A, X, out_dtype, R, S, w_scale, x_scale, bias=None, relu=False, inv_y_scale=1.0, pad=(0, 0),
+                                stride=(1, 1), out=None):
+    """The same with the dense int8 filter matrix."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    geom, N = _conv_args(X, K, R, S, pad, stride)
+    ws, bs = _scale_args(M, w_scale, bias)
+    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_conv2d_dense_i8_scaled(A.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, A.stride(0), D.stride(0), ws,
+                                             float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], _stream()),
+           "sp24_conv2d_dense_i8_scaled")
     return D

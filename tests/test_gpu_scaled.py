@@ -88,3 +88,34 @@ def test_unit_scales_reproduce_the_clamped_integer_product():
     D32 = sp24.sp24_spmm(V, meta, to_gpu(Bt, "i8"), torch.int32)
     torch.cuda.synchronize()
     assert torch.equal(D8.to(torch.int32), D32.clamp(-128, 127))
+
+
+@pytest.mark.parametrize("geom", [
+    # M, n_img, H, W, C, R, S, pad, stride, layout
+    (33, 3, 5, 5, 32, 3, 3, (1, 1), (1, 1), "canonical"),      # general kernel
+    (256, 4, 10, 10, 128, 3, 3, (1, 1), (1, 1), "tiled"),      # tiled kernel, implicit gather
+    (128, 2, 9, 9, 128, 3, 3, (0, 1), (2, 1), "tiled"),
+])
+def test_quantised_convolution_int8_output_is_bit_exact(geom):
+    M, n_img, H, W, C, R, S, pad, stride, layout = geom
+    rng = np.random.default_rng([31, M])
+    A = rng.integers(-127, 128, size=(M, R * S * C), dtype=np.int8)
+    X = rng.integers(-127, 128, size=(n_img, H, W, C), dtype=np.int8)
+    w_scale = rng.uniform(4e-4, 2e-3, size=M).astype(np.float32)          # one per output channel
+    bias = rng.normal(0.0, 0.5, size=M).astype(np.float32)
+    x_scale, inv_y = np.float32(0.018), 23.0
+    Pn = oracle.prune(A, "i8")
+    acc = oracle.conv2d(Pn, X, "i8", R, S, pad, stride)
+    want = oracle.requant(acc, w_scale, x_scale, inv_y, bias, True)
+    ws, bs = torch.from_numpy(w_scale).cuda(), torch.from_numpy(bias).cuda()
+    V, meta = sp24.sp24_compress(to_gpu(A, "i8"), layout=layout)
+    Xd = to_gpu(X, "i8")
+    D = sp24.sp24_spmm_conv2d_i8_scaled(V, meta, Xd, torch.int8, R, S, ws, x_scale, bs, True, inv_y, pad, stride, layout=layout)
+    Dd = sp24.sp24_conv2d_dense_i8_scaled(to_gpu(Pn, "i8"), Xd, torch.int8, R, S, ws, x_scale, bs, True, inv_y, pad, stride)
+    torch.cuda.synchronize()
+    assert np.array_equal(D.cpu().numpy(), want)
+    assert np.array_equal(Dd.cpu().numpy(), want)
+    ref = oracle.dequant(acc, w_scale, x_scale, bias, True)
+    Df = sp24.sp24_spmm_conv2d_i8_scaled(V, meta, Xd, torch.float32, R, S, ws, x_scale, bs, True, 1.0, pad, stride, layout=layout)
+    torch.cuda.synchronize()
+    assert np.allclose(out_to_f64(Df), ref, rtol=1e-6, atol=1e-5)
