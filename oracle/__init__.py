@@ -45,6 +45,8 @@ def _load():
         lib.sp24o_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64]
         lib.sp24o_conv2d_f64.argtypes = [vp, vp, vp] + [i64] * 11 + [i32]
         lib.sp24o_conv2d_i32.argtypes = [vp, vp, vp] + [i64] * 11
+        lib.sp24o_mask_apply.argtypes = [vp, vp, vp, i64, i64, i32]
+        lib.sp24o_compress_masked.argtypes = [vp, vp, vp, i64, i64, i32]
         f32 = ctypes.c_float
         lib.sp24o_dequant_f64.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32]
         lib.sp24o_requant_i8.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32, f32]
@@ -106,6 +108,34 @@ def decompress(V, meta, dtype):
     if rc:
         raise ValueError(f"oracle decompress failed ({rc}): illegal metadata code")
     return P
+
+
+def _check_meta(W, meta):
+    M, K = W.shape
+    if meta.dtype != np.uint8 or meta.shape != (M, K // 8) or not meta.flags.c_contiguous:
+        raise ValueError("meta must be C-contiguous uint8 [M, K/8]")
+
+
+def mask_apply(W, meta, dtype):
+    """Sec. 4.1 Step 3: W with every position that the metadata does not record set to +0."""
+    _check(W, dtype)
+    _check_meta(W, meta)
+    P = np.empty_like(W)
+    rc = _load().sp24o_mask_apply(_ptr(W), _ptr(meta), _ptr(P), W.shape[0], W.shape[1], _TYPES[dtype])
+    if rc:
+        raise ValueError(f"oracle mask_apply failed ({rc})")
+    return P
+
+
+def compress_masked(W, meta, dtype):
+    """The compressed values of W at the positions the metadata records (no new selection)."""
+    _check(W, dtype)
+    _check_meta(W, meta)
+    V = np.empty((W.shape[0], W.shape[1] // 2), dtype=W.dtype)
+    rc = _load().sp24o_compress_masked(_ptr(W), _ptr(meta), _ptr(V), W.shape[0], W.shape[1], _TYPES[dtype])
+    if rc:
+        raise ValueError(f"oracle compress_masked failed ({rc})")
+    return V
 
 
 def gemm(P, B, dtype):

@@ -309,6 +309,56 @@ int sp24o_conv2d_i32(const int8_t *P, const int8_t *X, int32_t *D, long M, long 
 }
 
 /*
+ * ---- O7: keeping the pattern during retraining (Sec. 4.1, Step 3) ---------
+ * "Maintain the sparsity pattern computed in Step 2": after an optimizer
+ * step on the dense weights W, every position that Step 2 removed is set back
+ * to +0 (mask_apply), and the compressed values are refreshed from W at the
+ * positions the metadata records, without selecting again (compress_masked).
+ * meta is canonical (O2).  Kept values are copied bit for bit.
+ */
+int sp24o_mask_apply(const void *W, const uint8_t *meta, void *P, long M, long K, int t)
+{
+    int es = esize(t);
+    if (es == 0 || K % 8)
+        return 1;
+    for (long m = 0; m < M; ++m)
+        for (long g = 0; g < K / 4; ++g) {
+            uint8_t byte = meta[m * (K / 8) + g / 2];
+            int code = (g % 2) ? (byte >> 4) : (byte & 15);
+            int p0 = code & 3, p1 = (code >> 2) & 3;
+            if (p0 >= p1)
+                return 2;
+            for (int j = 0; j < 4; ++j) {
+                char *dst = (char *)P + (m * K + 4 * g + j) * es;
+                if (j == p0 || j == p1)
+                    memcpy(dst, (const char *)W + (m * K + 4 * g + j) * es, es);
+                else
+                    memset(dst, 0, es);
+            }
+        }
+    return 0;
+}
+
+int sp24o_compress_masked(const void *W, const uint8_t *meta, void *V, long M, long K, int t)
+{
+    int es = esize(t);
+    if (es == 0 || K % 8)
+        return 1;
+    for (long m = 0; m < M; ++m)
+        for (long g = 0; g < K / 4; ++g) {
+            uint8_t byte = meta[m * (K / 8) + g / 2];
+            int code = (g % 2) ? (byte >> 4) : (byte & 15);
+            int pos[2] = {code & 3, (code >> 2) & 3};
+            if (pos[0] >= pos[1])
+                return 2;
+            for (int s = 0; s < 2; ++s)
+                memcpy((char *)V + (m * (K / 2) + 2 * g + s) * es,
+                       (const char *)W + (m * K + 4 * g + pos[s]) * es, es);
+        }
+    return 0;
+}
+
+/*
  * ---- O6: epilogue of the quantised path ----------------------------------
  * The paper's INT8 recipe (Sec. 5, image classification and translation
  * paragraphs) fixes the granularity of the scaling factors: one per tensor

@@ -517,3 +517,32 @@ def test_requant_is_monotone_and_odd_without_bias():
     q = oracle.requant(acc, [0.0213], 1.7, 0.31).astype(np.int32)[0]
     assert np.all(np.diff(q) >= 0)
     assert np.array_equal(np.clip(q, -127, 127), -np.clip(q[::-1], -127, 127))
+
+
+# ---- keeping the pattern during retraining (Sec. 4.1 Step 3) -------------------------------------------------
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "i8"])
+def test_fixed_mask_operations(dt):
+    name = {"f16": "tiny_f16", "bf16": "ffn_bf16", "i8": "square_i8"}[dt]
+    A, _ = synth.make(name, M=24, N=16, K=96, seed=5)
+    W, _ = synth.make(name, M=24, N=16, K=96, seed=6)              # the weights after an optimizer step
+    V, meta = oracle.compress(A, dt)
+    # with the weights the mask was computed from, the mask reproduces pruning and the values of compress
+    assert np.array_equal(oracle.mask_apply(A, meta, dt), oracle.prune(A, dt))
+    assert np.array_equal(oracle.compress_masked(A, meta, dt), V)
+    # on new weights: the pattern of A, the values of W
+    P = oracle.mask_apply(W, meta, dt)
+    keep = oracle.prune(A, dt) != 0 if dt == "i8" else None
+    pattern = oracle.decompress(np.ones_like(V), meta, dt) != 0      # 1 at every recorded position
+    assert np.array_equal(P[pattern], W[pattern]) and not P[~pattern].any()
+    assert pattern.reshape(24, -1, 4).sum(axis=2).tolist() == [[2] * 24] * 24
+    # idempotent; and the compressed pair (compress_masked(W), meta) decompresses to it
+    assert np.array_equal(oracle.mask_apply(P, meta, dt), P)
+    Vw = oracle.compress_masked(W, meta, dt)
+    assert np.array_equal(oracle.decompress(Vw, meta, dt), P)
+    assert np.array_equal(oracle.compress_masked(P, meta, dt), Vw)
+    # the worked example of Sec. 3.1: positions [[0,3],[1,2]] = byte 0x9C keep columns 0, 3, 5, 6
+    w = np.arange(1, 9).astype(W.dtype).reshape(1, 8)
+    m = np.array([[0x9C]], dtype=np.uint8)
+    assert oracle.mask_apply(w, m, dt).tolist() == [[1, 0, 0, 4, 0, 6, 7, 0]]
+    assert oracle.compress_masked(w, m, dt).tolist() == [[1, 4, 6, 7]]
