@@ -133,6 +133,27 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
                             sp24_dtype t, sp24_layout l, void* stream);
 
 /*
+ * Sec. 4.1 Step 3 (retraining keeps the pattern of Step 2; a removed weight
+ * stays zero): P = W with every position that `meta` does not record set to
+ * +0, recorded positions copied bit for bit.  W holds the dense weights after
+ * an optimizer step; `meta` (layout l) comes from sp24_compress of the Step-2
+ * weights.  W, P: device, M x K, row strides ldw, ldp; P may equal W (then
+ * ldp = ldw).  Codes other than the six legal ones keep unspecified positions
+ * of their group.
+ */
+sp24_status sp24_mask_apply(const void* W, const void* meta, void* P, int64_t M, int64_t K,
+                            int64_t ldw, int64_t ldp, sp24_dtype t, sp24_layout l, void* stream);
+
+/*
+ * The compressed values of W under the same fixed pattern: V (layout l, same
+ * size as from sp24_compress) receives W's values at the positions `meta`
+ * records; nothing is selected and `meta` is not written.  (V, meta) then
+ * decompresses to sp24_mask_apply(W, meta) and is ready for sp24_spmm.
+ */
+sp24_status sp24_compress_masked(const void* W, const void* meta, void* V, int64_t M, int64_t K,
+                                 int64_t ldw, sp24_dtype t, sp24_layout l, void* stream);
+
+/*
  * Sec. 3.2, Fig. 2: D = decompress(V, meta) x B.  Products of 16-bit inputs
  * are accumulated in fp32 and written as `out` = SP24_F32, SP24_F16 or
  * SP24_BF16 (one rounding, to nearest even); int8 products are accumulated in

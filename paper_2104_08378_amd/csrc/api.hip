@@ -116,6 +116,46 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
 }
 
 // x_bytes: extent of the NHWC input when a.conv.on (a.B then points at it), else unused
+sp24_status sp24_mask_apply(const void* W, const void* meta, void* P, int64_t M, int64_t K, int64_t ldw, int64_t ldp, sp24_dtype t,
+                            sp24_layout l, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (!is_layout(l)) return SP24_ERR_LAYOUT;
+    if (M < 0 || !k_legal(K, t)) return SP24_ERR_SHAPE;
+    if (!layout_fits(M, K, l)) return SP24_ERR_LAYOUT;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(W, M, K, ldw, es);
+    if (s != SP24_OK) return s;
+    s = check_matrix(P, M, K, ldp, es);
+    if (s != SP24_OK) return s;
+    if (M == 0) return SP24_OK;
+    if (!meta) return SP24_ERR_NULL;
+    if (!aligned16(meta)) return SP24_ERR_ALIGN;
+    if (W == P && ldw != ldp) return SP24_ERR_SHAPE;
+    size_t nw = ((size_t)(M - 1) * ldw + K) * es, np = ((size_t)(M - 1) * ldp + K) * es;
+    if (W != P && ranges_overlap(W, nw, P, np)) return SP24_ERR_SHAPE;
+    if (ranges_overlap(P, np, meta, sp24_meta_bytes(M, K, t, l))) return SP24_ERR_SHAPE;
+    return launch_mask_apply(W, meta, P, M, K, ldw, ldp, t, l, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_compress_masked(const void* W, const void* meta, void* V, int64_t M, int64_t K, int64_t ldw, sp24_dtype t,
+                                 sp24_layout l, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (!is_layout(l)) return SP24_ERR_LAYOUT;
+    if (M < 0 || !k_legal(K, t)) return SP24_ERR_SHAPE;
+    if (!layout_fits(M, K, l)) return SP24_ERR_LAYOUT;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(W, M, K, ldw, es);
+    if (s != SP24_OK) return s;
+    if (M == 0) return SP24_OK;
+    if (!V || !meta) return SP24_ERR_NULL;
+    if (!aligned16(V) || !aligned16(meta)) return SP24_ERR_ALIGN;
+    size_t nw = ((size_t)(M - 1) * ldw + K) * es, nv = sp24_values_bytes(M, K, t);
+    if (ranges_overlap(W, nw, V, nv) || ranges_overlap(V, nv, meta, sp24_meta_bytes(M, K, t, l))) return SP24_ERR_SHAPE;
+    return launch_compress_masked(W, meta, V, M, K, ldw, t, l, static_cast<hipStream_t>(stream));
+}
+
 static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
 {
     if (!is_input_type(a.in) || !out_legal(a.in, a.out, a.epi.on != 0)) return SP24_ERR_DTYPE;

@@ -24,6 +24,12 @@ __device__ __forceinline__ uint32_t mask8(uint32_t w)
     return keep_mask(mag_key8(w & 0xFFu), mag_key8((w >> 8) & 0xFFu), mag_key8((w >> 16) & 0xFFu), mag_key8(w >> 24));
 }
 
+// keep mask of a recorded code pos0 | pos1 << 2 (any 4-bit value gives a mask inside the group)
+__device__ __forceinline__ uint32_t mask_of_code(uint32_t code)
+{
+    return (1u << (code & 3u)) | (1u << ((code >> 2) & 3u));
+}
+
 __device__ __forceinline__ void prune16(uint32_t& w0, uint32_t& w1, uint32_t m)
 {
     w0 &= ((m & 1u) ? 0xFFFFu : 0u) | ((m & 2u) ? 0xFFFF0000u : 0u);
@@ -76,22 +82,45 @@ __device__ __forceinline__ uint32_t unpack8(uint32_t pair, uint32_t code)
     return x0 | (x1 << 8) | (x2 << 16) | (x3 << 24);
 }
 
+// The codes of the 16-byte piece c of row m (4 groups for int8, 2 for 16-bit types) from stored metadata, in the
+// low bits of the result, group 0 first.  K8 = K/8 (canonical row length in bytes), KB = K/64 (tiles per row block).
+template <int DT, int LAYOUT>
+__device__ __forceinline__ uint32_t stored_codes(const uint8_t* meta, int64_t m, int64_t c, int64_t K8, int64_t KB)
+{
+    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int GROUPS = 4 / ES;                       // groups per 16-byte piece
+    if constexpr (LAYOUT == SP24_LAYOUT_CANONICAL) {
+        if constexpr (DT == SP24_I8) return *reinterpret_cast<const uint16_t*>(meta + m * K8 + c * 2);
+        else return meta[m * K8 + c];
+    } else {
+        const int64_t e0 = c * (16 / ES);                // first column of the piece
+        const int64_t kb = e0 >> 6;
+        const uint32_t h = (uint32_t)(e0 >> 5) & 1u, g0 = (uint32_t)(e0 & 31) >> 2;
+        const uint32_t word = reinterpret_cast<const uint32_t*>(meta)[((m >> 5) * KB + kb) * 64 + (m & 31) + 32 * h];
+        return (word >> (4 * g0)) & ((1u << (4 * GROUPS)) - 1u);
+    }
+}
+
 // ---- prune: dense -> dense ----------------------------------------------
-// One lane per 16-byte piece of a row.
-template <int DT>
+// One lane per 16-byte piece of a row.  FIXED: the keep pattern comes from stored metadata instead of the
+// magnitudes (Sec. 4.1 Step 3: removed weights stay zero while the network is retrained).
+template <int DT, bool FIXED, int LAYOUT>
 __global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, uint8_t* __restrict__ P, int64_t M,
-                                               int64_t chunks_per_row, int64_t lda_bytes, int64_t ldp_bytes)
+                                               int64_t chunks_per_row, int64_t lda_bytes, int64_t ldp_bytes,
+                                               const uint8_t* __restrict__ meta, int64_t K8, int64_t KB)
 {
     int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= M * chunks_per_row) return;
     int64_t m = id / chunks_per_row, c = id - m * chunks_per_row;
     uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
+    uint32_t codes = 0;
+    if constexpr (FIXED) codes = stored_codes<DT, LAYOUT>(meta, m, c, K8, KB);
     if constexpr (DT == SP24_I8) {
-        for (int g = 0; g < 4; ++g) w[g] = prune8(w[g], mask8(w[g]));
+        for (int g = 0; g < 4; ++g) w[g] = prune8(w[g], FIXED ? mask_of_code((codes >> (4 * g)) & 0xFu) : mask8(w[g]));
     } else {
         for (int g = 0; g < 2; ++g) {
             uint32_t w0 = w[2 * g], w1 = w[2 * g + 1];
-            prune16(w0, w1, mask16<DT>(w0, w1));
+            prune16(w0, w1, FIXED ? mask_of_code((codes >> (4 * g)) & 0xFu) : mask16<DT>(w0, w1));
             w[2 * g] = w0;
             w[2 * g + 1] = w1;
         }
@@ -102,7 +131,8 @@ __global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, ui
 // ---- compress, canonical layout -------------------------------------------
 // One lane per 16 input bytes: 8 bytes of V and 1 (16-bit) or 2 (int8) bytes
 // of metadata; consecutive lanes write consecutive addresses in both arrays.
-template <int DT>
+// FIXED: the metadata is an input; the values at its recorded positions are gathered, nothing is selected.
+template <int DT, bool FIXED>
 __global__ __launch_bounds__(256) void k_compress_canon(const uint8_t* __restrict__ A, uint8_t* __restrict__ V,
                                                         uint8_t* __restrict__ meta, int64_t M, int64_t chunks_per_row,
                                                         int64_t lda_bytes)
@@ -113,16 +143,29 @@ __global__ __launch_bounds__(256) void k_compress_canon(const uint8_t* __restric
     uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
     uint2v v;
     if constexpr (DT == SP24_I8) {
-        uint32_t m0 = mask8(w[0]), m1 = mask8(w[1]), m2 = mask8(w[2]), m3 = mask8(w[3]);
+        uint32_t m0, m1, m2, m3;
+        if constexpr (FIXED) {
+            const uint32_t codes = *reinterpret_cast<const uint16_t*>(meta + id * 2);
+            m0 = mask_of_code(codes & 0xFu), m1 = mask_of_code((codes >> 4) & 0xFu);
+            m2 = mask_of_code((codes >> 8) & 0xFu), m3 = mask_of_code(codes >> 12);
+        } else {
+            m0 = mask8(w[0]), m1 = mask8(w[1]), m2 = mask8(w[2]), m3 = mask8(w[3]);
+            uint32_t codes = code_of_mask(m0) | (code_of_mask(m1) << 4) | (code_of_mask(m2) << 8) | (code_of_mask(m3) << 12);
+            *reinterpret_cast<uint16_t*>(meta + id * 2) = (uint16_t)codes; // rows are K/8 = 2*chunks bytes: id*2 is exact
+        }
         v[0] = pack8(w[0], m0) | (pack8(w[1], m1) << 16);
         v[1] = pack8(w[2], m2) | (pack8(w[3], m3) << 16);
-        uint32_t codes = code_of_mask(m0) | (code_of_mask(m1) << 4) | (code_of_mask(m2) << 8) | (code_of_mask(m3) << 12);
-        *reinterpret_cast<uint16_t*>(meta + id * 2) = (uint16_t)codes; // rows are K/8 = 2*chunks bytes: id*2 is exact
     } else {
-        uint32_t m0 = mask16<DT>(w[0], w[1]), m1 = mask16<DT>(w[2], w[3]);
+        uint32_t m0, m1;
+        if constexpr (FIXED) {
+            const uint32_t codes = meta[id];
+            m0 = mask_of_code(codes & 0xFu), m1 = mask_of_code(codes >> 4);
+        } else {
+            m0 = mask16<DT>(w[0], w[1]), m1 = mask16<DT>(w[2], w[3]);
+            meta[id] = (uint8_t)(code_of_mask(m0) | (code_of_mask(m1) << 4)); // rows are K/8 = chunks bytes
+        }
         v[0] = pack16(w[0], w[1], m0);
         v[1] = pack16(w[2], w[3], m1);
-        meta[id] = (uint8_t)(code_of_mask(m0) | (code_of_mask(m1) << 4)); // rows are K/8 = chunks bytes
     }
     *reinterpret_cast<uint2v*>(V + id * 8) = v; // V rows are 8 * chunks bytes in both cases
 }
@@ -131,7 +174,7 @@ __global__ __launch_bounds__(256) void k_compress_canon(const uint8_t* __restric
 // One lane per slot: 32 consecutive elements of one row (half of a 32x64
 // tile).  A wavefront covers one whole tile, so its V and metadata stores are
 // contiguous runs of 1 KiB and 256 bytes.
-template <int DT>
+template <int DT, bool FIXED>
 __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restrict__ A, uint8_t* __restrict__ V,
                                                         uint32_t* __restrict__ meta, int64_t tiles, int64_t KB,
                                                         int64_t lda_bytes)
@@ -143,6 +186,8 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
     int64_t rb = tile / KB, kb = tile - rb * KB;
     int64_t m = rb * 32 + r;
     uint32_t codes = 0;
+    uint32_t given = 0;
+    if constexpr (FIXED) given = meta[tile * 64 + slot];
     if constexpr (DT == SP24_I8) {
         const uint4v* src = reinterpret_cast<const uint4v*>(A + m * lda_bytes + kb * 64 + h * 32);
         uint4v v;
@@ -150,9 +195,9 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
             uint4v w = src[q];
             uint32_t pk[4];
             for (int g = 0; g < 4; ++g) {
-                uint32_t mk = mask8(w[g]);
+                uint32_t mk = FIXED ? mask_of_code((given >> (4 * (4 * q + g))) & 0xFu) : mask8(w[g]);
                 pk[g] = pack8(w[g], mk);
-                codes |= code_of_mask(mk) << (4 * (4 * q + g));
+                if constexpr (!FIXED) codes |= code_of_mask(mk) << (4 * (4 * q + g));
             }
             v[2 * q] = pk[0] | (pk[1] << 16);
             v[2 * q + 1] = pk[2] | (pk[3] << 16);
@@ -164,15 +209,17 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
             uint4v v;
             for (int q = 0; q < 2; ++q) {
                 uint4v w = src[2 * s + q];
-                uint32_t m0 = mask16<DT>(w[0], w[1]), m1 = mask16<DT>(w[2], w[3]);
+                const uint32_t gc = (given >> (8 * (2 * s + q))) & 0xFFu;
+                uint32_t m0 = FIXED ? mask_of_code(gc & 0xFu) : mask16<DT>(w[0], w[1]);
+                uint32_t m1 = FIXED ? mask_of_code(gc >> 4) : mask16<DT>(w[2], w[3]);
                 v[2 * q] = pack16(w[0], w[1], m0);
                 v[2 * q + 1] = pack16(w[2], w[3], m1);
-                codes |= (code_of_mask(m0) | (code_of_mask(m1) << 4)) << (8 * (2 * s + q));
+                if constexpr (!FIXED) codes |= (code_of_mask(m0) | (code_of_mask(m1) << 4)) << (8 * (2 * s + q));
             }
             *reinterpret_cast<uint4v*>(V + ((tile * 2 + s) * 64 + slot) * 16) = v;
         }
     }
-    meta[tile * 64 + slot] = codes;
+    if constexpr (!FIXED) meta[tile * 64 + slot] = codes;
 }
 
 // ---- decompress -----------------------------------------------------------
@@ -247,24 +294,33 @@ __global__ __launch_bounds__(256) void k_decompress_tiled(const uint8_t* __restr
 // ---- launchers ------------------------------------------------------------
 static inline unsigned blocks_for(int64_t items) { return (unsigned)((items + 255) / 256); }
 
+// meta == nullptr: select by magnitude; else keep the pattern that `meta` (in layout l) records
 template <int DT>
-static void run_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, hipStream_t st)
+static void run_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, const void* meta, sp24_layout l,
+                      hipStream_t st)
 {
     constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
-    int64_t cpr = K * es / 16;
-    k_prune<DT><<<blocks_for(M * cpr), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)P, M, cpr, lda * es, ldp * es);
+    const int64_t cpr = K * es / 16;
+    const dim3 grid(blocks_for(M * cpr));
+    const uint8_t *a = (const uint8_t*)A, *mt = (const uint8_t*)meta;
+    uint8_t* p = (uint8_t*)P;
+    if (!meta) k_prune<DT, false, SP24_LAYOUT_CANONICAL><<<grid, 256, 0, st>>>(a, p, M, cpr, lda * es, ldp * es, nullptr, 0, 0);
+    else if (l == SP24_LAYOUT_CANONICAL)
+        k_prune<DT, true, SP24_LAYOUT_CANONICAL><<<grid, 256, 0, st>>>(a, p, M, cpr, lda * es, ldp * es, mt, K / 8, K / 64);
+    else k_prune<DT, true, SP24_LAYOUT_TILED><<<grid, 256, 0, st>>>(a, p, M, cpr, lda * es, ldp * es, mt, K / 8, K / 64);
 }
 
-template <int DT>
+// fixed: `meta` is an input and only V is written
+template <int DT, bool FIXED>
 static void run_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_layout l, hipStream_t st)
 {
     constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
     if (l == SP24_LAYOUT_CANONICAL) {
         int64_t cpr = K * es / 16;
-        k_compress_canon<DT><<<blocks_for(M * cpr), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint8_t*)meta, M, cpr, lda * es);
+        k_compress_canon<DT, FIXED><<<blocks_for(M * cpr), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint8_t*)meta, M, cpr, lda * es);
     } else {
         int64_t KB = K / 64, tiles = (M / 32) * KB;
-        k_compress_tiled<DT><<<blocks_for(tiles * 64), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint32_t*)meta, tiles, KB, lda * es);
+        k_compress_tiled<DT, FIXED><<<blocks_for(tiles * 64), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint32_t*)meta, tiles, KB, lda * es);
     }
 }
 
@@ -286,18 +342,39 @@ static sp24_status launch_result() { return hipGetLastError() == hipSuccess ? SP
 sp24_status launch_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t, hipStream_t st)
 {
     if (M * K == 0) return SP24_OK;
-    if (t == SP24_F16) run_prune<SP24_F16>(A, P, M, K, lda, ldp, st);
-    else if (t == SP24_BF16) run_prune<SP24_BF16>(A, P, M, K, lda, ldp, st);
-    else run_prune<SP24_I8>(A, P, M, K, lda, ldp, st);
+    if (t == SP24_F16) run_prune<SP24_F16>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
+    else if (t == SP24_BF16) run_prune<SP24_BF16>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
+    else run_prune<SP24_I8>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
+    return launch_result();
+}
+
+sp24_status launch_mask_apply(const void* W, const void* meta, void* P, int64_t M, int64_t K, int64_t ldw, int64_t ldp, sp24_dtype t,
+                              sp24_layout l, hipStream_t st)
+{
+    if (M * K == 0) return SP24_OK;
+    if (t == SP24_F16) run_prune<SP24_F16>(W, P, M, K, ldw, ldp, meta, l, st);
+    else if (t == SP24_BF16) run_prune<SP24_BF16>(W, P, M, K, ldw, ldp, meta, l, st);
+    else run_prune<SP24_I8>(W, P, M, K, ldw, ldp, meta, l, st);
+    return launch_result();
+}
+
+sp24_status launch_compress_masked(const void* W, const void* meta, void* V, int64_t M, int64_t K, int64_t ldw, sp24_dtype t,
+                                   sp24_layout l, hipStream_t st)
+{
+    if (M * K == 0) return SP24_OK;
+    void* mt = const_cast<void*>(meta);   // read only in the fixed-mask kernels
+    if (t == SP24_F16) run_compress<SP24_F16, true>(W, V, mt, M, K, ldw, l, st);
+    else if (t == SP24_BF16) run_compress<SP24_BF16, true>(W, V, mt, M, K, ldw, l, st);
+    else run_compress<SP24_I8, true>(W, V, mt, M, K, ldw, l, st);
     return launch_result();
 }
 
 sp24_status launch_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_dtype t, sp24_layout l, hipStream_t st)
 {
     if (M * K == 0) return SP24_OK;
-    if (t == SP24_F16) run_compress<SP24_F16>(A, V, meta, M, K, lda, l, st);
-    else if (t == SP24_BF16) run_compress<SP24_BF16>(A, V, meta, M, K, lda, l, st);
-    else run_compress<SP24_I8>(A, V, meta, M, K, lda, l, st);
+    if (t == SP24_F16) run_compress<SP24_F16, false>(A, V, meta, M, K, lda, l, st);
+    else if (t == SP24_BF16) run_compress<SP24_BF16, false>(A, V, meta, M, K, lda, l, st);
+    else run_compress<SP24_I8, false>(A, V, meta, M, K, lda, l, st);
     return launch_result();
 }
 

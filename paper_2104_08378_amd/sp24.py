@@ -44,6 +44,8 @@ def lib():
         L.sp24_prune.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp]
         L.sp24_compress.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.sp24_decompress.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
+        L.sp24_mask_apply.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, i32, vp]
+        L.sp24_compress_masked.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
         L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
         L.sp24_spmm_conv2d.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i32, i32, i32, vp]
@@ -55,7 +57,7 @@ def lib():
         L.sp24_conv2d_dense_i8_scaled.argtypes = [vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i64, vp, f32, vp, i32, f32, i32, vp]
         L.sp24_status_string.argtypes = [i32]
         L.sp24_status_string.restype = ctypes.c_char_p
-        for name in ("sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
+        for name in ("sp24_mask_apply", "sp24_compress_masked", "sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
                      "sp24_conv2d_dense", "sp24_spmm_i8_scaled", "sp24_gemm_dense_i8_scaled",
                      "sp24_spmm_conv2d_i8_scaled", "sp24_conv2d_dense_i8_scaled"):
             getattr(L, name).restype = i32
@@ -130,6 +132,26 @@ def sp24_decompress(V, meta, layout="canonical", out=None):
     _check(lib().sp24_decompress(V.data_ptr(), meta.data_ptr(), P.data_ptr(), M, K, P.stride(0), _DT[V.dtype],
                                  _LAYOUT[layout], _stream()), "sp24_decompress")
     return P
+
+
+def sp24_mask_apply(W, meta, layout="canonical", out=None):
+    """W with every position that the metadata does not record set to +0 (the pattern is kept, not re-selected)."""
+    _rowmajor(W, "W"), _dev(meta, "meta")
+    M, K = W.shape
+    P = torch.empty_like(W) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_mask_apply(W.data_ptr(), meta.data_ptr(), P.data_ptr(), M, K, W.stride(0), P.stride(0), _DT[W.dtype],
+                                 _LAYOUT[layout], _stream()), "sp24_mask_apply")
+    return P
+
+
+def sp24_compress_masked(W, meta, layout="canonical", out=None):
+    """Compressed values of W at the positions the metadata records."""
+    _rowmajor(W, "W"), _dev(meta, "meta")
+    M, K = W.shape
+    V = torch.empty((M, K // 2), dtype=W.dtype, device=W.device) if out is None else _dev(out, "out")
+    _check(lib().sp24_compress_masked(W.data_ptr(), meta.data_ptr(), V.data_ptr(), M, K, W.stride(0), _DT[W.dtype],
+                                      _LAYOUT[layout], _stream()), "sp24_compress_masked")
+    return V
 
 
 def _b_args(B, b_order):

@@ -139,3 +139,20 @@ def test_scaled_product_validation():
     assert scaled(M=0) == OK
     assert L.sp24_gemm_dense_i8_scaled(V, B, D, 64, 64, 64, 64, 64, 64, 0, f(1.0), 0, 0, f(1.0), sp24.F16, 0, None) == NULL
     assert L.sp24_gemm_dense_i8_scaled(V, B, D, 64, 64, 64, 64, 64, 64, W, f(1.0), 0, 0, f(1.0), sp24.I32, 0, None) == DTYPE
+
+
+def test_fixed_mask_validation():
+    L = sp24.lib()
+    W, Mt, Pp, V = P, P + 0x1000000, P + 0x2000000, P + 0x3000000
+
+    def apply(M=64, K=64, ldw=64, ldp=64, t=sp24.F16, lay=0, W=W, Mt=Mt, Pp=Pp):
+        return L.sp24_mask_apply(W, Mt, Pp, M, K, ldw, ldp, t, lay, None)
+
+    assert apply(t=sp24.F32) == DTYPE and apply(lay=2) == LAYOUT and apply(K=24) == SHAPE and apply(ldp=32) == SHAPE
+    assert apply(M=48, lay=sp24.TILED) == LAYOUT
+    assert apply(Mt=0) == NULL and apply(W=0) == NULL and apply(Mt=Mt + 4) == ALIGN and apply(Pp=Pp + 2) == ALIGN
+    assert apply(Pp=W, ldp=128) == SHAPE and apply(Pp=Mt) == SHAPE and apply(M=0) == OK
+    comp = L.sp24_compress_masked
+    assert comp(W, Mt, 0, 64, 64, 64, sp24.I8, 0, None) == NULL and comp(W, 0, V, 64, 64, 64, sp24.I8, 0, None) == NULL
+    assert comp(W, Mt, W, 64, 64, 64, sp24.I8, 0, None) == SHAPE and comp(W, Mt, V, 64, 48, 64, sp24.I8, 0, None) == SHAPE
+    assert comp(W, Mt, V, 0, 64, 64, sp24.I8, 0, None) == OK

@@ -94,6 +94,35 @@ def test_tiled_layout_is_the_documented_permutation(dtype):
         assert np.array_equal(to_bits(P), oracle.prune(A, dtype))
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("layout", ["canonical", "tiled"])
+def test_fixed_mask_operations_bit_exact(dtype, layout):
+    """Sec. 4.1 Step 3: the pattern of one matrix applied to another, and its compressed values."""
+    for i, (M, K) in enumerate([(32, 64), (96, 192), (160, 1088)] if layout == "tiled" else [(1, 32), (37, 96), (96, 192), (257, 1056)]):
+        A, _ = synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=i)
+        W = adversarial(dtype, M, K, 40 + i) if i == 1 else synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=20 + i)[0]
+        _, ometa = oracle.compress(A, dtype)
+        Ad, Wd = to_gpu(A, dtype), to_gpu(W, dtype)
+        V0, meta = sp24.sp24_compress(Ad, layout=layout)
+        P = sp24.sp24_mask_apply(Wd, meta, layout=layout)
+        V = sp24.sp24_compress_masked(Wd, meta, layout=layout)
+        P2 = sp24.sp24_decompress(V, meta, layout=layout)
+        Q = Wd.clone()
+        sp24.sp24_mask_apply(Q, meta, layout=layout, out=Q)                    # in place
+        torch.cuda.synchronize()
+        want = oracle.mask_apply(W, ometa, dtype)
+        assert np.array_equal(to_bits(P), want), (dtype, layout, M, K)
+        assert np.array_equal(to_bits(Q), want)
+        assert np.array_equal(to_bits(P2), want)
+        wantV = oracle.compress_masked(W, ometa, dtype)
+        if layout == "tiled":
+            wantV, _ = tiled_from_canonical(wantV, ometa, dtype)
+        assert np.array_equal(to_bits(V), wantV), (dtype, layout, M, K)
+        # on the matrix the pattern came from, both reproduce prune / compress
+        assert np.array_equal(to_bits(sp24.sp24_mask_apply(Ad, meta, layout=layout)), oracle.prune(A, dtype))
+        assert torch.equal(sp24.sp24_compress_masked(Ad, meta, layout=layout).view(torch.uint8), V0.view(torch.uint8))
+
+
 MM_CASES = [
     # dtype, out, M, N, K
     ("f16", "f32", 32, 32, 64),
