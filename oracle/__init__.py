@@ -45,6 +45,7 @@ def _load():
         lib.sp24o_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64]
         lib.sp24o_conv2d_f64.argtypes = [vp, vp, vp] + [i64] * 11 + [i32]
         lib.sp24o_conv2d_i32.argtypes = [vp, vp, vp] + [i64] * 11
+        lib.sp24o_prune_transposable.argtypes = [vp, vp, i64, i64, i32]
         lib.sp24o_mask_apply.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_compress_masked.argtypes = [vp, vp, vp, i64, i64, i32]
         f32 = ctypes.c_float
@@ -107,6 +108,17 @@ def decompress(V, meta, dtype):
     rc = _load().sp24o_decompress(_ptr(V), _ptr(meta), _ptr(P), M, K, _TYPES[dtype])
     if rc:
         raise ValueError(f"oracle decompress failed ({rc}): illegal metadata code")
+    return P
+
+
+def prune_transposable(A, dtype):
+    """Sec. 6: a 2:4 pattern along rows and along columns -- per aligned 4x4 block the pattern with two kept entries
+    in every row and column that retains the most magnitude (exhaustive search; ties to the first pattern)."""
+    _check(A, dtype)
+    P = np.empty_like(A)
+    rc = _load().sp24o_prune_transposable(_ptr(A), _ptr(P), A.shape[0], A.shape[1], _TYPES[dtype])
+    if rc:
+        raise ValueError("oracle prune_transposable: M and K must be multiples of 4")
     return P
 
 

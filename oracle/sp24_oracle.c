@@ -359,6 +359,76 @@ int sp24o_compress_masked(const void *W, const uint8_t *meta, void *V, long M, l
 }
 
 /*
+ * ---- O8: patterns that also hold for the transposed matrix -----------------
+ * To use the sparse product in the backward pass the 2:4 constraint must hold
+ * along rows and along columns (Sec. 6).  The paper names an exhaustive search
+ * "that seeks to minimize the weight magnitude lost" and gives no listing; this
+ * is that search written out: every aligned 4 x 4 block keeps the entries of
+ * the one pattern, among those with exactly two kept entries in each row and
+ * each column (there are 90), whose kept magnitudes sum highest.
+ * Made unique by: magnitudes as in O1 (every NaN counts as +infinity here);
+ * the sum of a pattern is ((r0 + r1) + r2) + r3 with r_i = |a[i][c]| + |a[i][c']|
+ * (c < c' the kept columns of row i), in double for the 16-bit types (exact
+ * conversion) and in integers for int8; patterns are visited in lexicographic
+ * order of their four column pairs, pairs ordered (0,1) (0,2) (0,3) (1,2) (1,3)
+ * (2,3), and only a strictly higher sum replaces the best so far.
+ */
+int sp24o_prune_transposable(const void *A, void *P, long M, long K, int t)
+{
+    static const int pair[6][2] = {{0, 1}, {0, 2}, {0, 3}, {1, 2}, {1, 3}, {2, 3}};
+    int es = esize(t);
+    if (es == 0 || M % 4 || K % 4)
+        return 1;
+    for (long bm = 0; bm < M; bm += 4)
+        for (long bk = 0; bk < K; bk += 4) {
+            double mag[4][4];
+            for (int i = 0; i < 4; ++i)
+                for (int j = 0; j < 4; ++j) {
+                    long idx = (bm + i) * K + bk + j;
+                    if (t == T_I8) {
+                        mag[i][j] = fabs((double)((const int8_t *)A)[idx]);
+                    } else {
+                        double v = elem_to_double(A, idx, t);
+                        mag[i][j] = (v != v) ? INFINITY : fabs(v);
+                    }
+                }
+            int best[4] = {-1, -1, -1, -1};
+            double best_sum = -1.0;
+            int p[4];
+            for (p[0] = 0; p[0] < 6; ++p[0])
+                for (p[1] = 0; p[1] < 6; ++p[1])
+                    for (p[2] = 0; p[2] < 6; ++p[2])
+                        for (p[3] = 0; p[3] < 6; ++p[3]) {
+                            int count[4] = {0, 0, 0, 0};
+                            for (int i = 0; i < 4; ++i) {
+                                ++count[pair[p[i]][0]];
+                                ++count[pair[p[i]][1]];
+                            }
+                            if (count[0] != 2 || count[1] != 2 || count[2] != 2 || count[3] != 2)
+                                continue;
+                            double r[4];
+                            for (int i = 0; i < 4; ++i)
+                                r[i] = mag[i][pair[p[i]][0]] + mag[i][pair[p[i]][1]];
+                            double sum = ((r[0] + r[1]) + r[2]) + r[3];
+                            if (sum > best_sum) {
+                                best_sum = sum;
+                                memcpy(best, p, sizeof best);
+                            }
+                        }
+            for (int i = 0; i < 4; ++i)
+                for (int j = 0; j < 4; ++j) {
+                    long idx = (bm + i) * K + bk + j;
+                    char *dst = (char *)P + idx * es;
+                    if (j == pair[best[i]][0] || j == pair[best[i]][1])
+                        memcpy(dst, (const char *)A + idx * es, es);
+                    else
+                        memset(dst, 0, es);
+                }
+        }
+    return 0;
+}
+
+/*
  * ---- O6: epilogue of the quantised path ----------------------------------
  * The paper's INT8 recipe (Sec. 5, image classification and translation
  * paragraphs) fixes the granularity of the scaling factors: one per tensor

@@ -546,3 +546,65 @@ def test_fixed_mask_operations(dt):
     m = np.array([[0x9C]], dtype=np.uint8)
     assert oracle.mask_apply(w, m, dt).tolist() == [[1, 0, 0, 4, 0, 6, 7, 0]]
     assert oracle.compress_masked(w, m, dt).tolist() == [[1, 4, 6, 7]]
+
+
+# ---- patterns that hold for the matrix and its transpose (Sec. 6) ---------------------------------------------
+
+def _valid_4x4_patterns():
+    pats = []
+    for bits in range(1 << 16):
+        m = np.array([(bits >> i) & 1 for i in range(16)]).reshape(4, 4)
+        if (m.sum(0) == 2).all() and (m.sum(1) == 2).all():
+            pats.append(m.astype(bool))
+    return pats
+
+
+def test_transposable_patterns_number_ninety():
+    assert len(_valid_4x4_patterns()) == 90
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "i8"])
+def test_transposable_pruning_is_valid_both_ways_and_optimal(dt):
+    rng = np.random.default_rng(31)
+    M, K = 16, 24
+    vals = rng.integers(-9, 10, size=(M, K))                         # small integers: every sum is exact
+    A = vals.astype(np.int8) if dt == "i8" else synth.to_bits(vals.astype(np.float64), dt)
+    P = oracle.prune_transposable(A, dt)
+    kept = P != 0
+    # kept entries are copies, the pattern is 2:4 along rows and along columns
+    assert np.array_equal(P[kept], A[kept])
+    assert (kept.reshape(M, K // 4, 4).sum(2) <= 2).all() and (kept.T.reshape(K, M // 4, 4).sum(2) <= 2).all()
+    Pt = np.ascontiguousarray(P.T)
+    if K % 8 == 0 and M % 8 == 0:
+        assert np.array_equal(oracle.prune(P, dt), P) and np.array_equal(oracle.prune(Pt, dt), Pt)
+    # brute force over all 90 patterns of every block: the retained magnitude is the maximum
+    pats = _valid_4x4_patterns()
+    mag = np.abs(vals)
+    for bm in range(0, M, 4):
+        for bk in range(0, K, 4):
+            blk = mag[bm:bm + 4, bk:bk + 4]
+            best = max(int(blk[p].sum()) for p in pats)
+            got = np.abs(oracle.to_double(P[bm:bm + 4, bk:bk + 4], dt)).sum() if dt != "i8" else np.abs(P[bm:bm + 4, bk:bk + 4].astype(int)).sum()
+            assert int(got) == best
+    # never better than the one-directional rule, which has fewer constraints
+    one_way = np.abs(oracle.to_double(oracle.prune(A, dt), dt)).sum()
+    assert np.abs(oracle.to_double(P, dt)).sum() <= one_way
+
+
+def test_transposable_pruning_tie_rule_and_fixed_points():
+    ones = np.ones((4, 8), dtype=np.int8)
+    P = oracle.prune_transposable(ones, "i8")
+    # all sums tie: the first pattern in lexicographic order of the row pairs: (0,1) (0,1) (2,3) (2,3)
+    assert P[:, :4].tolist() == [[1, 1, 0, 0], [1, 1, 0, 0], [0, 0, 1, 1], [0, 0, 1, 1]]
+    assert np.array_equal(P[:, 4:], P[:, :4])
+    # a matrix that already satisfies both constraints is returned unchanged; so is the result of the search
+    Q = np.array([[5, 0, 0, 7], [0, 3, 2, 0], [0, 9, 0, 1], [4, 0, 6, 0]], dtype=np.int8)
+    assert np.array_equal(oracle.prune_transposable(Q, "i8"), Q)
+    A, _ = synth.make("tiny_f16", M=32, N=16, K=64, seed=8)
+    once = oracle.prune_transposable(A, "f16")
+    assert np.array_equal(oracle.prune_transposable(once, "f16"), once)
+    # one dominant entry per row and column is always kept
+    D = np.ones((4, 4), dtype=np.int8)
+    for i, j in enumerate([2, 0, 3, 1]):
+        D[i, j] = 100
+    assert (oracle.prune_transposable(D, "i8")[[0, 1, 2, 3], [2, 0, 3, 1]] == 100).all()
