@@ -133,6 +133,23 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
                             sp24_dtype t, sp24_layout l, void* stream);
 
 /*
+ * Sec. 6: a pattern that satisfies the 2:4 constraint along rows and along
+ * columns, so that the transposed matrix (the backward pass) can use the
+ * sparse product too.  The exhaustive search the paper names, per aligned
+ * 4 x 4 block: of the 90 patterns with exactly two kept entries in every row
+ * and every column the one whose kept magnitudes sum highest stays, the rest
+ * of the block becomes +0; kept entries are copied bit for bit.
+ * Made unique by: a pattern's sum is ((r0 + r1) + r2) + r3, r_i = the sum of
+ * row i's two kept magnitudes (lower column first), in binary64 for the 16-bit
+ * types and exactly for int8; NaN counts as +infinity; patterns are visited in
+ * lexicographic order of their four column pairs (pairs ordered (0,1) (0,2)
+ * (0,3) (1,2) (1,3) (2,3)) and only a strictly higher sum replaces the best.
+ * A, P as for sp24_prune; additionally M % 4 == 0, else SP24_ERR_SHAPE.
+ */
+sp24_status sp24_prune_transposable(const void* A, void* P, int64_t M, int64_t K, int64_t lda,
+                                    int64_t ldp, sp24_dtype t, void* stream);
+
+/*
  * Sec. 4.1 Step 3 (retraining keeps the pattern of Step 2; a removed weight
  * stays zero): P = W with every position that `meta` does not record set to
  * +0, recorded positions copied bit for bit.  W holds the dense weights after

@@ -116,6 +116,23 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
 }
 
 // x_bytes: extent of the NHWC input when a.conv.on (a.B then points at it), else unused
+sp24_status sp24_prune_transposable(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (M < 0 || M % 4 != 0 || !k_legal(K, t)) return SP24_ERR_SHAPE;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(A, M, K, lda, es);
+    if (s != SP24_OK) return s;
+    s = check_matrix(P, M, K, ldp, es);
+    if (s != SP24_OK) return s;
+    if (M > 0 && A == P && lda != ldp) return SP24_ERR_SHAPE;
+    if (M > 0 && A != P) {
+        size_t na = ((size_t)(M - 1) * lda + K) * es, np = ((size_t)(M - 1) * ldp + K) * es;
+        if (ranges_overlap(A, na, P, np)) return SP24_ERR_SHAPE;
+    }
+    return launch_prune_transposable(A, P, M, K, lda, ldp, t, static_cast<hipStream_t>(stream));
+}
+
 sp24_status sp24_mask_apply(const void* W, const void* meta, void* P, int64_t M, int64_t K, int64_t ldw, int64_t ldp, sp24_dtype t,
                             sp24_layout l, void* stream)
 {

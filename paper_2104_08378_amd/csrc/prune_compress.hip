@@ -7,6 +7,8 @@
 #include "common.hpp"
 #include "launch.hpp"
 
+#include <type_traits>
+
 namespace sp24 {
 
 // ---- per-group arithmetic ------------------------------------------------
@@ -126,6 +128,111 @@ __global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, ui
         }
     }
     *reinterpret_cast<uint4v*>(P + m * ldp_bytes + c * 16) = w;
+}
+
+// ---- patterns that also hold for the transposed matrix (Sec. 6) -----------
+// Exhaustive search per aligned 4x4 block over the 90 patterns with two kept entries in every row and column;
+// the one with the highest sum of kept magnitudes stays.  One lane per block.  To be reproducible bit for bit the
+// sum of a pattern is ((r0 + r1) + r2) + r3, r_i the sum of row i's two kept magnitudes (lower column first), in
+// double for the 16-bit types and in integers for int8; NaN counts as +infinity; patterns are visited in
+// lexicographic order of their row pairs, pairs ordered (0,1) (0,2) (0,3) (1,2) (1,3) (2,3); a later pattern
+// replaces the best only with a strictly higher sum.
+struct PatternTable {
+    uint8_t pair[90][4];
+};
+constexpr PatternTable make_pattern_table()
+{
+    constexpr int c0[6] = {0, 0, 0, 1, 1, 2}, c1[6] = {1, 2, 3, 2, 3, 3};
+    PatternTable t{};
+    int n = 0;
+    for (int p0 = 0; p0 < 6; ++p0)
+        for (int p1 = 0; p1 < 6; ++p1)
+            for (int p2 = 0; p2 < 6; ++p2)
+                for (int p3 = 0; p3 < 6; ++p3) {
+                    int count[4] = {0, 0, 0, 0};
+                    const int p[4] = {p0, p1, p2, p3};
+                    for (int i = 0; i < 4; ++i) { ++count[c0[p[i]]]; ++count[c1[p[i]]]; }
+                    if (count[0] == 2 && count[1] == 2 && count[2] == 2 && count[3] == 2) {
+                        for (int i = 0; i < 4; ++i) t.pair[n][i] = (uint8_t)p[i];
+                        ++n;
+                    }
+                }
+    return t;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_prune_transposable(const uint8_t* __restrict__ A, uint8_t* __restrict__ P, int64_t M4,
+                                                            int64_t K4, int64_t lda_bytes, int64_t ldp_bytes)
+{
+    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    using sum_t = typename std::conditional<DT == SP24_I8, int, double>::type;
+    constexpr PatternTable table = make_pattern_table();
+    constexpr int c0[6] = {0, 0, 0, 1, 1, 2}, c1[6] = {1, 2, 3, 2, 3, 3};
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= M4 * K4) return;
+    const int64_t bm = id / K4, bk = id - bm * K4;
+    uint32_t raw[4][2];                                   // a row of the block: 4 or 8 bytes
+    sum_t r[4][6];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint8_t* src = A + (bm * 4 + i) * lda_bytes + bk * (4 * ES);
+        sum_t mag[4];
+        if constexpr (DT == SP24_I8) {
+            raw[i][0] = *reinterpret_cast<const uint32_t*>(src);
+            raw[i][1] = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mag[j] = (int)mag_key8((raw[i][0] >> (8 * j)) & 0xFFu);
+        } else {
+            const uint2v w = *reinterpret_cast<const uint2v*>(src);
+            raw[i][0] = w[0];
+            raw[i][1] = w[1];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t bits = (raw[i][j >> 1] >> (16 * (j & 1))) & 0x7FFFu;      // sign cleared
+                float f;
+                if constexpr (DT == SP24_F16) f = (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+                else f = __uint_as_float(bits << 16);
+                mag[j] = (f != f) ? (double)__builtin_inff() : (double)f;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < 6; ++p) r[i][p] = mag[c0[p]] + mag[c1[p]];
+    }
+    int best = 0;
+    sum_t best_sum = (sum_t)-1;
+#pragma unroll
+    for (int e = 0; e < 90; ++e) {
+        const sum_t sum = ((r[0][table.pair[e][0]] + r[1][table.pair[e][1]]) + r[2][table.pair[e][2]]) + r[3][table.pair[e][3]];
+        if (sum > best_sum) {
+            best_sum = sum;
+            best = e;
+        }
+    }
+    // pair indices of the winner, 3 bits per row, looked up without indexing memory by a lane-dependent value
+    uint32_t win = 0;
+#pragma unroll
+    for (int e = 0; e < 90; ++e) {
+        const uint32_t packed = table.pair[e][0] | (table.pair[e][1] << 3) | (table.pair[e][2] << 6) | (table.pair[e][3] << 9);
+        win = (best == e) ? packed : win;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t p = (win >> (3 * i)) & 7u;
+        // columns of pair p: c0 = {0,0,0,1,1,2}, c1 = {1,2,3,2,3,3} as 2-bit fields of two constants
+        const uint32_t k0 = (0x940u >> (2 * p)) & 3u, k1 = (0xFB9u >> (2 * p)) & 3u;
+        const uint32_t keep = (1u << k0) | (1u << k1);
+        uint8_t* dst = P + (bm * 4 + i) * ldp_bytes + bk * (4 * ES);
+        if constexpr (DT == SP24_I8) {
+            *reinterpret_cast<uint32_t*>(dst) = prune8(raw[i][0], keep);
+        } else {
+            uint32_t w0 = raw[i][0], w1 = raw[i][1];
+            prune16(w0, w1, keep);
+            uint2v w;
+            w[0] = w0;
+            w[1] = w1;
+            *reinterpret_cast<uint2v*>(dst) = w;
+        }
+    }
 }
 
 // ---- compress, canonical layout -------------------------------------------
@@ -345,6 +452,19 @@ sp24_status launch_prune(const void* A, void* P, int64_t M, int64_t K, int64_t l
     if (t == SP24_F16) run_prune<SP24_F16>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
     else if (t == SP24_BF16) run_prune<SP24_BF16>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
     else run_prune<SP24_I8>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
+    return launch_result();
+}
+
+sp24_status launch_prune_transposable(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t, hipStream_t st)
+{
+    if (M * K == 0) return SP24_OK;
+    const int64_t M4 = M / 4, K4 = K / 4;
+    const dim3 grid(blocks_for(M4 * K4));
+    const uint8_t* a = (const uint8_t*)A;
+    uint8_t* p = (uint8_t*)P;
+    if (t == SP24_F16) k_prune_transposable<SP24_F16><<<grid, 256, 0, st>>>(a, p, M4, K4, lda * 2, ldp * 2);
+    else if (t == SP24_BF16) k_prune_transposable<SP24_BF16><<<grid, 256, 0, st>>>(a, p, M4, K4, lda * 2, ldp * 2);
+    else k_prune_transposable<SP24_I8><<<grid, 256, 0, st>>>(a, p, M4, K4, lda, ldp);
     return launch_result();
 }
 

@@ -44,6 +44,7 @@ def lib():
         L.sp24_prune.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp]
         L.sp24_compress.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.sp24_decompress.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
+        L.sp24_prune_transposable.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp]
         L.sp24_mask_apply.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, i32, vp]
         L.sp24_compress_masked.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
@@ -57,7 +58,7 @@ def lib():
         L.sp24_conv2d_dense_i8_scaled.argtypes = [vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i64, vp, f32, vp, i32, f32, i32, vp]
         L.sp24_status_string.argtypes = [i32]
         L.sp24_status_string.restype = ctypes.c_char_p
-        for name in ("sp24_mask_apply", "sp24_compress_masked", "sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
+        for name in ("sp24_prune_transposable", "sp24_mask_apply", "sp24_compress_masked", "sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
                      "sp24_conv2d_dense", "sp24_spmm_i8_scaled", "sp24_gemm_dense_i8_scaled",
                      "sp24_spmm_conv2d_i8_scaled", "sp24_conv2d_dense_i8_scaled"):
             getattr(L, name).restype = i32
@@ -131,6 +132,16 @@ def sp24_decompress(V, meta, layout="canonical", out=None):
     P = torch.empty((M, K), dtype=V.dtype, device=V.device) if out is None else _rowmajor(out, "out")
     _check(lib().sp24_decompress(V.data_ptr(), meta.data_ptr(), P.data_ptr(), M, K, P.stride(0), _DT[V.dtype],
                                  _LAYOUT[layout], _stream()), "sp24_decompress")
+    return P
+
+
+def sp24_prune_transposable(A, out=None):
+    """2:4 along rows and along columns: per 4x4 block the two-per-row-and-column pattern that keeps the most magnitude."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_prune_transposable(A.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype], _stream()),
+           "sp24_prune_transposable")
     return P
 
 

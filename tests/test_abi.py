@@ -156,3 +156,16 @@ def test_fixed_mask_validation():
     assert comp(W, Mt, 0, 64, 64, 64, sp24.I8, 0, None) == NULL and comp(W, 0, V, 64, 64, 64, sp24.I8, 0, None) == NULL
     assert comp(W, Mt, W, 64, 64, 64, sp24.I8, 0, None) == SHAPE and comp(W, Mt, V, 64, 48, 64, sp24.I8, 0, None) == SHAPE
     assert comp(W, Mt, V, 0, 64, 64, sp24.I8, 0, None) == OK
+
+
+def test_transposable_pruning_validation():
+    L = sp24.lib()
+    A, Pp = P, P + 0x1000000
+    f = L.sp24_prune_transposable
+    assert f(A, Pp, 64, 64, 64, 64, sp24.F32, None) == DTYPE
+    assert f(A, Pp, 62, 64, 64, 64, sp24.F16, None) == SHAPE          # M % 4
+    assert f(A, Pp, 64, 24, 64, 64, sp24.F16, None) == SHAPE          # K % 16
+    assert f(A, Pp, 64, 64, 32, 64, sp24.F16, None) == SHAPE
+    assert f(0, Pp, 64, 64, 64, 64, sp24.F16, None) == NULL and f(A, Pp + 4, 64, 64, 64, 64, sp24.F16, None) == ALIGN
+    assert f(A, A + 64, 64, 64, 64, 64, sp24.I8, None) == SHAPE       # partial overlap
+    assert f(A, Pp, 0, 64, 64, 64, sp24.F16, None) == OK

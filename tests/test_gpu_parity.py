@@ -123,6 +123,28 @@ def test_fixed_mask_operations_bit_exact(dtype, layout):
         assert torch.equal(sp24.sp24_compress_masked(Ad, meta, layout=layout).view(torch.uint8), V0.view(torch.uint8))
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_transposable_pruning_bit_exact(dtype):
+    """Sec. 6: the exhaustive 4x4-block search; the result and its transpose both compress without loss."""
+    for i, (M, K) in enumerate([(4, 32), (36, 96), (128, 256), (260, 1056)]):
+        A = adversarial(dtype, M, K, 50 + i) if i == 1 else synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=30 + i)[0]
+        Ad = to_gpu(A, dtype)
+        P = sp24.sp24_prune_transposable(Ad)
+        Q = Ad.clone()
+        sp24.sp24_prune_transposable(Q, out=Q)
+        torch.cuda.synchronize()
+        want = oracle.prune_transposable(A, dtype)
+        assert np.array_equal(to_bits(P), want), (dtype, M, K)
+        assert np.array_equal(to_bits(Q), want)
+    # the pruned matrix and its transpose are both fixed points of one-directional pruning (both are 2:4)
+    M = K = 128
+    A = synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=77)[0]
+    P = sp24.sp24_prune_transposable(to_gpu(A, dtype))
+    Pt = P.t().contiguous()
+    assert torch.equal(sp24.sp24_prune(P).view(torch.uint8), P.view(torch.uint8))
+    assert torch.equal(sp24.sp24_prune(Pt).view(torch.uint8), Pt.view(torch.uint8))
+
+
 MM_CASES = [
     # dtype, out, M, N, K
     ("f16", "f32", 32, 32, 64),
