@@ -53,6 +53,10 @@ def parse():
     p.add_argument("--only", default="", help="comma list of ops to run in a step (profiling aid); default all")
     p.add_argument("--materialised", action="store_true",
                    help="conv3x3_f16 only: multiply by the im2col matrix built beforehand instead of gathering it implicitly")
+    p.add_argument("--extras", action="store_true",
+                   help="also time the operations beyond the five-step path on this workload's operands: the retraining "
+                        "support (mask apply, fixed-mask compress, row-and-column pruning) and, for int8, the product "
+                        "with the quantised path's epilogue; each beside the CPU oracle on a sample")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one 1 GiB device copy, so that a counter profile of this run holds a kernel of known traffic")
     return p.parse_args()
@@ -84,6 +88,66 @@ def cpu_baseline(name, A, Bt, budget_s):
     return {"value": 2.0 * rows * cols * K / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"first {rows} rows of A x first {cols} columns of B, K={K}: compress + decompress + "
                       f"{'int32' if dt == 'i8' else 'fp64'} triple loop, {t:.1f} s"}
+
+
+def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
+    """Back-to-back timings of the operations outside the five-step path, each with its algorithmic bytes against
+    the HBM peak (or, for the scaled product, dense-equivalent op/s), and the oracle's time on the first rows."""
+    import numpy as np
+    import oracle
+    import torch
+    from paper_2104_08378_amd import sp24, synth
+    w = synth.WORKLOADS[name]
+    dt, M, K, N = w["dtype"], w["M"], w["K"], w["N"]
+    es = 1 if dt == "i8" else 2
+    R = len(As)
+
+    def timed(fn):
+        for i in range(3):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e-3
+
+    rows = min(M, 512)
+    sample = np.ascontiguousarray(A_host[:rows])
+    _, smeta = oracle.compress(sample, dt)
+
+    def cpu(fn):
+        t0 = time.perf_counter()
+        fn()
+        return (time.perf_counter() - t0) * M / rows       # scaled from `rows` rows to the whole matrix
+
+    Pm = torch.empty_like(As[0])
+    Vm = torch.empty_like(V)
+    out = {}
+    ops = {
+        "mask_apply": (lambda i: sp24.sp24_mask_apply(As[i % R], meta, layout="tiled", out=Pm), 2.0 * M * K * es + M * K / 8,
+                       lambda: oracle.mask_apply(sample, smeta, dt)),
+        "compress_masked": (lambda i: sp24.sp24_compress_masked(As[i % R], meta, layout="tiled", out=Vm), 1.5 * M * K * es + M * K / 8,
+                            lambda: oracle.compress_masked(sample, smeta, dt)),
+        "prune_transposable": (lambda i: sp24.sp24_prune_transposable(As[i % R], out=Pm), 2.0 * M * K * es,
+                               lambda: oracle.prune_transposable(sample, dt)),
+    }
+    for op, (fn, nbytes, cfn) in ops.items():
+        t = timed(fn)
+        out[op] = {"us": t * 1e6, "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / PEAK_HBM,
+                   "cpu_oracle_us_scaled_from_%d_rows" % rows: cpu(cfn) * 1e6}
+    if dt == "i8" and not conv:
+        ws = torch.full((M,), 1.0e-3, dtype=torch.float32, device="cuda")
+        bs = torch.zeros(M, dtype=torch.float32, device="cuda")
+        D8, D8d = torch.empty((M, N), dtype=torch.int8, device="cuda"), torch.empty((M, N), dtype=torch.int8, device="cuda")
+        ts = timed(lambda i: sp24.sp24_spmm_i8_scaled(V, meta, Bs[i % R], torch.int8, ws, 0.02, bs, True, 30.0, layout="tiled", out=D8))
+        td = timed(lambda i: sp24.sp24_gemm_dense_i8_scaled(P, Bs[i % R], torch.int8, ws, 0.02, bs, True, 30.0, out=D8d))
+        out["spmm_i8_scaled_int8_out"] = {"us": ts * 1e6, "dense_us": td * 1e6, "speedup_vs_dense": td / ts,
+                                          "dense_equiv_Tops": 2.0 * M * N * K / ts / 1e12,
+                                          "frac_of_sparse_peak": M * N * K / ts / PEAK_DENSE[dt]}
+    return out
 
 
 def main():
@@ -233,6 +297,8 @@ def main():
         "decompress_GBps": bytes_pc / (ms["decompress"] * 1e-3) / 1e9 if "decompress" in only else None,
         "roofline": roof,
     }
+    if args.extras:
+        line["extras"] = extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A, args.steps, conv)
     if args.cpu_seconds > 0:
         line["cpu_baseline"] = cpu_baseline(name, A, Bt, args.cpu_seconds)
     print(json.dumps(line))
