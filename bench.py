@@ -85,9 +85,17 @@ def cpu_baseline(name, A, Bt, budget_s):
     rows = int(max(rows, min(w["M"], rows * budget_s / max(t, 1e-3))))   # scale the sample to the budget
     rows -= rows % 32
     t = run(rows)
-    return {"value": 2.0 * rows * cols * K / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+    cores = oracle.threads()
+    # the same on one thread, on a sample cut down by the thread count
+    rows1 = max(32, rows // max(cores, 1) // 32 * 32)
+    before = oracle.set_threads(1)
+    t1 = run(rows1)
+    oracle.set_threads(before)
+    return {"value": 2.0 * rows * cols * K / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "sample": f"first {rows} rows of A x first {cols} columns of B, K={K}: compress + decompress + "
-                      f"{'int32' if dt == 'i8' else 'fp64'} triple loop, {t:.1f} s"}
+                      f"{'int32' if dt == 'i8' else 'fp64'} triple loop, {t:.1f} s",
+            "value_one_thread": 2.0 * rows1 * cols * K / t1 / 1e12,
+            "sample_one_thread": f"first {rows1} rows, {t1:.1f} s"}
 
 
 def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):

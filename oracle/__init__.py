@@ -248,3 +248,8 @@ def to_double(bits, dtype):
 
 def threads():
     return int(_load().sp24o_threads())
+
+
+def set_threads(n):
+    """Use n OpenMP threads from now on; returns the previous count."""
+    return int(_load().sp24o_set_threads(int(n)))

@@ -483,6 +483,20 @@ int sp24o_requant_i8(const int32_t *acc, int8_t *Q, long M, long N, const float 
     return 0;
 }
 
+/* number of OpenMP threads the row loops use from now on (n >= 1); returns the previous maximum */
+int sp24o_set_threads(int n)
+{
+#ifdef _OPENMP
+    int before = omp_get_max_threads();
+    if (n >= 1)
+        omp_set_num_threads(n);
+    return before;
+#else
+    (void)n;
+    return 1;
+#endif
+}
+
 int sp24o_threads(void)
 {
 #ifdef _OPENMP
