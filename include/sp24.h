@@ -31,7 +31,8 @@
  *     (ld * element_size % 16 == 0); B and D need only the alignment of their
  *     element type and any leading dimension that covers a row.  Otherwise
  *     SP24_ERR_ALIGN.  (The fast product kernels are chosen when B and D rows
- *     are 16-byte aligned too; other cases run a general kernel.)
+ *     are 16-byte aligned too -- for N-major B also N * element size a
+ *     multiple of 16; other cases run a general kernel.)
  *   - K must be a multiple of 16 for 16-bit types and of 32 for int8
  *     (the dimension rule of Sec. 3.2 / Sec. 4.2, applied to the inner
  *     dimension), else SP24_ERR_SHAPE.  M and N may be any positive value; a

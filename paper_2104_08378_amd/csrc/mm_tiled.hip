@@ -19,6 +19,12 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
     bool ok = a.bo == SP24_B_KMAJOR && a.K % (kStepBytes / es) == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 &&
               (a.ldb * es) % 16 == 0 && a.N >= 32 && a.M >= 64 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
               a.ldb * es < ((int64_t)1 << 22) && ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
+    if (!a.conv.on && a.bo == SP24_B_NMAJOR) {
+        // N-major B: whole 16-byte chunks of columns, rows 16-byte aligned, 32-bit row offsets within a step
+        ok = a.K % (kStepBytes / es) == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 && (a.ldb * es) % 16 == 0 &&
+             (a.N * es) % 16 == 0 && a.N >= 32 && a.M >= 64 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
+             a.ldb * es < ((int64_t)1 << 22) && ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
+    }
     if (a.conv.on) {
         // implicit GEMM: a step must lie inside one filter tap, and byte offsets into the input must fit 31 bits
         // (N / (OH*OW) images of H*W*C elements, plus the virtual pixels of the padding)

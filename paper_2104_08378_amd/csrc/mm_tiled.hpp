@@ -159,6 +159,86 @@ struct conv_rows {
     }
 };
 
+// ---------------------------------------------------------------------------
+// B stored N-major (element (k, n) at B[k*ldb + n]).  A stage then holds the step's K rows, each the tile's BN
+// columns (BN * element size bytes, 16-byte chunks swizzled by row), and a wavefront reads its fragments with
+// the transposing LDS reads of gfx950: in every group of 16 lanes, lane l receives from the 8-byte pieces the
+// 16 lanes address
+//     ds_read_b64_tr_b8 :  byte j (0..7)    = byte l % 8 of the piece of lane 2*j + l / 8
+//     ds_read_b64_tr_b16:  element j (0..3) = element l % 4 of the piece of lane 4*j + l / 4
+// (measured).  With lane s of a group addressing row k0 + s/2 (s/4), columns 8*(s%2).. (4*(s%4)..), lane l gets
+// column l of the group's 16 columns, rows k0 .. k0+7 (k0+3): K-contiguous values, as the matrix cores want them.
+// ---------------------------------------------------------------------------
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef int int2v __attribute__((ext_vector_type(2)));
+
+// swizzle of the 16-byte chunks of row k: rows that one transposing read touches land in different banks
+template <int ES>
+__device__ __forceinline__ int nmajor_swizzle(int k, int chunks)
+{
+    return (ES == 1) ? ((2 * (k & 7)) & (chunks - 1)) : (4 * (k & 3));
+}
+
+// Offsets (from the tile's first column of the step's first row) of the B transfers of one of NW wavefronts:
+// LDS position p of the B region <- row p / row_bytes, chunk (p % row_bytes) / 16 ^ swizzle(row); chunks past the
+// last column of the matrix are replaced by the last valid one (never stored).
+template <int BN, int NW, int ES>
+__device__ __forceinline__ void dma_offsets_nmajor(int64_t col0, int64_t N, int64_t ld_bytes, int wave, int lane, uint32_t (&off)[BN / 8 / NW])
+{
+    constexpr int kRowB = BN * ES, kChunks = kRowB / 16;
+    const int64_t left = (N - col0) * ES / 16;
+    const int valid = left < kChunks ? (int)left : kChunks;
+#pragma unroll
+    for (int j = 0; j < BN / 8 / NW; ++j) {
+        const int p = (wave * (BN / 8 / NW) + j) * 1024 + lane * 16;
+        const int row = p / kRowB;
+        int c = ((p % kRowB) >> 4) ^ nmajor_swizzle<ES>(row, kChunks);
+        if (c >= valid) c = valid - 1;
+        off[j] = (uint32_t)(row * ld_bytes + c * 16);
+    }
+}
+
+// Per-lane addressing of the transposing fragment reads: piece c2 (16 K-bytes at K-byte offset 16*(2*c2 + q) of
+// the step) of column (wavefront's first column + 32*nj + lane % 32).
+template <int BN, int TN, int ES>
+struct nmajor_frags {
+    static constexpr int kRowB = BN * ES, kChunks = kRowB / 16;
+    static constexpr int kRowsPerC2 = 32 / ES;        // K rows per unit of c2 (two pieces: q = 0, 1)
+    static constexpr int kRowsPerRead = 8 / ES;       // K rows one transposing read covers
+    int row_off;                                      // bytes: this lane's source row
+    int col_off[TN];                                  // bytes within the row, swizzled, per 32-column block
+    __device__ __forceinline__ void init(int wn, int lane)
+    {
+        const int g = lane >> 4, s = lane & 15, q = g >> 1;
+        const int sub = (ES == 1) ? (s >> 1) : (s >> 2);                       // row inside one read
+        const int col_in_group = (ES == 1) ? 8 * (s & 1) : 8 * (s & 3);        // bytes
+        row_off = ((kRowsPerC2 / 2) * q + sub) * kRowB;
+        const int swz = nmajor_swizzle<ES>(sub, kChunks);
+#pragma unroll
+        for (int nj = 0; nj < TN; ++nj) {
+            const int bytes = (wn * 32 * TN + nj * 32 + 16 * (g & 1)) * ES + col_in_group;
+            col_off[nj] = (((bytes >> 4) ^ swz) << 4) + (bytes & 15);
+        }
+    }
+    // the 16 bytes of piece 2*c2 + q for this lane's column of block nj; `b` = start of the B region of a stage
+    __device__ __forceinline__ uint4v piece(const uint8_t* b, int c2, int nj) const
+    {
+        const uint8_t* p0 = b + row_off + col_off[nj] + c2 * kRowsPerC2 * kRowB;
+        const uint8_t* p1 = p0 + kRowsPerRead * kRowB;
+        uint4v v;
+        if constexpr (ES == 1) {
+            const int2v x = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) int2v*)p0);
+            const int2v y = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) int2v*)p1);
+            v[0] = (uint32_t)x[0]; v[1] = (uint32_t)x[1]; v[2] = (uint32_t)y[0]; v[3] = (uint32_t)y[1];
+        } else {
+            const int2v x = __builtin_bit_cast(int2v, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p0));
+            const int2v y = __builtin_bit_cast(int2v, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)p1));
+            v[0] = (uint32_t)x[0]; v[1] = (uint32_t)x[1]; v[2] = (uint32_t)y[0]; v[3] = (uint32_t)y[1];
+        }
+        return v;
+    }
+};
+
 template <int ROWS, int NW>
 __device__ __forceinline__ void dma_rows(const uint8_t* base, const uint32_t (&off)[ROWS / 8 / NW], uint8_t* stage, int wave)
 {
@@ -237,9 +317,11 @@ __device__ __forceinline__ void store_wave_tile(const MmArgs& a, typename acc_of
 // NS stages; the transfers for step s+NS-1 are issued during step s, and the
 // first operands of step s+1 are read from LDS during the tail of step s.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, bool CONV>
+// BSRC: where B comes from -- 0 a K-major matrix, 1 NHWC activations (implicit GEMM), 2 an N-major matrix
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, int BSRC>
 __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
+    constexpr bool CONV = BSRC == 1, NMAJ = BSRC == 2;
     constexpr int ES = (DT == SP24_I8) ? 1 : 2;
     constexpr int BK = kRowBytes / ES;        // K elements per step
     constexpr int T64 = BK / 64;              // 32x64 A tiles per step and row block (2 for int8, 1 for 16-bit)
@@ -271,10 +353,13 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
 
     // ---- transfers of this wavefront ----
     const int64_t ldb_bytes = a.ldb * ES;
-    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
+    // K-major: the tile's first row of B, a step is 128 bytes further; N-major: its first column, a step BK rows further
+    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (NMAJ ? (int64_t)tn * BN * ES : (int64_t)tn * BN * ldb_bytes);
+    const int64_t b_step = NMAJ ? (int64_t)BK * ldb_bytes : (int64_t)kRowBytes;
     uint32_t b_off[NJB];
     conv_rows<BN, NW, ES> b_conv;
     if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
+    else if constexpr (NMAJ) dma_offsets_nmajor<BN, NW, ES>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
     else dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
     // V: transfer x of this wavefront is 1 KiB number (wave*NJV + x) of the RB*2 of a step: row block /2, half %2
     const uint8_t* v_base[NJV];                            // wavefront-uniform; lane l adds 16*l
@@ -303,7 +388,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
         uint8_t* stg = stage_ptr(u);
         if (x < NJB) {
             if constexpr (CONV) b_conv.issue(x, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stg, wave);
-            else lds_dma16(b_blk + (int64_t)step * kRowBytes, b_off[x], stg + (wave * NJB + x) * 1024);
+            else lds_dma16(b_blk + (int64_t)step * b_step, b_off[x], stg + (wave * NJB + x) * 1024);
         }
         else if (x < NJB + NJV) lds_dma16(v_base[x - NJB] + (int64_t)step * 2048, lane16, stg + kVOff + (wave * NJV + x - NJB) * 1024);
         else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * (T64 * 256), lane4, stg + kMOff + (wave * NJM + x - NJB - NJV) * 256);
@@ -333,6 +418,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     int frag_off[4];
 #pragma unroll
     for (int c2 = 0; c2 < 4; ++c2) frag_off[c2] = (wn * 32 * TN + r) * kRowBytes + ((((2 * c2) | q) ^ ((r >> 1) & 7)) << 4);
+    nmajor_frags<BN, TN, ES> b_nm;
+    if constexpr (NMAJ) b_nm.init(wn, lane);
     const int va_off = kVOff + wm * TM * 2048 + lane * 16;
     const int ma_off = kMOff + wm * TM * T64 * 256 + lane * 4;
 
@@ -349,8 +436,14 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
         const int j = t / TN, nj = t % TN;
         // K-byte offset of the two pieces of instruction j: (int8) 64j + 32h + 16q, (16-bit) 64h + 32j + 16q
         const int c2lo = (DT == SP24_I8) ? 2 * j : j, c2hi = (DT == SP24_I8) ? 2 * j + 1 : 2 + j;
-        uint4v lo = *reinterpret_cast<const uint4v*>(base + frag_off[c2lo] + nj * 32 * kRowBytes);
-        uint4v hi = *reinterpret_cast<const uint4v*>(base + frag_off[c2hi] + nj * 32 * kRowBytes);
+        uint4v lo, hi;
+        if constexpr (NMAJ) {
+            lo = b_nm.piece(base, c2lo, nj);
+            hi = b_nm.piece(base, c2hi, nj);
+        } else {
+            lo = *reinterpret_cast<const uint4v*>(base + frag_off[c2lo] + nj * 32 * kRowBytes);
+            hi = *reinterpret_cast<const uint4v*>(base + frag_off[c2hi] + nj * 32 * kRowBytes);
+        }
         bv[0] = lo[0]; bv[1] = lo[1]; bv[2] = lo[2]; bv[3] = lo[3];
         bv[4] = hi[0]; bv[5] = hi[1]; bv[6] = hi[2]; bv[7] = hi[3];
     };
@@ -447,9 +540,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
 // through LDS (A is plain row-major, so its fragments are not contiguous in
 // memory); NS stages, transfers NS - 1 steps ahead.
 // ---------------------------------------------------------------------------
-template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, bool CONV>
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, int BSRC>
 __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
+    constexpr bool CONV = BSRC == 1, NMAJ = BSRC == 2;
     constexpr int ES = (DT == SP24_I8) ? 1 : 2;
     constexpr int BK = kRowBytes / ES;
     constexpr int NW = WM * WN;
@@ -472,12 +566,16 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
 
     const int64_t lda_bytes = a.lda * ES, ldb_bytes = a.ldb * ES;
     const uint8_t* a_blk = reinterpret_cast<const uint8_t*>(a.A) + (int64_t)tm * BM * lda_bytes;
-    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)tn * BN * ldb_bytes;
+    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (NMAJ ? (int64_t)tn * BN * ES : (int64_t)tn * BN * ldb_bytes);
+    const int64_t b_step = NMAJ ? (int64_t)BK * ldb_bytes : (int64_t)kRowBytes;
     uint32_t a_off[NJA], b_off[NJB];
     dma_offsets<BM, NW>((int64_t)tm * BM, a.M, lda_bytes, wave, lane, a_off);
     conv_rows<BN, NW, ES> b_conv;
     if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
+    else if constexpr (NMAJ) dma_offsets_nmajor<BN, NW, ES>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
     else dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
+    nmajor_frags<BN, TN, ES> b_nm;
+    if constexpr (NMAJ) b_nm.init(wn, lane);
 
     acc_t acc[TM][TN];
 #pragma unroll
@@ -493,7 +591,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
 #pragma unroll
             for (int j = 0; j < NJB; ++j)
                 b_conv.issue(j, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stage_ptr(u) + BM * kRowBytes, wave);
-        } else dma_rows<BN, NW>(b_blk + (int64_t)step * kRowBytes, b_off, stage_ptr(u) + BM * kRowBytes, wave);
+        } else dma_rows<BN, NW>(b_blk + (int64_t)step * b_step, b_off, stage_ptr(u) + BM * kRowBytes, wave);
     };
     // the step whose transfers are issued next, NS - 1 ahead of the arithmetic; it stops at the last step, which
     // is then fetched again into stages nobody reads
@@ -522,7 +620,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
 #pragma unroll
             for (int i = 0; i < TM; ++i) xa[i] = *reinterpret_cast<const int4v*>(base + fa_off[jj] + i * 32 * kRowBytes);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) xb[j] = *reinterpret_cast<const int4v*>(base + fb_off[jj] + j * 32 * kRowBytes);
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (NMAJ) xb[j] = __builtin_bit_cast(int4v, b_nm.piece(base + BM * kRowBytes, jj, j));
+                else xb[j] = *reinterpret_cast<const int4v*>(base + fb_off[jj] + j * 32 * kRowBytes);
+            }
         };
         read_frags(0, fa[0], fb[0]);
 #pragma unroll
@@ -591,11 +692,13 @@ static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WM * WN);
     if (a.sparse) {
-        if (a.conv.on) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, true><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
-        else k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, false><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        if (a.conv.on) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 1><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else if (a.bo == SP24_B_NMAJOR) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 2><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 0><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
     } else {
-        if (a.conv.on) k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, true><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
-        else k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, false><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        if (a.conv.on) k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, 1><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else if (a.bo == SP24_B_NMAJOR) k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, 2><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        else k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, 0><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
     }
     return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;
 }

@@ -218,6 +218,29 @@ def test_dense_tiled_kernels_match_oracle(case):
     run_mm_case(*case, layout="canonical", b_order="k", sparse=False, seed=3)
 
 
+NMAJOR_CASES = [
+    # B stored N-major (element (k, n) at B[k*ldb + n]) on the tiled kernels: transposing LDS reads
+    ("i8", "i32", 320, 304, 256),         # 128x128 tiles, ragged N (a whole number of 16-byte chunks)
+    ("bf16", "bf16", 512, 520, 192),
+    ("f16", "f32", 192, 1000, 128),
+    ("i8", "i32", 4096, 3328, 640),       # 256x256 tiles, 5 steps
+    ("bf16", "bf16", 3328, 4096, 448),
+    ("f16", "f16", 4096, 3320, 128),      # ragged N on the eight-wavefront shape
+    ("i8", "i32", 4352, 4000, 384),
+    ("i8", "i32", 320, 300, 256),         # N not a whole number of chunks: the general kernel
+]
+
+
+@pytest.mark.parametrize("case", NMAJOR_CASES)
+def test_spmm_n_major_b_matches_oracle(case):
+    run_mm_case(*case, layout="tiled", b_order="n", sparse=True, seed=6)
+
+
+@pytest.mark.parametrize("case", NMAJOR_CASES)
+def test_dense_n_major_b_matches_oracle(case):
+    run_mm_case(*case, layout="canonical", b_order="n", sparse=False, seed=7)
+
+
 SKINNY_CASES = [
     ("bf16", "bf16", 256, 16, 1024),
     ("f16", "f32", 96, 7, 576),       # ragged N, K split unevenly over the wavefronts
