@@ -1,14 +1,22 @@
 // Tiled product kernels: which problems they take, and the per-type entry points.  The kernels themselves are
-// templates in mm_tiled.hpp; each input type is instantiated in a translation unit of its own
-// (mm_tiled_f16.hip, mm_tiled_bf16.hip, mm_tiled_i8.hip) so that they compile side by side.
+// templates in mm_tiled.hpp; each pair of input and output type is instantiated in a
+// translation unit of its own (mm_tiled_<in>_<out>.hip) so that they compile side by side.
 #include "common.hpp"
 #include "launch.hpp"
 
 namespace sp24 {
 
-sp24_status tiled_f16(const MmArgs& a, hipStream_t st);
-sp24_status tiled_bf16(const MmArgs& a, hipStream_t st);
-sp24_status tiled_i8(const MmArgs& a, hipStream_t st);
+sp24_status tiled_f16_f32(const MmArgs& a, hipStream_t st);
+sp24_status tiled_f16_f16(const MmArgs& a, hipStream_t st);
+sp24_status tiled_f16_bf16(const MmArgs& a, hipStream_t st);
+sp24_status tiled_bf16_f32(const MmArgs& a, hipStream_t st);
+sp24_status tiled_bf16_f16(const MmArgs& a, hipStream_t st);
+sp24_status tiled_bf16_bf16(const MmArgs& a, hipStream_t st);
+sp24_status tiled_i8_i32(const MmArgs& a, hipStream_t st);
+sp24_status tiled_i8_i8(const MmArgs& a, hipStream_t st);
+sp24_status tiled_i8_f32(const MmArgs& a, hipStream_t st);
+sp24_status tiled_i8_f16(const MmArgs& a, hipStream_t st);
+sp24_status tiled_i8_bf16(const MmArgs& a, hipStream_t st);
 
 constexpr int kStepBytes = 128;   // bytes of one operand row consumed per step (kRowBytes of the kernels)
 
@@ -39,9 +47,21 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
     else ok = ok && a.lda * es < ((int64_t)1 << 22);
     if (!ok) return SP24_OK;
     *handled = true;
-    if (a.in == SP24_I8) return tiled_i8(a, st);
-    if (a.in == SP24_F16) return tiled_f16(a, st);
-    return tiled_bf16(a, st);
+    if (a.in == SP24_I8) {
+        if (a.out == SP24_I32) return tiled_i8_i32(a, st);
+        if (a.out == SP24_I8) return tiled_i8_i8(a, st);
+        if (a.out == SP24_F32) return tiled_i8_f32(a, st);
+        if (a.out == SP24_F16) return tiled_i8_f16(a, st);
+        return tiled_i8_bf16(a, st);
+    }
+    if (a.in == SP24_F16) {
+        if (a.out == SP24_F32) return tiled_f16_f32(a, st);
+        if (a.out == SP24_F16) return tiled_f16_f16(a, st);
+        return tiled_f16_bf16(a, st);
+    }
+    if (a.out == SP24_F32) return tiled_bf16_f32(a, st);
+    if (a.out == SP24_F16) return tiled_bf16_f16(a, st);
+    return tiled_bf16_bf16(a, st);
 }
 
 } // namespace sp24
