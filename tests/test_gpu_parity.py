@@ -241,6 +241,36 @@ def test_dense_n_major_b_matches_oracle(case):
     run_mm_case(*case, layout="canonical", b_order="n", sparse=False, seed=7)
 
 
+@pytest.mark.parametrize("dtype,out,M,N,K", [("i8", "i32", 256, 384, 256), ("bf16", "bf16", 4096, 3328, 128), ("f16", "f32", 128, 16, 512)])
+@pytest.mark.parametrize("b_order", ["k", "n"])
+def test_leading_dimensions_larger_than_the_rows(dtype, out, M, N, K, b_order):
+    """A, B and D as windows of wider buffers (lda > K, ldb > K or N, ldd > N): tiled, skinny and dense kernels."""
+    A, Bt = synth.make(NAME_OF[dtype], M=M, N=N, K=K, seed=11)
+    Pn = oracle.prune(A, dtype)
+    ref = oracle.gemm(Pn, np.ascontiguousarray(Bt.T), dtype)
+    pad = 64
+    Bsrc = to_gpu(Bt, dtype) if b_order == "k" else to_gpu(np.ascontiguousarray(Bt.T), dtype)
+    Bbuf = torch.zeros((Bsrc.shape[0], Bsrc.shape[1] + pad), dtype=Bsrc.dtype, device="cuda")
+    Bbuf[:, :Bsrc.shape[1]] = Bsrc
+    Bv = Bbuf[:, :Bsrc.shape[1]]
+    Abuf = torch.zeros((M, K + pad), dtype=Bsrc.dtype, device="cuda")
+    Abuf[:, :K] = to_gpu(Pn, dtype)
+    V, meta = sp24.sp24_compress(to_gpu(A, dtype), layout="tiled")
+    for sparse in (True, False):
+        Dbuf = torch.full((M, N + pad), 7, dtype=OUT_DT[out], device="cuda")
+        Dv = Dbuf[:, :N]
+        if sparse:
+            sp24.sp24_spmm(V, meta, Bv, OUT_DT[out], b_order=b_order, layout="tiled", out=Dv)
+        else:
+            sp24.sp24_gemm_dense(Abuf[:, :K], Bv, OUT_DT[out], b_order=b_order, out=Dv)
+        torch.cuda.synchronize()
+        assert (Dbuf[:, N:] == 7).all()                       # nothing written past the rows
+        if dtype == "i8":
+            assert np.array_equal(Dv.cpu().numpy(), ref)
+        else:
+            assert rel_err(out_to_f64(Dv.contiguous()), ref) <= REL_TOL
+
+
 SKINNY_CASES = [
     ("bf16", "bf16", 256, 16, 1024),
     ("f16", "f32", 96, 7, 576),       # ragged N, K split unevenly over the wavefronts
