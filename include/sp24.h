@@ -78,6 +78,8 @@ typedef enum {
  * SP24_LAYOUT_CANONICAL  V row-major [M][K/2]; meta bytes [M][K/8], the even
  *     group of a byte in bits 0..3.  Interchange format.
  *
+ *     Every product accepts it; the tiled layout below is 1.2-1.5x faster.
+ *
  * SP24_LAYOUT_TILED  the same codes and values permuted so that one wavefront
  *     loads the operands of a 32x32 sparse-MFMA tile with contiguous 16-byte
  *     and 4-byte accesses.  Needs M % 32 == 0 and K % 64 == 0, else

@@ -42,6 +42,10 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
     const uint8_t* arow = reinterpret_cast<const uint8_t*>(a.A) + m * a.lda * ES;
     const uint4v* Vp = reinterpret_cast<const uint4v*>(a.A);
     const uint32_t* Mp = reinterpret_cast<const uint32_t*>(a.meta);
+    // canonical layout: lane (m % 32, h) reads its slot's 16 bytes of values and 4 bytes of codes from row m
+    const bool canonical = SPARSE && a.layout == SP24_LAYOUT_CANONICAL;
+    const uint8_t* vrow = reinterpret_cast<const uint8_t*>(a.A) + m * (a.K / 2 * ES) + (ES == 1 ? 16 : 32) * q;
+    const uint8_t* mrow = reinterpret_cast<const uint8_t*>(a.meta) + m * (a.K / 8) + 4 * q;
 
     acc_t acc = {};
     const uint4v zero4 = {0u, 0u, 0u, 0u};
@@ -55,11 +59,20 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
             const bool ok = kb < KB64;
             if constexpr (SPARSE) {
                 const int64_t tile = rb * (a.K / 64) + kb;
-                codes[u] = ok ? Mp[tile * 64 + lane] : 0u;
-                if constexpr (DT == SP24_I8) va[u][0] = ok ? Vp[tile * 64 + lane] : zero4;
-                else {
-                    va[u][0] = ok ? Vp[(tile * 2) * 64 + lane] : zero4;
-                    va[u][1] = ok ? Vp[(tile * 2 + 1) * 64 + lane] : zero4;
+                if (canonical) {
+                    codes[u] = ok ? *reinterpret_cast<const uint32_t*>(mrow + kb * 8) : 0u;
+                    if constexpr (DT == SP24_I8) va[u][0] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 32) : zero4;
+                    else {
+                        va[u][0] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 64) : zero4;
+                        va[u][1] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 64 + 16) : zero4;
+                    }
+                } else {
+                    codes[u] = ok ? Mp[tile * 64 + lane] : 0u;
+                    if constexpr (DT == SP24_I8) va[u][0] = ok ? Vp[tile * 64 + lane] : zero4;
+                    else {
+                        va[u][0] = ok ? Vp[(tile * 2) * 64 + lane] : zero4;
+                        va[u][1] = ok ? Vp[(tile * 2 + 1) * 64 + lane] : zero4;
+                    }
                 }
             } else {
 #pragma unroll
@@ -141,7 +154,7 @@ sp24_status launch_mm_skinny(const MmArgs& a, hipStream_t st, bool* handled)
     const int es = esize_of(a.in);
     bool ok = a.N <= 32 && a.bo == SP24_B_KMAJOR && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 && (a.ldb * es) % 16 == 0 &&
               a.M >= 32 && (a.M + 31) / 32 < ((int64_t)1 << 31);
-    if (a.sparse) ok = ok && a.layout == SP24_LAYOUT_TILED;
+    if (a.sparse && a.layout == SP24_LAYOUT_CANONICAL) ok = ok && a.K % 64 == 0;
     if (!ok) return SP24_OK;
     *handled = true;
     if (a.in == SP24_I8) {

@@ -43,7 +43,8 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
              ((int64_t)g.C * es) % kStepBytes == 0 && span < ((int64_t)1 << 31) &&
              ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
     }
-    if (a.sparse) ok = ok && a.layout == SP24_LAYOUT_TILED;
+    // compressed operand: the tiled layout, or the canonical one gathered row by row (32-bit offsets inside a tile)
+    if (a.sparse && a.layout == SP24_LAYOUT_CANONICAL) ok = ok && a.K % 64 == 0 && (a.K / 2 * es) * 256 < ((int64_t)1 << 31);
     else ok = ok && a.lda * es < ((int64_t)1 << 22);
     if (!ok) return SP24_OK;
     *handled = true;

@@ -82,15 +82,23 @@ __device__ __forceinline__ void dma_offsets(int64_t row0, int64_t limit, int64_t
 // builtin in a loop, its wait-count pass treats the LDS counter as out of order and turns every wait for an
 // LDS read into lgkmcnt(0), which serialises the operand reads with the arithmetic.  The price is that the
 // compiler does not count these transfers in vmcnt: every wait for them below is written by hand.
+// a pointer the compiler can keep in scalar registers (the value must be the same in every lane)
+__device__ __forceinline__ const uint8_t* wave_uniform(const uint8_t* p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint8_t*>(((uint64_t)hi << 32) | lo);
+}
+
 __device__ __forceinline__ void lds_dma16(const uint8_t* base, uint32_t off, const uint8_t* lds)
 {
-    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(l) : "m0");
+    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr)lds);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0");
 }
 __device__ __forceinline__ void lds_dma4(const uint8_t* base, uint32_t off, const uint8_t* lds)
 {
-    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(l) : "m0");
+    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr)lds);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0");
 }
 
 // The same transfer with a full 64-bit address per lane (for gathers that a base + 32-bit offset cannot express).
@@ -361,25 +369,53 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
     else if constexpr (NMAJ) dma_offsets_nmajor<BN, NW, ES>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
     else dma_offsets<BN, NW>((int64_t)tn * BN, a.N, ldb_bytes, wave, lane, b_off);
-    // V: transfer x of this wavefront is 1 KiB number (wave*NJV + x) of the RB*2 of a step: row block /2, half %2
-    const uint8_t* v_base[NJV];                            // wavefront-uniform; lane l adds 16*l
+    // V: transfer x of this wavefront is 1 KiB number (wave*NJV + x) of the RB*2 of a step: row block /2, half %2.
+    // metadata: transfer x is 256-byte tile number (wave*NJM + x) of the RB*T64 of a step.
+    // Either way the stage receives the tiled layout's slot order (slot = lane).  From the tiled layout a transfer
+    // is one contiguous run; from the canonical one lane (m % 32, h) fetches its 16 bytes of values and 4 bytes
+    // of codes from row m of the row-major arrays (Sec. 3.1: their position follows from the row and column alone).
+    const bool canonical = a.layout == SP24_LAYOUT_CANONICAL;
+    const uint8_t* v_base[NJV];                            // wavefront-uniform
+    const uint8_t* m_base[NJM];
+    uint32_t v_off[NJV], m_off[NJM];                       // per lane
+    const int64_t v_step = canonical ? 64 : 2048, m_step = canonical ? 8 * T64 : T64 * 256;   // bytes per step
+    if (canonical) {
+        const int64_t vrow = a.K / 2 * ES, mrow = a.K / 8, row0 = (int64_t)tm * BM;
+        const int h = lane >> 5;
 #pragma unroll
-    for (int x = 0; x < NJV; ++x) {
-        const int id = wave * NJV + x;
-        int64_t rb = (int64_t)tm * RB + (id >> 1);
-        if (rb >= rb_total) rb = rb_total - 1;             // ragged M: compute on a valid row block, never stored
-        v_base[x] = reinterpret_cast<const uint8_t*>(a.A) + rb * KB64 * (1024 * ES) + (id & 1) * 1024;
-    }
-    // metadata: transfer x is 256-byte tile number (wave*NJM + x) of the RB*T64 of a step
-    const uint8_t* m_base[NJM];                            // wavefront-uniform; lane l adds 4*l
+        for (int x = 0; x < NJV; ++x) {
+            const int id = wave * NJV + x;
+            int64_t row = row0 + (id >> 1) * 32 + (lane & 31);
+            if (row >= a.M) row = a.M - 1;                 // ragged M: a valid row, never stored
+            v_base[x] = wave_uniform(reinterpret_cast<const uint8_t*>(a.A) + row0 * vrow);
+            v_off[x] = (uint32_t)((row - row0) * vrow + ((ES == 1) ? 32 * (id & 1) + 16 * h : 32 * h + 16 * (id & 1)));
+        }
 #pragma unroll
-    for (int x = 0; x < NJM; ++x) {
-        const int id = wave * NJM + x;
-        int64_t rb = (int64_t)tm * RB + id / T64;
-        if (rb >= rb_total) rb = rb_total - 1;
-        m_base[x] = reinterpret_cast<const uint8_t*>(a.meta) + (rb * KB64 + id % T64) * 256;
+        for (int x = 0; x < NJM; ++x) {
+            const int id = wave * NJM + x;
+            int64_t row = row0 + (id / T64) * 32 + (lane & 31);
+            if (row >= a.M) row = a.M - 1;
+            m_base[x] = wave_uniform(reinterpret_cast<const uint8_t*>(a.meta) + row0 * mrow);
+            m_off[x] = (uint32_t)((row - row0) * mrow + 8 * (id % T64) + 4 * h);
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < NJV; ++x) {
+            const int id = wave * NJV + x;
+            int64_t rb = (int64_t)tm * RB + (id >> 1);
+            if (rb >= rb_total) rb = rb_total - 1;         // ragged M: compute on a valid row block, never stored
+            v_base[x] = wave_uniform(reinterpret_cast<const uint8_t*>(a.A) + rb * KB64 * (1024 * ES) + (id & 1) * 1024);
+            v_off[x] = lane * 16;
+        }
+#pragma unroll
+        for (int x = 0; x < NJM; ++x) {
+            const int id = wave * NJM + x;
+            int64_t rb = (int64_t)tm * RB + id / T64;
+            if (rb >= rb_total) rb = rb_total - 1;
+            m_base[x] = wave_uniform(reinterpret_cast<const uint8_t*>(a.meta) + (rb * KB64 + id % T64) * 256);
+            m_off[x] = lane * 4;
+        }
     }
-    const uint32_t lane16 = lane * 16, lane4 = lane * 4;
 
     auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
     // transfer number x (0 .. NV-1) of this wavefront for a step: B rows, then values, then codes
@@ -390,8 +426,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
             if constexpr (CONV) b_conv.issue(x, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stg, wave);
             else lds_dma16(b_blk + (int64_t)step * b_step, b_off[x], stg + (wave * NJB + x) * 1024);
         }
-        else if (x < NJB + NJV) lds_dma16(v_base[x - NJB] + (int64_t)step * 2048, lane16, stg + kVOff + (wave * NJV + x - NJB) * 1024);
-        else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * (T64 * 256), lane4, stg + kMOff + (wave * NJM + x - NJB - NJV) * 256);
+        else if (x < NJB + NJV) lds_dma16(v_base[x - NJB] + (int64_t)step * v_step, v_off[x - NJB], stg + kVOff + (wave * NJV + x - NJB) * 1024);
+        else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * m_step, m_off[x - NJB - NJV], stg + kMOff + (wave * NJM + x - NJB - NJV) * 256);
     };
     auto dma = [&](int step, const ConvTap& tap, int u) {
 #pragma unroll

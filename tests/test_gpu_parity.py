@@ -271,6 +271,12 @@ def test_leading_dimensions_larger_than_the_rows(dtype, out, M, N, K, b_order):
             assert rel_err(out_to_f64(Dv.contiguous()), ref) <= REL_TOL
 
 
+@pytest.mark.parametrize("case", TILED_CASES[:9] + [("i8", "i32", 4352, 4000, 384), ("bf16", "f32", 300, 200, 192)])
+def test_spmm_canonical_layout_on_the_tiled_kernels(case):
+    """The row-major compressed pair feeds the tiled kernels directly (ragged M included)."""
+    run_mm_case(*case, layout="canonical", b_order="k", sparse=True, seed=8)
+
+
 SKINNY_CASES = [
     ("bf16", "bf16", 256, 16, 1024),
     ("f16", "f32", 96, 7, 576),       # ragged N, K split unevenly over the wavefronts
@@ -282,6 +288,8 @@ SKINNY_CASES = [
 @pytest.mark.parametrize("case", SKINNY_CASES)
 def test_skinny_kernels_match_oracle(case):
     run_mm_case(*case, layout="tiled", b_order="k", sparse=True, seed=4)
+    run_mm_case(*case, layout="canonical", b_order="k", sparse=True, seed=9)
+    run_mm_case(case[0], case[1], case[2] + 13, case[3], case[4], layout="canonical", b_order="k", sparse=True, seed=10)   # ragged M
     run_mm_case(*case, layout="canonical", b_order="k", sparse=False, seed=5)
 
 
