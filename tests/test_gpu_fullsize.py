@@ -77,3 +77,29 @@ def test_full_size_convolution_without_im2col():
         for got_t in (D, Dd):
             got = got_t[torch.as_tensor(rows, device="cuda")][:, img * 196:(img + 1) * 196]
             assert rel_err(out_to_f64(got), ref, rms) <= 1e-2, img
+
+
+def test_full_size_quantised_product():
+    """square_i8 with the quantised path's epilogue (int8 output): sampled rows x columns, bit for bit."""
+    w = synth.WORKLOADS["square_i8"]
+    M, K, N = w["M"], w["K"], w["N"]
+    A, Bt = synth.make("square_i8")
+    rng = np.random.default_rng(12)
+    w_scale = rng.uniform(2e-5, 9e-5, size=M).astype(np.float32)
+    bias = rng.normal(0.0, 0.3, size=M).astype(np.float32)
+    x_scale, inv_y = np.float32(0.02), 40.0
+    Ad, Bd = to_gpu(A, "i8"), to_gpu(Bt, "i8")
+    V, meta = sp24.sp24_compress(Ad, layout="tiled")
+    ws, bs = torch.from_numpy(w_scale).cuda(), torch.from_numpy(bias).cuda()
+    D = sp24.sp24_spmm_i8_scaled(V, meta, Bd, torch.int8, ws, x_scale, bs, True, inv_y, layout="tiled")
+    Dd = sp24.sp24_gemm_dense_i8_scaled(sp24.sp24_prune(Ad), Bd, torch.int8, ws, x_scale, bs, True, inv_y)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 31, 32, 255, 256, M - 1], rng.integers(0, M, 30)]))
+    cols = np.unique(np.concatenate([[0, 31, 32, 255, 256, N - 1], rng.integers(0, N, 40)]))
+    Prows = oracle.prune(np.ascontiguousarray(A[rows]), "i8")
+    acc = oracle.gemm(Prows, np.ascontiguousarray(Bt[cols].T), "i8")
+    want = oracle.requant(acc, w_scale[rows], x_scale, inv_y, bias[rows], True)
+    for got_t in (D, Dd):
+        got = got_t[torch.as_tensor(rows, device="cuda")][:, torch.as_tensor(cols, device="cuda")].cpu().numpy()
+        assert np.array_equal(got, want)
+    assert len(np.unique(want)) > 30
