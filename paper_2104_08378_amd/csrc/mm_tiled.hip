@@ -24,12 +24,13 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
 {
     *handled = false;
     const int es = esize_of(a.in);
-    bool ok = a.bo == SP24_B_KMAJOR && a.K % (kStepBytes / es) == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 &&
+    // K: whole 32-byte runs (a last, partial step is filled up with zeros)
+    bool ok = a.bo == SP24_B_KMAJOR && (a.K * es) % 32 == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 &&
               (a.ldb * es) % 16 == 0 && a.N >= 32 && a.M >= 64 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
               a.ldb * es < ((int64_t)1 << 22) && ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
     if (!a.conv.on && a.bo == SP24_B_NMAJOR) {
         // N-major B: whole 16-byte chunks of columns, rows 16-byte aligned, 32-bit row offsets within a step
-        ok = a.K % (kStepBytes / es) == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 && (a.ldb * es) % 16 == 0 &&
+        ok = (a.K * es) % 32 == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 && (a.ldb * es) % 16 == 0 &&
              (a.N * es) % 16 == 0 && a.N >= 32 && a.M >= 64 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
              a.ldb * es < ((int64_t)1 << 22) && ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
     }
@@ -44,7 +45,8 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
              ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
     }
     // compressed operand: the tiled layout, or the canonical one gathered row by row (32-bit offsets inside a tile)
-    if (a.sparse && a.layout == SP24_LAYOUT_CANONICAL) ok = ok && a.K % 64 == 0 && (a.K / 2 * es) * 256 < ((int64_t)1 << 31);
+    // (canonical codes are fetched as 4-byte words = 32 columns)
+    if (a.sparse && a.layout == SP24_LAYOUT_CANONICAL) ok = ok && a.K % 32 == 0 && (a.K / 2 * es) * 256 < ((int64_t)1 << 31);
     else ok = ok && a.lda * es < ((int64_t)1 << 22);
     if (!ok) return SP24_OK;
     *handled = true;

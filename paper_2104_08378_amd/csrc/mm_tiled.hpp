@@ -108,8 +108,40 @@ __device__ __forceinline__ void lds_dma16_addr(const uint8_t* addr, const uint8_
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(l) : "m0");
 }
 
-// 128 zero bytes: the source of B rows that fall into a convolution's padding or past the last output pixel.
+__device__ __forceinline__ void lds_dma4_addr(const uint8_t* addr, const uint8_t* lds)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(addr), "s"(l) : "m0");
+}
+
+// 128 zero bytes: the source of B rows that fall into a convolution's padding or past the last output pixel, and
+// of every operand piece that lies past K in the last step when K is not a whole number of steps.
 __device__ __attribute__((aligned(128))) const uint8_t k_zero_row[128] = {};
+
+// One transfer of the last, partial step: lanes whose piece lies past K fetch zeros instead (branch-free).
+template <bool DWORD>
+__device__ __forceinline__ void lds_dma_tail(const uint8_t* base, uint32_t off, bool past_k, const uint8_t* lds)
+{
+    const uint64_t mask = (uint64_t)0 - (uint64_t)past_k;
+    const uint64_t src = ((reinterpret_cast<uint64_t>(base) + off) & ~mask) | (reinterpret_cast<uint64_t>(k_zero_row) & mask);
+    if constexpr (DWORD) lds_dma4_addr(reinterpret_cast<const uint8_t*>(src), lds);
+    else lds_dma16_addr(reinterpret_cast<const uint8_t*>(src), lds);
+}
+
+// Does transfer j of a K-major operand block (dma_offsets) / of an N-major B block (dma_offsets_nmajor) lie past
+// the first `tail` bytes of K in the step, for this lane?
+template <int ROWS, int NW>
+__device__ __forceinline__ bool past_k_kmajor(int j, int wave, int lane, int tail)
+{
+    const int row = (wave * (ROWS / 8 / NW) + j) * 8 + (lane >> 3);
+    return (((lane & 7) ^ ((row >> 1) & 7)) << 4) >= tail;
+}
+template <int BN, int NW, int ES>
+__device__ __forceinline__ bool past_k_nmajor(int j, int wave, int lane, int tail)
+{
+    const int p = (wave * (BN / 8 / NW) + j) * 1024 + lane * 16;
+    return (p / (BN * ES)) * ES >= tail;
+}
 
 // Position of a K step inside a convolution's inner dimension k = (r*S + s)*C + c: a step (128 bytes of K) lies
 // inside one filter tap when C * element size is a multiple of 128 bytes.
@@ -356,7 +388,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, q = lane >> 5;
     const int64_t KB64 = a.K / 64;
-    const int nsteps = (int)(a.K / BK);
+    const int nsteps = (int)(a.K / BK);                    // whole steps
+    const int tail = (int)((a.K * ES) % kRowBytes);        // bytes of K in a further, partial step (0: none)
     const int64_t rb_total = a.M / 32;
 
     // ---- transfers of this wavefront ----
@@ -417,21 +450,59 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
         }
     }
 
+    // last, partial step (K not a whole number of steps; never with a convolution): which of this lane's transfers
+    // lie past K.  A step holds tail bytes of every B row, tail/2 bytes of values and tail/(8*ES) bytes of codes
+    // per A row; in the tiled layout a whole 64-column tile is present or absent.
+    uint32_t past_k = 0;                                   // bit x: transfer x of this wavefront
+    if (tail) {
+#pragma unroll
+        for (int x = 0; x < NJB; ++x) {
+            const bool p = NMAJ ? past_k_nmajor<BN, NW, ES>(x, wave, lane, tail) : past_k_kmajor<BN, NW>(x, wave, lane, tail);
+            past_k |= (uint32_t)p << x;
+        }
+        const int h = lane >> 5;
+#pragma unroll
+        for (int x = 0; x < NJV; ++x) {
+            const int id = wave * NJV + x;
+            const int col = (ES == 1) ? 32 * (id & 1) + 16 * h : 32 * h + 16 * (id & 1);     // byte of the 64 value bytes of a row and step
+            const bool p = canonical ? col >= tail / 2 : ((ES == 1) ? 64 * (id & 1) >= tail : false);
+            past_k |= (uint32_t)p << (NJB + x);
+        }
+#pragma unroll
+        for (int x = 0; x < NJM; ++x) {
+            const int id = wave * NJM + x;
+            const bool p = canonical ? (8 * (id % T64) + 4 * h) * 8 * ES >= tail : 64 * ES * (id % T64) >= tail;
+            past_k |= (uint32_t)p << (NJB + NJV + x);
+        }
+    }
+
     auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
     // transfer number x (0 .. NV-1) of this wavefront for a step: B rows, then values, then codes
     // (convolution: `tap` is the position of `step` in the inner dimension)
-    auto dma_one = [&](int step, const ConvTap& tap, int u, int x) {
+    // `partial_tag` (compile time): the step is the partial one past the last whole step; pieces past K are zeros.
+    // The main loop only ever fetches whole steps, so that a step stays one basic block.
+    auto dma_one = [&](int step, const ConvTap& tap, int u, int x, auto partial_tag) {
         uint8_t* stg = stage_ptr(u);
+        constexpr bool partial = decltype(partial_tag)::value && !CONV;
+        const bool pk = (past_k >> x) & 1u;
         if (x < NJB) {
+            uint8_t* dst = stg + (wave * NJB + x) * 1024;
             if constexpr (CONV) b_conv.issue(x, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stg, wave);
-            else lds_dma16(b_blk + (int64_t)step * b_step, b_off[x], stg + (wave * NJB + x) * 1024);
+            else if (partial) lds_dma_tail<false>(b_blk + (int64_t)step * b_step, b_off[x], pk, dst);
+            else lds_dma16(b_blk + (int64_t)step * b_step, b_off[x], dst);
+        } else if (x < NJB + NJV) {
+            uint8_t* dst = stg + kVOff + (wave * NJV + x - NJB) * 1024;
+            if (partial) lds_dma_tail<false>(v_base[x - NJB] + (int64_t)step * v_step, v_off[x - NJB], pk, dst);
+            else lds_dma16(v_base[x - NJB] + (int64_t)step * v_step, v_off[x - NJB], dst);
+        } else {
+            uint8_t* dst = stg + kMOff + (wave * NJM + x - NJB - NJV) * 256;
+            if (partial) lds_dma_tail<true>(m_base[x - NJB - NJV] + (int64_t)step * m_step, m_off[x - NJB - NJV], pk, dst);
+            else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * m_step, m_off[x - NJB - NJV], dst);
         }
-        else if (x < NJB + NJV) lds_dma16(v_base[x - NJB] + (int64_t)step * v_step, v_off[x - NJB], stg + kVOff + (wave * NJV + x - NJB) * 1024);
-        else lds_dma4(m_base[x - NJB - NJV] + (int64_t)step * m_step, m_off[x - NJB - NJV], stg + kMOff + (wave * NJM + x - NJB - NJV) * 256);
     };
     auto dma = [&](int step, const ConvTap& tap, int u) {
 #pragma unroll
-        for (int x = 0; x < NV; ++x) dma_one(step, tap, u, x);
+        for (int x = 0; x < NV; ++x) dma_one(step, tap, u, x, std::false_type{});
     };
     // the step whose transfers are issued next, kept NS - 1 ahead of the arithmetic.  It stops at the last step:
     // past the end that step is fetched again into a stage nobody reads, which keeps the counts uniform.
@@ -532,41 +603,70 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
                 if (t < T1) {
                     const int m = t * TM + i;
 #pragma unroll
-                    for (int x = m * NV / (T1 * TM); x < (m + 1) * NV / (T1 * TM); ++x) dma_one(f_step, f_tap, (u + NS - 1) % NS, x);
+                    for (int x = m * NV / (T1 * TM); x < (m + 1) * NV / (T1 * TM); ++x) dma_one(f_step, f_tap, (u + NS - 1) % NS, x, std::false_type{});
                 }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
         advance_fetch();
     };
-
-    // prologue: the first NS - 1 stages on their way; first operands of step 0 once stage 0 has landed
+    if (nsteps > 0) {
+        // prologue: the first NS - 1 stages on their way; first operands of step 0 once stage 0 has landed
 #pragma unroll
-    for (int u = 0; u < NS - 1; ++u) {
-        dma(f_step, f_tap, u);
-        advance_fetch();
+        for (int u = 0; u < NS - 1; ++u) {
+            dma(f_step, f_tap, u);
+            advance_fetch();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(kWait);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(lds_all, 0, a_first, m_first, true);
+        read_frag(lds_all, 0, f_first[0]);
+        read_frag(lds_all, 1, f_first[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        // NS steps per iteration, so that stage indices are compile-time constants; the remainder runs after the loop
+        int step = 0;
+        for (; step + NS <= nsteps; step += NS) {
+#pragma unroll
+            for (int u = 0; u < NS; ++u) do_step(u);
+        }
+#pragma unroll
+        for (int u = 0; u < NS - 1; ++u)
+            if (step + u < nsteps) do_step(u);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(kWait);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    read_a(lds_all, 0, a_first, m_first, true);
-    read_frag(lds_all, 0, f_first[0]);
-    read_frag(lds_all, 1, f_first[1]);
-    __builtin_amdgcn_sched_barrier(0);
-    // NS steps per iteration, so that stage indices are compile-time constants; the remainder runs after the loop
-    int step = 0;
-    for (; step + NS <= nsteps; step += NS) {
-#pragma unroll
-        for (int u = 0; u < NS; ++u) do_step(u);
-    }
-#pragma unroll
-    for (int u = 0; u < NS - 1; ++u)
-        if (step + u < nsteps) do_step(u);
-    // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
+    // the surplus transfers have landed and every wavefront is done with the stages
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    if (!CONV && tail != 0) {
+        // K is not a whole number of steps: one more, partial step on its own -- fetched into stage 0 with every
+        // piece past K replaced by zeros, then computed without overlap (it happens once per tile)
+#pragma unroll
+        for (int x = 0; x < NV; ++x) dma_one(nsteps, f_tap, 0, x, std::true_type{});
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        int4v av[2][TM];
+        int mv[2][TM];
+        read_a(lds_all, 0, av[0], mv[0], true);
+        read_a(lds_all, 1, av[1], mv[1], DT == SP24_I8);
+#pragma unroll
+        for (int t = 0; t < NF; ++t) {
+            const int j = t / TN, nj = t % TN;
+            int8v fb;
+            read_frag(lds_all, t, fb);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], fb, acc[i][nj], mv[j][i]);
+                else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], fb, acc[i][nj], mv[0][i]);
+                else acc[i][nj] = smfmac32<DT, 1>(av[1][i], fb, acc[i][nj], mv[0][i]);
+            }
+        }
+        __builtin_amdgcn_s_barrier();                // every wavefront has read stage 0 before it becomes store scratch
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // LDS becomes store scratch
     store_wave_tile<DT, OUT, TM, TN>(a, acc, lds_all + wave * epilogue_geometry<OUT, TN>::kWaveBytes,
                                      (int64_t)tm * BM + wm * TM * 32, (int64_t)tn * BN + wn * TN * 32, lane);
 }
@@ -598,7 +698,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, q = lane >> 5;
-    const int nsteps = (int)(a.K / BK);
+    const int nsteps = (int)(a.K / BK);                    // whole steps
+    const int tail = (int)((a.K * ES) % kRowBytes);        // bytes of K in a further, partial step (0: none)
 
     const int64_t lda_bytes = a.lda * ES, ldb_bytes = a.ldb * ES;
     const uint8_t* a_blk = reinterpret_cast<const uint8_t*>(a.A) + (int64_t)tm * BM * lda_bytes;
@@ -621,6 +722,20 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
 
     auto stage_ptr = [&](int u) -> uint8_t* { return lds_all + u * kStageBytes; };
     // (convolution: `tap` is the position of `step` in the inner dimension)
+    // the partial step past the last whole one: pieces past K come from the zero row
+    auto dma_partial = [&](int step, int u) {
+        if constexpr (!CONV) {
+#pragma unroll
+            for (int j = 0; j < NJA; ++j)
+                lds_dma_tail<false>(a_blk + (int64_t)step * kRowBytes, a_off[j], past_k_kmajor<BM, NW>(j, wave, lane, tail),
+                                    stage_ptr(u) + (wave * NJA + j) * 1024);
+#pragma unroll
+            for (int j = 0; j < NJB; ++j)
+                lds_dma_tail<false>(b_blk + (int64_t)step * b_step, b_off[j],
+                                    NMAJ ? past_k_nmajor<BN, NW, ES>(j, wave, lane, tail) : past_k_kmajor<BN, NW>(j, wave, lane, tail),
+                                    stage_ptr(u) + BM * kRowBytes + (wave * NJB + j) * 1024);
+        }
+    };
     auto dma = [&](int step, const ConvTap& tap, int u) {
         dma_rows<BM, NW>(a_blk + (int64_t)step * kRowBytes, a_off, stage_ptr(u), wave);
         if constexpr (CONV) {
@@ -695,24 +810,37 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    if (nsteps > 0) {
 #pragma unroll
-    for (int u = 0; u < NS - 1; ++u) {
-        dma(f_step, f_tap, u);
-        advance_fetch();
+        for (int u = 0; u < NS - 1; ++u) {
+            dma(f_step, f_tap, u);
+            advance_fetch();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        int step = 0;
+        for (; step + NS <= nsteps; step += NS) {
+#pragma unroll
+            for (int u = 0; u < NS; ++u) do_step(u);
+        }
+#pragma unroll
+        for (int u = 0; u < NS - 1; ++u)
+            if (step + u < nsteps) do_step(u);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    int step = 0;
-    for (; step + NS <= nsteps; step += NS) {
-#pragma unroll
-        for (int u = 0; u < NS; ++u) do_step(u);
-    }
-#pragma unroll
-    for (int u = 0; u < NS - 1; ++u)
-        if (step + u < nsteps) do_step(u);
-    // the surplus transfers have landed and every wavefront is done with the stages: LDS becomes store scratch
+    // the surplus transfers have landed and every wavefront is done with the stages
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    if (!CONV && tail != 0) {
+        // K is not a whole number of steps: one more, partial step on its own (pieces past K are zeros)
+        dma_partial(nsteps, 0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        compute(0);
+        __builtin_amdgcn_s_barrier();                // every wavefront has read stage 0 before it becomes store scratch
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // LDS becomes store scratch
     store_wave_tile<DT, OUT, TM, TN>(a, acc, lds_all + wave * epilogue_geometry<OUT, TN>::kWaveBytes,
                                      (int64_t)tm * BM + wm * TM * 32, (int64_t)tn * BN + wn * TN * 32, lane);
 }

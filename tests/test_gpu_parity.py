@@ -277,6 +277,26 @@ def test_spmm_canonical_layout_on_the_tiled_kernels(case):
     run_mm_case(*case, layout="canonical", b_order="k", sparse=True, seed=8)
 
 
+RAGGED_K_CASES = [
+    # K not a whole number of 128-byte steps: the last step is filled up with zeros
+    ("i8", "i32", 256, 320, 192, "tiled"),        # half a step (one 64-column tile)
+    ("i8", "i32", 4096, 3328, 320, "tiled"),      # the same on 256x256 tiles
+    ("i8", "i32", 160, 200, 160, "canonical"),    # a quarter step, ragged M and N
+    ("i8", "i32", 128, 128, 96, "canonical"),     # a single, partial step
+    ("bf16", "bf16", 256, 264, 96, "canonical"),  # 16-bit: K % 64 = 32
+    ("f16", "f32", 192, 128, 224, "canonical"),
+    ("f16", "f16", 128, 256, 208, "canonical"),   # K % 32 = 16: sparse runs the general kernel, dense the tiled one
+]
+
+
+@pytest.mark.parametrize("case", RAGGED_K_CASES)
+@pytest.mark.parametrize("b_order", ["k", "n"])
+def test_partial_last_step(case, b_order):
+    dtype, out, M, N, K, layout = case
+    run_mm_case(dtype, out, M, N, K, layout=layout, b_order=b_order, sparse=True, seed=12)
+    run_mm_case(dtype, out, M, N, K, layout="canonical", b_order=b_order, sparse=False, seed=13)
+
+
 SKINNY_CASES = [
     ("bf16", "bf16", 256, 16, 1024),
     ("f16", "f32", 96, 7, 576),       # ragged N, K split unevenly over the wavefronts
