@@ -72,18 +72,33 @@ __device__ __forceinline__ uint32_t code_of_mask(uint32_t mask)
 // ---------------------------------------------------------------------------
 // fp32 -> 16-bit storage, round to nearest even.
 // ---------------------------------------------------------------------------
+// float -> 16-bit output, round to nearest even, as the hardware converts (v_cvt_pk_bf16_f32 / v_cvt_f16_f32:
+// one instruction, no branch on NaN)
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u); // quiet NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, h);
 }
 
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
 {
-    _Float16 h = (_Float16)f; // v_cvt_f16_f32: round to nearest even
+    _Float16 h = (_Float16)f;
     return __builtin_bit_cast(uint16_t, h);
+}
+
+// two floats -> two 16-bit outputs in one register (lo in bits 0-15), one packed conversion
+template <int OUT>
+__device__ __forceinline__ uint32_t pack_out16(float lo, float hi)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    if constexpr (OUT == SP24_BF16) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    } else {
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
 }
 
 // ---------------------------------------------------------------------------

@@ -328,16 +328,40 @@ __device__ __forceinline__ void store_wave_tile(const MmArgs& a, typename acc_of
                 epilogue_row(a.epi, m < a.M ? m : a.M - 1, es[e], eb[e]);
             }
         }
+        if constexpr (kOsz == 2) {
+            // A lane holds rows e, e + 1 of one column; converted as a pair they fill a register.  Neighbouring
+            // lanes (columns r, r ^ 1) then trade halves: the even lane ends up with row e of both columns, the odd
+            // one with row e + 1, so that the image is written 4 bytes per lane.
+            const uint32_t sel = (lane & 1) ? 0x03020706u : 0x05040100u;   // v_perm_b32: bytes 0-3 own, 4-7 neighbour
+            uint8_t* img = scratch + (4 * q + (lane & 1)) * kPitch + (r & ~1) * 2;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                uint8_t* p = scratch + (8 * (e / 4) + 4 * q + (e % 4)) * kPitch + (j * 32 + r) * kOsz;
-                auto v = acc[i][j][e];
-                float s = 0.0f, b = 0.0f;
-                if constexpr (DT == SP24_I8 && OUT != SP24_I32) { s = es[e]; b = eb[e]; }
-                store_bits<OUT>(p, 0, output_bits<OUT>(v, s, b, a.epi));
-            }
+                for (int e = 0; e < 16; e += 2) {
+                    float y0, y1;
+                    if constexpr (DT == SP24_I8) {
+                        y0 = dequant_value(acc[i][j][e], es[e], eb[e], a.epi.relu);
+                        y1 = dequant_value(acc[i][j][e + 1], es[e + 1], eb[e + 1], a.epi.relu);
+                    } else {
+                        y0 = acc[i][j][e];
+                        y1 = acc[i][j][e + 1];
+                    }
+                    const uint32_t own = pack_out16<OUT>(y0, y1);
+                    const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+                    *reinterpret_cast<uint32_t*>(img + (8 * (e / 4) + (e % 4)) * kPitch + j * 64) = __builtin_amdgcn_perm(nb, own, sel);
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    uint8_t* p = scratch + (8 * (e / 4) + 4 * q + (e % 4)) * kPitch + (j * 32 + r) * kOsz;
+                    auto v = acc[i][j][e];
+                    float s = 0.0f, b = 0.0f;
+                    if constexpr (DT == SP24_I8 && OUT != SP24_I32) { s = es[e]; b = eb[e]; }
+                    store_bits<OUT>(p, 0, output_bits<OUT>(v, s, b, a.epi));
+                }
+        }
 #pragma unroll
         for (int it = 0; it < 32 * kChunksPerRow / 64; ++it) {
             const int idx = it * 64 + lane;
