@@ -256,6 +256,30 @@ def main():
         only[:] = saved
         return e0.elapsed_time(e1) / args.steps
     ms_b2b = {"spmm": back_to_back("spmm"), "dense": back_to_back("dense")}
+
+    # Context, not the product: the vendor library's dense GEMM on the same shape and the same rotating inputs
+    # (torch.matmul / torch._int_mm, i.e. hipBLASLt or rocBLAS), the counterpart of the paper's dense denominator
+    # (Sec. 3.2, Fig. 3 use the vendor's dense library).  Output type: the input type (int32 for int8 inputs).
+    def vendor_dense():
+        if conv or "dense" not in only or "spmm" not in only:
+            return None
+        try:
+            mm = (lambda a, b: torch._int_mm(a, b.t())) if dt == "i8" else (lambda a, b: torch.matmul(a, b.t()))
+            for i in range(3):
+                mm(P, Bs[i % R])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(args.steps):
+                mm(P, Bs[i % R])
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) / args.steps
+            return {"ms": t, "speedup_of_sparse": t / ms_b2b["spmm"], "own_dense_over_vendor": ms_b2b["dense"] / t,
+                    "library": "torch %s (%s)" % (torch.__version__, "torch._int_mm" if dt == "i8" else "torch.matmul")}
+        except Exception as e:                               # a shape the library call does not take
+            return {"error": repr(e)[:200]}
+    vendor = vendor_dense()
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -298,6 +322,7 @@ def main():
         "step_ms": ms, "kernel_ms_back_to_back": ms_b2b,
         "speedup_vs_dense": (t_dn / t_sp) if ("dense" in only and "spmm" in only) else None,
         "dense_tflops": flops_equiv / t_dn / 1e12 if "dense" in only else None,
+        "vendor_dense": vendor,
         "spmm_GBps": bytes_spmm / t_sp / 1e9 if "spmm" in only else None,
         "dense_GBps": bytes_dense / t_dn / 1e9 if "dense" in only else None,
         "prune_GBps": 2.0 * M * K * es / (ms["prune"] * 1e-3) / 1e9 if "prune" in only else None,

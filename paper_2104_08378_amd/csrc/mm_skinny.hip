@@ -10,6 +10,14 @@
 // or 2 KiB (16-bit) run of values and one 256-byte run of metadata words, 56 %
 // (16-bit) or 62.5 % (8-bit) of the dense bytes -- the bandwidth saving of
 // Sec. 3.1.  B is small (K x N) and is read straight from cache.
+//
+// In the dense variant every workgroup starts its sweep over K at a different
+// tile and wraps around: with all of them at the same K at the same time, the
+// rows of the row-major A -- a power-of-two pitch apart -- fall into the same
+// memory channels.  Measured on 8192 x 8192 x 16 bf16: 29 -> 22 us inside the
+// kernel.  The sparse variant reads one contiguous stream per workgroup front
+// to back, with the tile addresses of a batch a constant apart (a start tile
+// per workgroup cost it 10 %: an address computation per load).
 #include "common.hpp"
 #include "launch.hpp"
 #include "mfma.hpp"
@@ -34,6 +42,7 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
     const int64_t rb = blockIdx.x;
     const int64_t KB64 = (a.K + 63) / 64;
     const int64_t Kbytes = a.K * ES;
+    const int64_t k_start = SPARSE ? 0 : (rb * 37) % KB64;   // this workgroup's first tile (dense only)
 
     const bool n_ok = r < a.N;
     const uint8_t* brow = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)(n_ok ? r : 0) * a.ldb * ES;
@@ -55,8 +64,13 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
         uint32_t codes[kSkinnyUnroll];
 #pragma unroll
         for (int u = 0; u < kSkinnyUnroll; ++u) {
-            const int64_t kb = kb0 + (int64_t)u * kSkinnyWaves;
-            const bool ok = kb < KB64;
+            const int64_t kbl = kb0 + (int64_t)u * kSkinnyWaves;
+            const bool ok = kbl < KB64;
+            int64_t kb = kbl;
+            if constexpr (!SPARSE) {
+                kb += k_start;                       // (with !ok nothing is loaded)
+                if (kb >= KB64) kb -= KB64;
+            }
             if constexpr (SPARSE) {
                 const int64_t tile = rb * (a.K / 64) + kb;
                 if (canonical) {
