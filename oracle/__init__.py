@@ -48,6 +48,8 @@ def _load():
         lib.sp24o_prune_transposable.argtypes = [vp, vp, i64, i64, i32]
         lib.sp24o_mask_apply.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_compress_masked.argtypes = [vp, vp, vp, i64, i64, i32]
+        lib.sp24o_permute_columns.argtypes = [vp, vp, vp, i64, i64, i32]
+        lib.sp24o_retained_magnitude.argtypes = [vp, vp, i64, i64, i32, vp]
         f32 = ctypes.c_float
         lib.sp24o_dequant_f64.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32]
         lib.sp24o_requant_i8.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32, f32]
@@ -148,6 +150,34 @@ def compress_masked(W, meta, dtype):
     if rc:
         raise ValueError(f"oracle compress_masked failed ({rc})")
     return V
+
+
+def permute_columns(A, perm, dtype):
+    """Sec. 4.1 Step 2 (channel permutations): the matrix with its columns in the order perm, P[:, k] = A[:, perm[k]]."""
+    _check(A, dtype)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    if perm.shape != (A.shape[1],):
+        raise ValueError("perm must hold K entries")
+    P = np.empty_like(A)
+    rc = _load().sp24o_permute_columns(_ptr(A), _ptr(perm), _ptr(P), A.shape[0], A.shape[1], _TYPES[dtype])
+    if rc:
+        raise ValueError(f"oracle permute_columns: perm is not a permutation of 0..K-1 ({rc})")
+    return P
+
+
+def retained_magnitude(A, dtype, perm=None):
+    """Fig. 5: the total magnitude that 2:4 pruning keeps when the groups of four are taken in the column order perm."""
+    _check(A, dtype)
+    out = np.zeros(1, dtype=np.float64)
+    if perm is not None:
+        perm = np.ascontiguousarray(perm, dtype=np.int32)
+        if perm.shape != (A.shape[1],):
+            raise ValueError("perm must hold K entries")
+    rc = _load().sp24o_retained_magnitude(_ptr(A), _ptr(perm) if perm is not None else None, A.shape[0], A.shape[1],
+                                          _TYPES[dtype], _ptr(out))
+    if rc:
+        raise ValueError(f"oracle retained_magnitude failed ({rc})")
+    return float(out[0])
 
 
 def gemm(P, B, dtype):

@@ -30,6 +30,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -480,6 +481,65 @@ int sp24o_requant_i8(const int32_t *acc, int8_t *Q, long M, long N, const float 
             Q[m * N + n] = (int8_t)(int)r;
         }
     }
+    return 0;
+}
+
+/* ---- channel permutations (Sec. 4.1, Step 2; Fig. 5) -------------------- */
+
+/*
+ * The matrix with its columns taken in the order perm: P[m][k] = A[m][perm[k]]
+ * (bit for bit).  perm must hold every column 0 .. K-1 once (else 2).
+ */
+int sp24o_permute_columns(const void *A, const int32_t *perm, void *P, long M, long K, int t)
+{
+    int es = esize(t);
+    if (es == 0)
+        return 1;
+    char *seen = (char *)calloc((size_t)(K > 0 ? K : 1), 1);
+    if (!seen)
+        return 3;
+    for (long k = 0; k < K; ++k) {
+        if (perm[k] < 0 || perm[k] >= K || seen[perm[k]]) {
+            free(seen);
+            return 2;
+        }
+        seen[perm[k]] = 1;
+    }
+    free(seen);
+    for (long m = 0; m < M; ++m)
+        for (long k = 0; k < K; ++k)
+            memcpy((char *)P + (m * K + k) * es, (const char *)A + (m * K + perm[k]) * es, es);
+    return 0;
+}
+
+/*
+ * The figure of merit of a column order (Fig. 5: "total weight magnitude"
+ * after pruning): the sum of |a| over the elements that the selection rule of
+ * Step 2 keeps when the groups of four are formed from columns perm[4g] ..
+ * perm[4g+3] (perm == NULL: the columns as they are).  Plain double sum, rows
+ * then groups then positions in ascending order; a kept NaN makes it NaN.
+ */
+int sp24o_retained_magnitude(const void *A, const int32_t *perm, long M, long K, int t, double *out)
+{
+    if (esize(t) == 0 || K % 4)
+        return 1;
+    double total = 0.0;
+    for (long m = 0; m < M; ++m)
+        for (long g = 0; g < K / 4; ++g) {
+            double x[4];
+            int keep[4];
+            for (int i = 0; i < 4; ++i) {
+                long col = perm ? perm[4 * g + i] : 4 * g + i;
+                if (col < 0 || col >= K)
+                    return 2;
+                x[i] = elem_to_double(A, m * K + col, t);
+            }
+            select_two(x, keep);
+            for (int i = 0; i < 4; ++i)
+                if (keep[i])
+                    total += fabs(x[i]);
+        }
+    *out = total;
     return 0;
 }
 

@@ -608,3 +608,81 @@ def test_transposable_pruning_tie_rule_and_fixed_points():
     for i, j in enumerate([2, 0, 3, 1]):
         D[i, j] = 100
     assert (oracle.prune_transposable(D, "i8")[[0, 1, 2, 3], [2, 0, 3, 1]] == 100).all()
+
+
+# --- channel permutations (Sec. 4.1 Step 2, Fig. 5) -------------------------
+@pytest.mark.parametrize("dt", DTYPES)
+def test_permute_columns_is_numpy_fancy_indexing(dt):
+    name = {"f16": "tiny_f16", "bf16": "ffn_bf16", "i8": "square_i8"}[dt]
+    A, _ = synth.make(name, M=24, N=8, K=96, seed=21)
+    rng = np.random.default_rng(5)
+    perm = rng.permutation(96).astype(np.int32)
+    P = oracle.permute_columns(A, perm, dt)
+    assert np.array_equal(P, A[:, perm])
+    # the inverse order undoes it; the identity changes nothing
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(96, dtype=np.int32)
+    assert np.array_equal(oracle.permute_columns(P, inv, dt), A)
+    assert np.array_equal(oracle.permute_columns(A, np.arange(96), dt), A)
+    for bad in ([0] * 96, list(range(95)) + [96], list(range(95)) + [-1]):
+        with pytest.raises(ValueError):
+            oracle.permute_columns(A, np.array(bad, dtype=np.int32), dt)
+
+
+def test_retained_magnitude_closed_forms():
+    # one group 1 2 3 4 keeps 3 + 4; signs do not matter; a second group of equal values keeps any two
+    A = np.array([[1, -2, 3, -4, 5, 5, 5, 5]], dtype=np.int8)
+    assert oracle.retained_magnitude(A, "i8") == 7 + 10
+    # Fig. 5's point in miniature: both large values of a row in one group, plus one more large value there,
+    # lose one of them; dealing the columns out over the groups keeps all three
+    B = np.array([[9, 8, 7, 0, 1, 0, 0, 0]], dtype=np.int8)
+    assert oracle.retained_magnitude(B, "i8") == 9 + 8 + 1 + 0
+    assert oracle.retained_magnitude(B, "i8", perm=[0, 1, 3, 5, 2, 4, 6, 7]) == 9 + 8 + 7 + 1
+    # -128 counts as 128
+    C = np.array([[-128, 127, 1, 1]], dtype=np.int8)
+    assert oracle.retained_magnitude(C, "i8") == 255
+    # NaN is kept (it ranks highest) and makes the total NaN
+    D = bits_of([[np.nan, 1.0, 2.0, 3.0]], "f16")
+    assert np.isnan(oracle.retained_magnitude(D, "f16"))
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_retained_magnitude_is_the_magnitude_of_the_pruned_permuted_matrix(dt):
+    # two routes to the same number: prune (pinned above) the permuted matrix and add up |p| with numpy
+    name = {"f16": "tiny_f16", "bf16": "ffn_bf16", "i8": "square_i8"}[dt]
+    A, _ = synth.make(name, M=40, N=8, K=64, seed=22)
+    rng = np.random.default_rng(6)
+    for perm in (None, rng.permutation(64).astype(np.int32)):
+        Ap = A if perm is None else np.ascontiguousarray(A[:, perm])
+        want = np.abs(exact_value(oracle.prune(Ap, dt), dt)).sum()
+        got = oracle.retained_magnitude(A, dt, perm=perm)
+        assert got == pytest.approx(want, rel=1e-13)
+    # orders that only move columns inside their group, or move whole groups, keep the same elements
+    base = oracle.retained_magnitude(A, dt)
+    inside = np.arange(64).reshape(16, 4)[:, [2, 0, 3, 1]].reshape(-1)
+    groups = np.arange(64).reshape(16, 4)[rng.permutation(16)].reshape(-1)
+    assert oracle.retained_magnitude(A, dt, perm=inside) == pytest.approx(base, rel=1e-13)
+    assert oracle.retained_magnitude(A, dt, perm=groups) == pytest.approx(base, rel=1e-13)
+
+
+def test_retained_magnitude_best_split_of_eight_columns_by_brute_force():
+    # 8 columns split into two groups in 35 ways: the best split keeps at least what the given order keeps and
+    # never more than the four largest magnitudes of every row
+    rng = np.random.default_rng(7)
+    A = rng.integers(-127, 128, size=(16, 8)).astype(np.int8)
+    top4 = np.sort(np.abs(A.astype(np.int64)), axis=1)[:, 4:].sum()
+    values = []
+    for first in itertools.combinations(range(8), 4):
+        if 0 not in first:
+            continue
+        rest = [c for c in range(8) if c not in first]
+        values.append(oracle.retained_magnitude(A, "i8", perm=list(first) + rest))
+    assert len(values) == 35
+    assert max(values) >= oracle.retained_magnitude(A, "i8")
+    assert max(values) <= top4
+    # a matrix whose rows have their four large values in columns 0-3 loses half of them unpermuted and none when
+    # the columns are dealt out two and two
+    L = np.zeros((5, 8), dtype=np.int8)
+    L[:, :4] = rng.integers(50, 100, size=(5, 4))
+    assert oracle.retained_magnitude(L, "i8", perm=[0, 1, 4, 5, 2, 3, 6, 7]) == np.abs(L.astype(np.int64)).sum()
+    assert oracle.retained_magnitude(L, "i8") < np.abs(L.astype(np.int64)).sum()
