@@ -133,6 +133,9 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
 
     Pm = torch.empty_like(As[0])
     Vm = torch.empty_like(V)
+    perm_h = np.random.default_rng(0).permutation(K).astype(np.int32)
+    perm_d = torch.from_numpy(perm_h).cuda()
+    total = torch.empty(1, dtype=torch.float64, device="cuda")
     out = {}
     ops = {
         "mask_apply": (lambda i: sp24.sp24_mask_apply(As[i % R], meta, layout="tiled", out=Pm), 2.0 * M * K * es + M * K / 8,
@@ -141,6 +144,11 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
                             lambda: oracle.compress_masked(sample, smeta, dt)),
         "prune_transposable": (lambda i: sp24.sp24_prune_transposable(As[i % R], out=Pm), 2.0 * M * K * es,
                                lambda: oracle.prune_transposable(sample, dt)),
+        # channel permutations: the gather reads and writes the matrix once, the figure of merit reads it once
+        "permute_columns": (lambda i: sp24.sp24_permute_columns(As[i % R], perm_d, out=Pm), 2.0 * M * K * es + 4.0 * K,
+                            lambda: oracle.permute_columns(sample, perm_h, dt)),
+        "retained_magnitude": (lambda i: sp24.sp24_retained_magnitude(As[i % R], perm_d, out=total), 1.0 * M * K * es + 4.0 * K,
+                               lambda: oracle.retained_magnitude(sample, dt, perm=perm_h)),
     }
     for op, (fn, nbytes, cfn) in ops.items():
         t = timed(fn)

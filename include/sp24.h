@@ -136,6 +136,33 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
                             sp24_dtype t, sp24_layout l, void* stream);
 
 /*
+ * Sec. 4.1, Step 2 (channel permutations; Fig. 5): the matrix with its columns
+ * taken in the order perm, P[m][k] = A[m][perm[k]], bit for bit.  Permuting
+ * the columns of the weights before pruning -- and the rows of the second
+ * operand alike: for a K-major B those are the columns of the stored array,
+ * the same call -- leaves the product unchanged and can raise the magnitude
+ * that pruning keeps.  perm: K int32 entries in device memory, a permutation
+ * of 0 .. K-1 (an entry outside that range reads column 0; never an
+ * out-of-range access).  A and P as for sp24_prune, but they must not overlap.
+ * K < 2^31.
+ */
+sp24_status sp24_permute_columns(const void* A, const int32_t* perm, void* P, int64_t M, int64_t K,
+                                 int64_t lda, int64_t ldp, sp24_dtype t, void* stream);
+
+/*
+ * Fig. 5's figure of merit for a column order: *total (one double in device
+ * memory, 8-byte aligned, overwritten) = the sum of |a| over the elements that
+ * sp24_prune would keep if the groups of four were formed from columns
+ * perm[4g] .. perm[4g+3] (perm == NULL: the columns as they are).  Magnitudes
+ * and selection as in sp24_prune (|-128| = 128; a kept NaN makes the total
+ * NaN).  The terms are exact binary64 values added in no fixed order: results
+ * of two calls may differ in the last bits.  A as for sp24_prune; with M == 0
+ * the total is 0.
+ */
+sp24_status sp24_retained_magnitude(const void* A, const int32_t* perm, double* total, int64_t M, int64_t K,
+                                    int64_t lda, sp24_dtype t, void* stream);
+
+/*
  * Sec. 6: a pattern that satisfies the 2:4 constraint along rows and along
  * columns, so that the transposed matrix (the backward pass) can use the
  * sparse product too.  The exhaustive search the paper names, per aligned

@@ -173,6 +173,41 @@ sp24_status sp24_compress_masked(const void* W, const void* meta, void* V, int64
     return launch_compress_masked(W, meta, V, M, K, ldw, t, l, static_cast<hipStream_t>(stream));
 }
 
+sp24_status sp24_permute_columns(const void* A, const int32_t* perm, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp,
+                                 sp24_dtype t, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (M < 0 || !k_legal(K, t) || K > 0x7FFFFFFF) return SP24_ERR_SHAPE;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(A, M, K, lda, es);
+    if (s != SP24_OK) return s;
+    s = check_matrix(P, M, K, ldp, es);
+    if (s != SP24_OK) return s;
+    if (M == 0) return SP24_OK;
+    if (!perm) return SP24_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(perm) % 4 != 0) return SP24_ERR_ALIGN;
+    size_t na = ((size_t)(M - 1) * lda + K) * es, np = ((size_t)(M - 1) * ldp + K) * es;
+    if (ranges_overlap(A, na, P, np) || ranges_overlap(P, np, perm, (size_t)K * 4)) return SP24_ERR_SHAPE;
+    return launch_permute_columns(A, perm, P, M, K, lda, ldp, t, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_retained_magnitude(const void* A, const int32_t* perm, double* total, int64_t M, int64_t K, int64_t lda,
+                                    sp24_dtype t, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (M < 0 || !k_legal(K, t) || K > 0x7FFFFFFF) return SP24_ERR_SHAPE;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(A, M, K, lda, es);
+    if (s != SP24_OK) return s;
+    if (!total) return SP24_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(total) % 8 != 0 || reinterpret_cast<uintptr_t>(perm) % 4 != 0) return SP24_ERR_ALIGN;
+    if (M > 0) {
+        size_t na = ((size_t)(M - 1) * lda + K) * es;
+        if (ranges_overlap(A, na, total, 8) || (perm && ranges_overlap(perm, (size_t)K * 4, total, 8))) return SP24_ERR_SHAPE;
+    }
+    return launch_retained_magnitude(A, perm, total, M, K, lda, t, static_cast<hipStream_t>(stream));
+}
+
 static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
 {
     if (!is_input_type(a.in) || !out_legal(a.in, a.out, a.epi.on != 0)) return SP24_ERR_DTYPE;

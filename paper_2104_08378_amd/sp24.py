@@ -47,6 +47,8 @@ def lib():
         L.sp24_prune_transposable.argtypes = [vp, vp, i64, i64, i64, i64, i32, vp]
         L.sp24_mask_apply.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, i32, vp]
         L.sp24_compress_masked.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
+        L.sp24_permute_columns.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp]
+        L.sp24_retained_magnitude.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
         L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
         L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
         L.sp24_spmm_conv2d.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i32, i32, i32, vp]
@@ -143,6 +145,39 @@ def sp24_prune_transposable(A, out=None):
     _check(lib().sp24_prune_transposable(A.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype], _stream()),
            "sp24_prune_transposable")
     return P
+
+
+def _perm_arg(perm, K):
+    _dev(perm, "perm")
+    if perm.dtype != torch.int32 or perm.dim() != 1 or perm.numel() != K or not perm.is_contiguous():
+        raise ValueError("perm must be a contiguous int32 device tensor with K entries")
+    return perm
+
+
+def sp24_permute_columns(A, perm, out=None):
+    """The matrix with its columns in the order perm: out[:, k] = A[:, perm[k]]."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    _perm_arg(perm, K)
+    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_permute_columns(A.data_ptr(), perm.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype],
+                                      _stream()), "sp24_permute_columns")
+    return P
+
+
+def sp24_retained_magnitude(A, perm=None, out=None):
+    """Total magnitude that 2:4 pruning keeps with the groups of four formed in the column order perm (a 1-element
+    float64 device tensor; no synchronisation)."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    if perm is not None:
+        _perm_arg(perm, K)
+    total = torch.empty(1, dtype=torch.float64, device=A.device) if out is None else _dev(out, "out")
+    if total.dtype != torch.float64 or total.numel() != 1:
+        raise ValueError("out must be one float64")
+    _check(lib().sp24_retained_magnitude(A.data_ptr(), perm.data_ptr() if perm is not None else None, total.data_ptr(), M, K,
+                                         A.stride(0), _DT[A.dtype], _stream()), "sp24_retained_magnitude")
+    return total
 
 
 def sp24_mask_apply(W, meta, layout="canonical", out=None):

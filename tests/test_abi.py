@@ -169,3 +169,24 @@ def test_transposable_pruning_validation():
     assert f(0, Pp, 64, 64, 64, 64, sp24.F16, None) == NULL and f(A, Pp + 4, 64, 64, 64, 64, sp24.F16, None) == ALIGN
     assert f(A, A + 64, 64, 64, 64, 64, sp24.I8, None) == SHAPE       # partial overlap
     assert f(A, Pp, 0, 64, 64, 64, sp24.F16, None) == OK
+
+
+def test_channel_permutation_validation():
+    L = sp24.lib()
+    A, Pp, perm, tot = P, P + 0x1000000, P + 0x2000000, P + 0x3000000
+    f = L.sp24_permute_columns
+    assert f(A, perm, Pp, 64, 64, 64, 64, sp24.F32, None) == DTYPE
+    assert f(A, perm, Pp, 64, 24, 64, 64, sp24.F16, None) == SHAPE       # K % 16
+    assert f(A, perm, Pp, 64, 64, 32, 64, sp24.F16, None) == SHAPE       # lda < K
+    assert f(A, perm, Pp, 64, 1 << 31, 1 << 31, 1 << 31, sp24.I8, None) == SHAPE   # K must fit the int32 entries
+    assert f(0, perm, Pp, 64, 64, 64, 64, sp24.F16, None) == NULL and f(A, 0, Pp, 64, 64, 64, 64, sp24.F16, None) == NULL
+    assert f(A, perm + 2, Pp, 64, 64, 64, 64, sp24.F16, None) == ALIGN and f(A, perm, Pp + 4, 64, 64, 64, 64, sp24.F16, None) == ALIGN
+    assert f(A, perm, A, 64, 64, 64, 64, sp24.I8, None) == SHAPE         # in place is not possible for a gather
+    assert f(A, Pp + 64, Pp, 64, 64, 64, 64, sp24.I8, None) == SHAPE     # the order must not lie in the output
+    assert f(A, perm, Pp, 0, 64, 64, 64, sp24.F16, None) == OK
+    g = L.sp24_retained_magnitude
+    assert g(A, perm, tot, 64, 64, 64, sp24.I32, None) == DTYPE
+    assert g(A, perm, tot, 64, 48, 64, sp24.I8, None) == SHAPE           # K % 32
+    assert g(0, perm, tot, 64, 64, 64, sp24.F16, None) == NULL and g(A, perm, 0, 64, 64, 64, sp24.F16, None) == NULL
+    assert g(A, perm, tot + 4, 64, 64, 64, sp24.F16, None) == ALIGN and g(A, perm + 1, tot, 64, 64, 64, sp24.F16, None) == ALIGN
+    assert g(A, perm, A + 64, 64, 64, 64, sp24.F16, None) == SHAPE       # the total must not lie in the matrix
