@@ -11,9 +11,12 @@ Prints one JSON line.  `value` is the metric: dense-equivalent TFLOP/s of the
 sparse product, 2*M*N*K divided by its mean duration, measured with HIP events
 on the launch stream: the whole-path steps give `ms_per_step` (wall time of a
 step) and `step_ms` (event pair around every launch), and the two products are
-then timed as back-to-back launches on the same inputs (`kernel_ms_back_to_back`),
-which is the duration `value`, `speedup_vs_dense` and `roofline` use.  `roofline` describes the sparse product kernel, `cpu_baseline`
-the CPU oracle timed on a bounded sample of the same workload.
+then timed as back-to-back launches on the same rotating inputs
+(`kernel_ms_back_to_back`: five batches, the median), which is the duration
+`value`, `speedup_vs_dense` and `roofline` use; `kernel_ms_cache_warm` is the
+same on one input set (operands resident in the last-level cache), for
+comparison only.  `roofline` describes the sparse product kernel,
+`cpu_baseline` the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -247,23 +250,29 @@ def main():
     # (about 3.5 us here, a fifth of the skinny product); a kernel profiler does not.  So the two products are
     # timed once more as `steps` back-to-back launches each, on the same rotating inputs, one event pair around
     # the batch: the mean of that is what rocprofv3 --kernel-trace reports as the kernel's average duration.
-    def back_to_back(op):
+    # Five batches each, the median reported.  `same_inputs`: every launch on input set 0, i.e. operands resident in
+    # the 256 MB last-level cache -- reported separately (`kernel_ms_cache_warm`), never used for `value`.
+    def back_to_back(op, same_inputs=False):
         if op not in only:
             return 0.0
         saved = list(only)
         only[:] = [op]
-        for i in range(3):
-            step(i)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(args.steps):
-            step(i)
-        e1.record()
-        torch.cuda.synchronize()
+        for i in range(5):
+            step(0 if same_inputs else i)
+        batches = []
+        for rep in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(args.steps):
+                step(0 if same_inputs else i)
+            e1.record()
+            torch.cuda.synchronize()
+            batches.append(e0.elapsed_time(e1) / args.steps)
         only[:] = saved
-        return e0.elapsed_time(e1) / args.steps
+        return float(np.median(batches))
     ms_b2b = {"spmm": back_to_back("spmm"), "dense": back_to_back("dense")}
+    ms_warm = {"spmm": back_to_back("spmm", True), "dense": back_to_back("dense", True)}
 
     # Context, not the product: the vendor library's dense GEMM on the same shape and the same rotating inputs
     # (torch.matmul / torch._int_mm, i.e. hipBLASLt or rocBLAS), the counterpart of the paper's dense denominator
@@ -327,7 +336,7 @@ def main():
         "config": {"workload": name, "M": M, "N": N, "K": K, "out": w["out"], "layout": "tiled",
                    "b_order": "implicit im2col of NHWC 64x14x14x256, 3x3, pad 1" if conv else "k-major",
                    "rotating_input_sets": R},
-        "step_ms": ms, "kernel_ms_back_to_back": ms_b2b,
+        "step_ms": ms, "kernel_ms_back_to_back": ms_b2b, "kernel_ms_cache_warm": ms_warm,
         "speedup_vs_dense": (t_dn / t_sp) if ("dense" in only and "spmm" in only) else None,
         "dense_tflops": flops_equiv / t_dn / 1e12 if "dense" in only else None,
         "vendor_dense": vendor,
