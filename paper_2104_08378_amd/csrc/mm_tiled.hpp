@@ -584,16 +584,24 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     int m_first[TM];
     int8v f_first[2];
 
-    // One step (stage u holds its operands; fragments t = 0 .. NF-1, TM instructions each).  LDS reads run two
-    // fragments ahead of the arithmetic.
-    //   barrier 0: every wavefront has finished the previous step, so the stage it read is free:
-    //              the transfers for step s+2 go there, dealt out between the instructions of t < T1;
-    //   barrier 1 (before t = T1): this wavefront's transfers for step s+1 have landed (vmcnt counts in order:
-    //              only the NV just issued may still be in flight), the barrier makes everybody's visible;
-    //   t >= T1:   the first operands of step s+1 are read while the last instructions of step s run, so that
-    //              no wavefront starts a step waiting for LDS.
+    // One step s (stage u holds its operands; fragments t = 0 .. NF-1, TM instructions each).  LDS reads run two
+    // fragments ahead of the arithmetic, so by t = T1 every read of stage u has been issued.  One barrier per step,
+    // before t = T1.  A wavefront arrives there when
+    //   * its own transfers for step s+1 have landed (vmcnt counts in order: only those of the NS - 2 later steps,
+    //     all issued by now, may still be in flight), and
+    //   * its reads of stage u have returned (lgkmcnt 0).
+    // Past the barrier, therefore, stage u+1 is complete and visible -- the first operands of step s+1 are read
+    // while the last instructions of step s run, so that no wavefront starts a step waiting for LDS -- and stage u
+    // is free: the transfers for step s+NS go there, dealt out between the matrix instructions from here to the
+    // next barrier (the first 2 of NF fragments' worth in this step, the rest at t < T1 of step s+1).
     constexpr int NF = 2 * TN, T1 = NF - 2;
     constexpr int kWait = waitcnt_vm((NS - 2) * NV);
+    constexpr int kWaitAndReads = kWait & ~(15 << 8);      // the same, and lgkmcnt 0
+    // transfer numbers dealt to slot m of the NF * TM matrix instructions between two barriers
+    auto dma_slot = [&](int m, int u) {
+#pragma unroll
+        for (int x = m * NV / (NF * TM); x < (m + 1) * NV / (NF * TM); ++x) dma_one(f_step, f_tap, u, x, std::false_type{});
+    };
     auto do_step = [&](int u) {
         const uint8_t* cur = stage_ptr(u);
         const uint8_t* nxt = stage_ptr((u + 1) % NS);
@@ -604,16 +612,15 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
         for (int i = 0; i < TM; ++i) { av[0][i] = a_first[i]; mv[0][i] = m_first[i]; }
         f[0] = f_first[0];
         f[1] = f_first[1];
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < NF; ++t) {
             const int j = t / TN, nj = t % TN;
             if (t == T1) {
                 __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_waitcnt(kWait);
+                __builtin_amdgcn_s_waitcnt(kWaitAndReads);
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
+                advance_fetch();                         // from here on: the transfers of step s+NS, into stage u
             }
             if (t + 2 < NF) read_frag(cur, t + 2, f[(t + 2) % 3]);
             else read_frag(nxt, t + 2 - NF, f_first[t + 2 - NF]);
@@ -624,23 +631,23 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
                 if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t % 3], acc[i][nj], mv[j][i]);
                 else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], f[t % 3], acc[i][nj], mv[0][i]);
                 else acc[i][nj] = smfmac32<DT, 1>(av[1][i], f[t % 3], acc[i][nj], mv[0][i]);
-                if (t < T1) {
-                    const int m = t * TM + i;
-#pragma unroll
-                    for (int x = m * NV / (T1 * TM); x < (m + 1) * NV / (T1 * TM); ++x) dma_one(f_step, f_tap, (u + NS - 1) % NS, x, std::false_type{});
-                }
+                if (t < T1) dma_slot(2 * TM + t * TM + i, (u + NS - 1) % NS);
+                else dma_slot((t - T1) * TM + i, u);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        advance_fetch();
     };
     if (nsteps > 0) {
-        // prologue: the first NS - 1 stages on their way; first operands of step 0 once stage 0 has landed
+        // prologue: the first NS - 1 stages on their way, and of the next step what a step issues after its barrier;
+        // first operands of step 0 once stage 0 has landed (the wait leaves room for the NS - 2 later stages only,
+        // a few transfers more than it must)
 #pragma unroll
         for (int u = 0; u < NS - 1; ++u) {
             dma(f_step, f_tap, u);
             advance_fetch();
         }
+#pragma unroll
+        for (int m = 0; m < 2 * TM; ++m) dma_slot(m, NS - 1);
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(kWait);
         __builtin_amdgcn_s_barrier();
