@@ -39,10 +39,10 @@ MEASURED_SPARSE_ISSUE = {"f16": 3.105e15, "bf16": 3.221e15, "i8": 6.656e15}
 # (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a 1 GiB device copy;
 # summaries under profiles/).  None where not measured.
 MEASURED_TRAFFIC = {
-    "ffn_bf16": (2.0 * 31548.3 + 66970.1) * 1024,      # profiles/ffn_bf16_path_rocprofv3.txt    (algorithmic: 88.6 MB)
-    "square_i8": (2.0 * 295027.0 + 262370.6) * 1024,   # profiles/square_i8_path_rocprofv3.txt   (algorithmic: 377.5 MB)
-    "skinny_bf16": (2.0 * 37924.8 + 256.0) * 1024,     # profiles/skinny_bf16_path_rocprofv3.txt  (algorithmic: 76.0 MB)
-    "conv3x3_f16": (2.0 * 5992.8 + 6272.0) * 1024,     # profiles/conv3x3_f16_path_rocprofv3.txt  (algorithmic: 13.5 MB, implicit gather)
+    "ffn_bf16": (2.0 * 31689.9 + 65676.0) * 1024,      # profiles/ffn_bf16_path_rocprofv3.txt    (algorithmic: 88.6 MB)
+    "square_i8": (2.0 * 295046.5 + 262226.5) * 1024,   # profiles/square_i8_path_rocprofv3.txt   (algorithmic: 377.5 MB)
+    "skinny_bf16": (2.0 * 37924.6 + 256.0) * 1024,     # profiles/skinny_bf16_path_rocprofv3.txt  (algorithmic: 76.0 MB)
+    "conv3x3_f16": (2.0 * 5991.1 + 6272.0) * 1024,     # profiles/conv3x3_f16_path_rocprofv3.txt  (algorithmic: 13.5 MB, implicit gather)
 }
 
 
