@@ -60,6 +60,9 @@ def parse():
                    help="also time the operations beyond the five-step path on this workload's operands: the retraining "
                         "support (mask apply, fixed-mask compress, row-and-column pruning) and, for int8, the product "
                         "with the quantised path's epilogue; each beside the CPU oracle on a sample")
+    p.add_argument("--sweep", action="store_true",
+                   help="add the counterpart of the paper's speedup plot (Sec. 3.2, Fig. 3): M = N = 8192, the inner dimension "
+                        "swept, sparse product against the own and the vendor's dense product (bf16 and int8 workloads)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one 1 GiB device copy, so that a counter profile of this run holds a kernel of known traffic")
     return p.parse_args()
@@ -167,6 +170,60 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
                                           "dense_equiv_Tops": 2.0 * M * N * K / ts / 1e12,
                                           "frac_of_sparse_peak": M * N * K / ts / PEAK_DENSE[dt]}
     return out
+
+
+def sweep(name, steps):
+    """Sparse against dense over the inner dimension at M = N = 8192 (the paper's Fig. 3 plots the speedup over GEMM-K
+    for large M and N).  Inputs drawn on the device with torch's seeded generator, same distributions as the workload;
+    enough rotating sets that the operands do not stay in the last-level cache."""
+    import torch
+    from paper_2104_08378_amd import sp24, synth
+    from util import OUT_DT
+    w = synth.WORKLOADS[name]
+    dt, out_dt = w["dtype"], OUT_DT[w["out"]]
+    M = N = 8192
+    gen = torch.Generator(device="cuda").manual_seed(0)
+
+    def draw(rows, cols, sigma):
+        if dt == "i8":
+            return torch.randint(-127, 128, (rows, cols), dtype=torch.int8, device="cuda", generator=gen)
+        x = torch.randn((rows, cols), dtype=torch.float32, device="cuda", generator=gen) * sigma
+        return x.to(torch.bfloat16 if dt == "bf16" else torch.float16)
+
+    def timed(fn):
+        for i in range(5):
+            fn(i)
+        batches = []
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(steps):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            batches.append(e0.elapsed_time(e1) / steps)
+        return sorted(batches)[1] * 1e-3
+
+    rows = []
+    for K in (512, 1024, 2048, 4096, 8192, 16384):
+        es = 1 if dt == "i8" else 2
+        R = max(2, min(24, int(600e6 // ((M + N) * K * es)) + 1))
+        As = [draw(M, K, 0.02) for _ in range(R)]
+        Bs = [draw(N, K, 1.0) for _ in range(R)]
+        VM = [sp24.sp24_compress(a, layout="tiled") for a in As]
+        Ps = [sp24.sp24_prune(a) for a in As]
+        D = torch.empty((M, N), dtype=out_dt, device="cuda")
+        t_sp = timed(lambda i: sp24.sp24_spmm(VM[i % R][0], VM[i % R][1], Bs[i % R], out_dt, layout="tiled", out=D))
+        t_dn = timed(lambda i: sp24.sp24_gemm_dense(Ps[i % R], Bs[i % R], out_dt, out=D))
+        mm = (lambda a, b: torch._int_mm(a, b.t())) if dt == "i8" else (lambda a, b: torch.matmul(a, b.t()))
+        t_v = timed(lambda i: mm(Ps[i % R], Bs[i % R]))
+        rows.append({"K": K, "sparse_us": t_sp * 1e6, "dense_us": t_dn * 1e6, "vendor_dense_us": t_v * 1e6,
+                     "speedup_vs_dense": t_dn / t_sp, "speedup_vs_vendor_dense": t_v / t_sp,
+                     "sparse_dense_equiv_Tops": 2.0 * M * N * K / t_sp / 1e12})
+        del As, Bs, VM, Ps, D
+        torch.cuda.empty_cache()
+    return {"M": M, "N": N, "rows": rows}
 
 
 def main():
@@ -370,6 +427,8 @@ def main():
         "decompress_GBps": bytes_pc / (ms["decompress"] * 1e-3) / 1e9 if "decompress" in only else None,
         "roofline": roof,
     }
+    if args.sweep and name in ("ffn_bf16", "square_i8"):
+        line["sweep_over_K"] = sweep(name, max(5, args.steps // 2))
     if args.extras:
         line["extras"] = extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A, args.steps, conv)
     if args.cpu_seconds > 0:
