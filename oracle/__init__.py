@@ -49,6 +49,7 @@ def _load():
         lib.sp24o_mask_apply.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_compress_masked.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_permute_columns.argtypes = [vp, vp, vp, i64, i64, i32]
+        lib.sp24o_permute_rows.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_retained_magnitude.argtypes = [vp, vp, i64, i64, i32, vp]
         f32 = ctypes.c_float
         lib.sp24o_dequant_f64.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32]
@@ -162,6 +163,19 @@ def permute_columns(A, perm, dtype):
     rc = _load().sp24o_permute_columns(_ptr(A), _ptr(perm), _ptr(P), A.shape[0], A.shape[1], _TYPES[dtype])
     if rc:
         raise ValueError(f"oracle permute_columns: perm is not a permutation of 0..K-1 ({rc})")
+    return P
+
+
+def permute_rows(A, perm, dtype):
+    """Sec. 4.1 Step 2, the producing layer's side: the matrix with its rows in the order perm, P[m] = A[perm[m]]."""
+    _check(A, dtype)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    if perm.shape != (A.shape[0],):
+        raise ValueError("perm must hold M entries")
+    P = np.empty_like(A)
+    rc = _load().sp24o_permute_rows(_ptr(A), _ptr(perm), _ptr(P), A.shape[0], A.shape[1], _TYPES[dtype])
+    if rc:
+        raise ValueError(f"oracle permute_rows: perm is not a permutation of 0..M-1 ({rc})")
     return P
 
 

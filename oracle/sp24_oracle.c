@@ -513,6 +513,33 @@ int sp24o_permute_columns(const void *A, const int32_t *perm, void *P, long M, l
 }
 
 /*
+ * The companion step (Sec. 4.1, Step 2): the rows of the matrix in the order
+ * perm, P[m][:] = A[perm[m]][:] -- what is done to the weights of the layer
+ * that produces the activations, so that the product stays the same.
+ * perm must hold every row 0 .. M-1 once (else 2).
+ */
+int sp24o_permute_rows(const void *A, const int32_t *perm, void *P, long M, long K, int t)
+{
+    int es = esize(t);
+    if (es == 0)
+        return 1;
+    char *seen = (char *)calloc((size_t)(M > 0 ? M : 1), 1);
+    if (!seen)
+        return 3;
+    for (long m = 0; m < M; ++m) {
+        if (perm[m] < 0 || perm[m] >= M || seen[perm[m]]) {
+            free(seen);
+            return 2;
+        }
+        seen[perm[m]] = 1;
+    }
+    free(seen);
+    for (long m = 0; m < M; ++m)
+        memcpy((char *)P + m * K * es, (const char *)A + (long)perm[m] * K * es, (size_t)(K * es));
+    return 0;
+}
+
+/*
  * The figure of merit of a column order (Fig. 5: "total weight magnitude"
  * after pruning): the sum of |a| over the elements that the selection rule of
  * Step 2 keeps when the groups of four are formed from columns perm[4g] ..

@@ -686,3 +686,29 @@ def test_retained_magnitude_best_split_of_eight_columns_by_brute_force():
     L[:, :4] = rng.integers(50, 100, size=(5, 4))
     assert oracle.retained_magnitude(L, "i8", perm=[0, 1, 4, 5, 2, 3, 6, 7]) == np.abs(L.astype(np.int64)).sum()
     assert oracle.retained_magnitude(L, "i8") < np.abs(L.astype(np.int64)).sum()
+
+
+@pytest.mark.parametrize("dt", DTYPES)
+def test_permute_rows_is_numpy_fancy_indexing_and_keeps_the_product(dt):
+    name = {"f16": "tiny_f16", "bf16": "ffn_bf16", "i8": "square_i8"}[dt]
+    W1, X = synth.make(name, M=48, N=8, K=32, seed=23)          # producing layer: 48 outputs from 32 inputs, 8 tokens
+    rng = np.random.default_rng(8)
+    perm = rng.permutation(48).astype(np.int32)
+    P = oracle.permute_rows(W1, perm, dt)
+    assert np.array_equal(P, W1[perm])
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(48, dtype=np.int32)
+    assert np.array_equal(oracle.permute_rows(P, inv, dt), W1)
+    with pytest.raises(ValueError):
+        oracle.permute_rows(W1, np.zeros(48, dtype=np.int32), dt)
+    if dt == "i8":
+        # Sec. 4.1: permuting the rows of the producing layer permutes the activations' rows the same way, and the
+        # consuming layer with its columns in that order gives the same result (exact in integers; no activation
+        # function in between here)
+        W2, _ = synth.make(name, M=16, N=8, K=64, seed=24)
+        W2 = W2[:, :48].copy()                                   # consuming layer: 16 outputs from the 48 activations
+        act = W1.astype(np.int64) @ X.astype(np.int64).T        # [48, 8]
+        out = W2.astype(np.int64) @ act
+        act_p = oracle.permute_rows(W1, perm, dt).astype(np.int64) @ X.astype(np.int64).T
+        out_p = W2[:, perm].astype(np.int64) @ act_p
+        assert np.array_equal(out, out_p)
