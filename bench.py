@@ -141,6 +141,7 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
     Vm = torch.empty_like(V)
     perm_h = np.random.default_rng(0).permutation(K).astype(np.int32)
     perm_d = torch.from_numpy(perm_h).cuda()
+    rperm_d = torch.from_numpy(np.random.default_rng(1).permutation(M).astype(np.int32)).cuda()
     total = torch.empty(1, dtype=torch.float64, device="cuda")
     out = {}
     ops = {
@@ -155,6 +156,8 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
                             lambda: oracle.permute_columns(sample, perm_h, dt)),
         "retained_magnitude": (lambda i: sp24.sp24_retained_magnitude(As[i % R], perm_d, out=total), 1.0 * M * K * es + 4.0 * K,
                                lambda: oracle.retained_magnitude(sample, dt, perm=perm_h)),
+        "permute_rows": (lambda i: sp24.sp24_permute_rows(As[i % R], rperm_d, out=Pm), 2.0 * M * K * es + 4.0 * M,
+                         lambda: oracle.permute_rows(sample, np.random.default_rng(1).permutation(rows).astype(np.int32), dt)),
     }
     for op, (fn, nbytes, cfn) in ops.items():
         t = timed(fn)

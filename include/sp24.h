@@ -150,6 +150,17 @@ sp24_status sp24_permute_columns(const void* A, const int32_t* perm, void* P, in
                                  int64_t lda, int64_t ldp, sp24_dtype t, void* stream);
 
 /*
+ * The companion of sp24_permute_columns on the layer that produces the
+ * activations (Sec. 4.1, Step 2: the rows of that layer's weights are permuted
+ * so that its outputs arrive in the order the permuted columns expect):
+ * P[m][:] = A[perm[m]][:], bit for bit.  perm: M int32 entries in device
+ * memory, a permutation of 0 .. M-1 (an entry outside that range reads row 0).
+ * A and P as for sp24_prune, not overlapping.  M < 2^31.
+ */
+sp24_status sp24_permute_rows(const void* A, const int32_t* perm, void* P, int64_t M, int64_t K,
+                              int64_t lda, int64_t ldp, sp24_dtype t, void* stream);
+
+/*
  * Fig. 5's figure of merit for a column order: *total (one double in device
  * memory, 8-byte aligned, overwritten) = the sum of |a| over the elements that
  * sp24_prune would keep if the groups of four were formed from columns

@@ -191,6 +191,24 @@ sp24_status sp24_permute_columns(const void* A, const int32_t* perm, void* P, in
     return launch_permute_columns(A, perm, P, M, K, lda, ldp, t, static_cast<hipStream_t>(stream));
 }
 
+sp24_status sp24_permute_rows(const void* A, const int32_t* perm, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t,
+                              void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (M < 0 || M > 0x7FFFFFFF || !k_legal(K, t)) return SP24_ERR_SHAPE;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(A, M, K, lda, es);
+    if (s != SP24_OK) return s;
+    s = check_matrix(P, M, K, ldp, es);
+    if (s != SP24_OK) return s;
+    if (M == 0) return SP24_OK;
+    if (!perm) return SP24_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(perm) % 4 != 0) return SP24_ERR_ALIGN;
+    size_t na = ((size_t)(M - 1) * lda + K) * es, np = ((size_t)(M - 1) * ldp + K) * es;
+    if (ranges_overlap(A, na, P, np) || ranges_overlap(P, np, perm, (size_t)M * 4)) return SP24_ERR_SHAPE;
+    return launch_permute_rows(A, perm, P, M, K, lda, ldp, t, static_cast<hipStream_t>(stream));
+}
+
 sp24_status sp24_retained_magnitude(const void* A, const int32_t* perm, double* total, int64_t M, int64_t K, int64_t lda,
                                     sp24_dtype t, void* stream)
 {

@@ -14,6 +14,8 @@ sp24_status launch_mask_apply(const void* W, const void* meta, void* P, int64_t 
                               sp24_layout l, hipStream_t st);
 sp24_status launch_permute_columns(const void* A, const void* perm, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t,
                                    hipStream_t st);
+sp24_status launch_permute_rows(const void* A, const void* perm, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t,
+                                hipStream_t st);
 sp24_status launch_retained_magnitude(const void* A, const void* perm, double* out, int64_t M, int64_t K, int64_t lda, sp24_dtype t,
                                       hipStream_t st);
 sp24_status launch_compress_masked(const void* W, const void* meta, void* V, int64_t M, int64_t K, int64_t ldw, sp24_dtype t,

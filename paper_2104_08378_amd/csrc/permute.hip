@@ -226,6 +226,32 @@ __global__ __launch_bounds__(64 * kPermWaves) void k_retained_magnitude(const ui
     }
 }
 
+// P[m][:] = A[perm[m]][:]: whole rows, 16 bytes per lane, one row per wavefront and pass.  An entry outside
+// 0 .. M-1 reads row 0.
+__global__ __launch_bounds__(64 * kPermWaves) void k_permute_rows(const uint8_t* A, const int32_t* perm, uint8_t* P, int64_t M, int64_t row_bytes,
+                                                                  int64_t lda_bytes, int64_t ldp_bytes)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int64_t row = (int64_t)blockIdx.x * kPermWaves + wave; row < M; row += (int64_t)gridDim.x * kPermWaves) {
+        const uint32_t p = (uint32_t)perm[row];
+        const uint8_t* src = A + (p < (uint64_t)M ? (int64_t)p : 0) * lda_bytes;
+        uint8_t* dst = P + row * ldp_bytes;
+        for (int64_t c0 = 0; c0 < row_bytes / 16; c0 += 8 * 64) {     // eight loads in flight per lane
+            uint4v part[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int64_t c = c0 + 64 * j + lane;
+                if (c < row_bytes / 16) part[j] = reinterpret_cast<const uint4v*>(src)[c];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int64_t c = c0 + 64 * j + lane;
+                if (c < row_bytes / 16) reinterpret_cast<uint4v*>(dst)[c] = part[j];
+            }
+        }
+    }
+}
+
 static sp24_status launch_result() { return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH; }
 
 static unsigned grid_for_rows(int64_t M)
@@ -260,6 +286,18 @@ sp24_status launch_permute_columns(const void* A, const void* perm, void* P, int
     const size_t lds = staged_lds_bytes(K, esize_of(t));
     if (t == SP24_I8) k_permute_columns<1><<<grid, block, lds, st>>>(a, p, o, M, K, lda, ldp);
     else k_permute_columns<2><<<grid, block, lds, st>>>(a, p, o, M, K, lda, ldp);
+    return launch_result();
+}
+
+sp24_status launch_permute_rows(const void* A, const void* perm, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t,
+                                hipStream_t st)
+{
+    if (M * K == 0) return SP24_OK;
+    const int es = esize_of(t);
+    const int64_t passes = (M + kPermWaves - 1) / kPermWaves;
+    const dim3 grid((unsigned)(passes < 4096 ? passes : 4096)), block(64 * kPermWaves);
+    k_permute_rows<<<grid, block, 0, st>>>(static_cast<const uint8_t*>(A), static_cast<const int32_t*>(perm), static_cast<uint8_t*>(P), M,
+                                           K * es, lda * es, ldp * es);
     return launch_result();
 }
 

@@ -48,6 +48,7 @@ def lib():
         L.sp24_mask_apply.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, i32, vp]
         L.sp24_compress_masked.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.sp24_permute_columns.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp]
+        L.sp24_permute_rows.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp]
         L.sp24_retained_magnitude.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
         L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
         L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
@@ -150,7 +151,7 @@ def sp24_prune_transposable(A, out=None):
 def _perm_arg(perm, K):
     _dev(perm, "perm")
     if perm.dtype != torch.int32 or perm.dim() != 1 or perm.numel() != K or not perm.is_contiguous():
-        raise ValueError("perm must be a contiguous int32 device tensor with K entries")
+        raise ValueError("perm must be a contiguous int32 device tensor with one entry per column (row)")
     return perm
 
 
@@ -162,6 +163,17 @@ def sp24_permute_columns(A, perm, out=None):
     P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
     _check(lib().sp24_permute_columns(A.data_ptr(), perm.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype],
                                       _stream()), "sp24_permute_columns")
+    return P
+
+
+def sp24_permute_rows(A, perm, out=None):
+    """The matrix with its rows in the order perm: out[m] = A[perm[m]]."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    _perm_arg(perm, M)
+    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_permute_rows(A.data_ptr(), perm.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype],
+                                   _stream()), "sp24_permute_rows")
     return P
 
 

@@ -190,3 +190,9 @@ def test_channel_permutation_validation():
     assert g(0, perm, tot, 64, 64, 64, sp24.F16, None) == NULL and g(A, perm, 0, 64, 64, 64, sp24.F16, None) == NULL
     assert g(A, perm, tot + 4, 64, 64, 64, sp24.F16, None) == ALIGN and g(A, perm + 1, tot, 64, 64, 64, sp24.F16, None) == ALIGN
     assert g(A, perm, A + 64, 64, 64, 64, sp24.F16, None) == SHAPE       # the total must not lie in the matrix
+    h = L.sp24_permute_rows
+    assert h(A, perm, Pp, 64, 64, 64, 64, sp24.I32, None) == DTYPE
+    assert h(A, perm, Pp, 1 << 31, 64, 64, 64, sp24.I8, None) == SHAPE  # M must fit the int32 entries
+    assert h(A, 0, Pp, 64, 64, 64, 64, sp24.F16, None) == NULL and h(A, perm + 2, Pp, 64, 64, 64, 64, sp24.F16, None) == ALIGN
+    assert h(A, perm, A + 128, 64, 64, 64, 64, sp24.F16, None) == SHAPE   # overlapping source and destination
+    assert h(A, perm, Pp, 0, 64, 64, 64, sp24.F16, None) == OK

@@ -54,6 +54,30 @@ def test_permute_columns_bit_exact(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_permute_rows_bit_exact(dtype):
+    for i, (M, K) in enumerate(SHAPES):
+        A = synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=110 + i)[0]
+        perm = np.random.default_rng(120 + i).permutation(M).astype(np.int32)
+        P = sp24.sp24_permute_rows(to_gpu(A, dtype), dev_perm(perm))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(P), oracle.permute_rows(A, perm, dtype)), (dtype, M, K)
+    # pitched rows on both sides; an entry outside 0..M-1 reads row 0
+    M, K = 37, 96
+    A = synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=116)[0]
+    big = torch.zeros((M, K + 32), dtype=to_gpu(A, dtype).dtype, device="cuda")
+    big[:, :K] = to_gpu(A, dtype)
+    out = torch.zeros((M, K + 64), dtype=big.dtype, device="cuda")
+    perm = np.random.default_rng(19).permutation(M).astype(np.int32)
+    perm[4] = M + 3
+    sp24.sp24_permute_rows(big[:, :K], dev_perm(perm), out=out[:, :K])
+    torch.cuda.synchronize()
+    safe = perm.copy()
+    safe[4] = 0
+    assert np.array_equal(to_bits(out[:, :K]), A[safe])
+    assert not to_bits(out[:, K:]).any()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
 def test_retained_magnitude_matches_the_oracle(dtype):
     for i, (M, K) in enumerate(SHAPES):
         A = synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=90 + i)[0]
