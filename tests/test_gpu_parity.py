@@ -201,7 +201,7 @@ TILED_CASES = [
     ("i8", "i32", 4096, 3328, 640),       # whole 256x256 tiles: pipelined kernel, 5 steps
     ("bf16", "bf16", 3328, 4096, 448),    # 7 steps
     ("f16", "f32", 4096, 3328, 64),       # a single step
-    # more tiles than workgroups resident on the chip: a workgroup walks over several tiles, interior and edge ones
+    # more tiles than compute units (several rounds of workgroups), interior and edge tiles
     ("i8", "i32", 4352, 4000, 384),       # 17 x 16 tiles of 256x256, ragged N, 3 steps
     ("bf16", "bf16", 4384, 4001, 128),    # 18 x 16 tiles, ragged M, odd N (no 16-byte stores), 2 steps
     ("f16", "f32", 3040, 3300, 192),      # 24 x 26 tiles of 128x128, ragged both ways, 3 steps
