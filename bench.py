@@ -388,7 +388,9 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
 
     flops_equiv = 2.0 * M * N * K
-    t_sp, t_dn = ms_b2b["spmm"] * 1e-3, ms_b2b["dense"] * 1e-3
+    # (--only without an operation: its time is taken as infinite, so that its rates read 0 instead of dividing by 0)
+    t_sp = ms_b2b["spmm"] * 1e-3 if "spmm" in only else float("inf")
+    t_dn = ms_b2b["dense"] * 1e-3 if "dense" in only else float("inf")
     value = flops_equiv / t_sp / 1e12 if "spmm" in only else 0.0
     bytes_pc = M * K * es * 1.5 + M * K / 8                  # fused prune+compress: read A, write V + meta
     b_bytes = Bsrc.nbytes                                    # the second operand as it lies in memory

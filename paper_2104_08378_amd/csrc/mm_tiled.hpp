@@ -811,22 +811,24 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
         fb_off[jj] = (BM + wn * 32 * TN + r) * kRowBytes + slot;
     }
 
+    // the fragments of sub-step jj (32 bytes of K) of a stage
+    auto read_frags = [&](const uint8_t* base, int jj, int4v (&xa)[TM], int4v (&xb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) xa[i] = *reinterpret_cast<const int4v*>(base + fa_off[jj] + i * 32 * kRowBytes);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if constexpr (NMAJ) xb[j] = __builtin_bit_cast(int4v, b_nm.piece(base + BM * kRowBytes, jj, j));
+            else xb[j] = *reinterpret_cast<const int4v*>(base + fb_off[jj] + j * 32 * kRowBytes);
+        }
+    };
+    // a whole stage on its own (the partial last step)
     auto compute = [&](int u) {
         const uint8_t* base = stage_ptr(u);
         int4v fa[2][TM], fb[2][TN];
-        auto read_frags = [&](int jj, int4v (&xa)[TM], int4v (&xb)[TN]) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) xa[i] = *reinterpret_cast<const int4v*>(base + fa_off[jj] + i * 32 * kRowBytes);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if constexpr (NMAJ) xb[j] = __builtin_bit_cast(int4v, b_nm.piece(base + BM * kRowBytes, jj, j));
-                else xb[j] = *reinterpret_cast<const int4v*>(base + fb_off[jj] + j * 32 * kRowBytes);
-            }
-        };
-        read_frags(0, fa[0], fb[0]);
+        read_frags(base, 0, fa[0], fb[0]);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            if (jj + 1 < 4) read_frags(jj + 1, fa[(jj + 1) & 1], fb[(jj + 1) & 1]);
+            if (jj + 1 < 4) read_frags(base, jj + 1, fa[(jj + 1) & 1], fb[(jj + 1) & 1]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -834,35 +836,74 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
         }
     };
 
-    constexpr int NMFMA = 4 * TM * TN, NV = NJA + NJB;
+    // One step s (stage u), four sub-steps of TM * TN matrix instructions; fragments are read one sub-step ahead, so
+    // when sub-step 3 begins every read of stage u has been issued.  One barrier per step, before sub-step 3, as in
+    // the sparse kernel: a wavefront arrives when its transfers for step s+1 have landed and its reads of stage u
+    // have returned; past it stage u+1 is visible (its first fragments are read under the last sub-step) and stage u
+    // is free for the transfers of step s+NS.  With two stages those are all issued right behind the barrier -- the
+    // stage is needed again one step later -- else they are spread over the matrix instructions up to the next one.
+    constexpr int NV = NJA + NJB;
+    constexpr int kSlots = (NS == 2) ? TM * TN : 4 * TM * TN;   // matrix instructions the NV transfers are dealt over
+    constexpr int kBehindBarrier = TM * TN * NV / kSlots;       // transfers issued in sub-step 3
+    constexpr int kWaitAndReads = waitcnt_vm((NS - 2) * NV) & ~(15 << 8);
+    auto dma_one = [&](int step, const ConvTap& tap, int u, int x) {
+        if (x < NJA) lds_dma16(a_blk + (int64_t)step * kRowBytes, a_off[x], stage_ptr(u) + (wave * NJA + x) * 1024);
+        else if constexpr (CONV) b_conv.issue(x - NJA, reinterpret_cast<const uint8_t*>(a.B), a.conv, tap, stage_ptr(u) + BM * kRowBytes, wave);
+        else lds_dma16(b_blk + (int64_t)step * b_step, b_off[x - NJA], stage_ptr(u) + BM * kRowBytes + (wave * NJB + x - NJA) * 1024);
+    };
+    auto dma_slot = [&](int m, int u) {
+        if (m < kSlots) {
+#pragma unroll
+            for (int x = m * NV / kSlots; x < (m + 1) * NV / kSlots; ++x) dma_one(f_step, f_tap, u, x);
+        }
+    };
+    int4v fa_first[TM], fb_first[TN];                        // sub-step 0 of the next step
     auto do_step = [&](int u) {
-        // this wavefront's share of stage u has landed (vmcnt counts in issue order: only the transfers of the
-        // NS - 2 later steps may still be in flight) ...
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 2) * NV));
-        __builtin_amdgcn_s_barrier();                // ... and everybody's; the stage read in the previous step is free
-        __builtin_amdgcn_sched_barrier(0);
-        dma(f_step, f_tap, (u + NS - 1) % NS);
-        advance_fetch();
-        compute(u);
-        __builtin_amdgcn_sched_group_barrier(kSgDsRead, TM + TN, 0);
+        const uint8_t* cur = stage_ptr(u);
+        const uint8_t* nxt = stage_ptr((u + 1) % NS);
+        int4v fa[2][TM], fb[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[0][i] = fa_first[i];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[0][j] = fb_first[j];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            if (jj + 1 < 4) __builtin_amdgcn_sched_group_barrier(kSgDsRead, TM + TN, 0);
-#pragma unroll
-            for (int i = 0; i < TM * TN; ++i) {
-                __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
-                if ((jj * TM * TN + i) % (NMFMA / NV) == 0) __builtin_amdgcn_sched_group_barrier(kSgVmem, 1, 0);
+            if (jj == 3) {
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(kWaitAndReads);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                advance_fetch();                             // from here on: the transfers of step s+NS, into stage u
             }
+            if (jj < 3) read_frags(cur, jj + 1, fa[(jj + 1) & 1], fb[(jj + 1) & 1]);
+            else read_frags(nxt, 0, fa_first, fb_first);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    acc[i][j] = mfma32<DT>(fa[jj & 1][i], fb[jj & 1][j], acc[i][j]);
+                    if (jj == 3) dma_slot(j * TM + i, u);
+                    else dma_slot((jj + 1) * TM * TN + j * TM + i, (u + NS - 1) % NS);
+                }
         }
         __builtin_amdgcn_sched_barrier(0);
     };
 
     if (nsteps > 0) {
+        // the first NS - 1 stages on their way, and of the next step what a step issues behind its barrier; the
+        // first fragments once stage 0 has landed
 #pragma unroll
         for (int u = 0; u < NS - 1; ++u) {
             dma(f_step, f_tap, u);
             advance_fetch();
         }
+#pragma unroll
+        for (int m = 0; m < TM * TN; ++m) dma_slot(m, NS - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 2) * NV + kBehindBarrier));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(lds_all, 0, fa_first, fb_first);
         __builtin_amdgcn_sched_barrier(0);
         int step = 0;
         for (; step + NS <= nsteps; step += NS) {
