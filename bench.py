@@ -40,9 +40,9 @@ MEASURED_SPARSE_ISSUE = {"f16": 3.105e15, "bf16": 3.221e15, "i8": 6.656e15}
 # summaries under profiles/).  None where not measured.
 MEASURED_TRAFFIC = {
     "ffn_bf16": (2.0 * 31689.9 + 65676.0) * 1024,      # profiles/ffn_bf16_path_rocprofv3.txt    (algorithmic: 88.6 MB)
-    "square_i8": (2.0 * 295046.5 + 262226.5) * 1024,   # profiles/square_i8_path_rocprofv3.txt   (algorithmic: 377.5 MB)
+    "square_i8": (2.0 * 295235.2 + 262556.3) * 1024,   # profiles/square_i8_path_rocprofv3.txt   (algorithmic: 377.5 MB)
     "skinny_bf16": (2.0 * 37924.6 + 256.0) * 1024,     # profiles/skinny_bf16_path_rocprofv3.txt  (algorithmic: 76.0 MB)
-    "conv3x3_f16": (2.0 * 5991.1 + 6272.0) * 1024,     # profiles/conv3x3_f16_path_rocprofv3.txt  (algorithmic: 13.5 MB, implicit gather)
+    "conv3x3_f16": (2.0 * 5982.6 + 6272.0) * 1024,     # profiles/conv3x3_f16_path_rocprofv3.txt  (algorithmic: 13.5 MB, implicit gather)
 }
 
 
