@@ -338,22 +338,31 @@ def main():
     # (torch.matmul / torch._int_mm, i.e. hipBLASLt or rocBLAS), the counterpart of the paper's dense denominator
     # (Sec. 3.2, Fig. 3 use the vendor's dense library).  Output type: the input type (int32 for int8 inputs).
     def vendor_dense():
-        if conv or "dense" not in only or "spmm" not in only:
+        if "dense" not in only or "spmm" not in only or (name == "conv3x3_f16" and not conv):
             return None
         try:
-            mm = (lambda a, b: torch._int_mm(a, b.t())) if dt == "i8" else (lambda a, b: torch.matmul(a, b.t()))
+            if conv:
+                # the vendor's convolution on the same NHWC activations (channels-last tensors; weights [M][r][s][c] as
+                # the inner dimension orders them), the pruned weights as a dense filter bank
+                wt = P.view(M, 3, 3, K // 9).permute(0, 3, 1, 2)                  # logical NCHW view of channels-last storage
+                xs = [b.view(-1, 14, 14, K // 9).permute(0, 3, 1, 2) for b in Bs]
+                run = lambda i: torch.nn.functional.conv2d(xs[i % R], wt, padding=1)
+            elif dt == "i8":
+                run = lambda i: torch._int_mm(P, Bs[i % R].t())
+            else:
+                run = lambda i: torch.matmul(P, Bs[i % R].t())
             for i in range(3):
-                mm(P, Bs[i % R])
+                run(i)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record()
             for i in range(args.steps):
-                mm(P, Bs[i % R])
+                run(i)
             e1.record()
             torch.cuda.synchronize()
             t = e0.elapsed_time(e1) / args.steps
             return {"ms": t, "speedup_of_sparse": t / ms_b2b["spmm"], "own_dense_over_vendor": ms_b2b["dense"] / t,
-                    "library": "torch %s (%s)" % (torch.__version__, "torch._int_mm" if dt == "i8" else "torch.matmul")}
+                    "library": "torch %s (%s)" % (torch.__version__, "conv2d, channels-last" if conv else "torch._int_mm" if dt == "i8" else "torch.matmul")}
         except Exception as e:                               # a shape the library call does not take
             return {"error": repr(e)[:200]}
     vendor = vendor_dense()
