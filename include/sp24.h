@@ -216,6 +216,11 @@ sp24_status sp24_compress_masked(const void* W, const void* meta, void* V, int64
  * are accumulated in fp32 and written as `out` = SP24_F32, SP24_F16 or
  * SP24_BF16 (one rounding, to nearest even); int8 products are accumulated in
  * int32 and `out` must be SP24_I32 (exact for K <= 2^17).
+ * The removed half of A takes no part in the sum (Sec. 3.2: the multiplications
+ * by zero are skipped): where B holds an infinity or a NaN opposite a removed
+ * position, the result is the finite sum of the kept products, whereas the
+ * dense product of the pruned matrix has 0 x inf = NaN there.  NaN and
+ * infinities in kept positions propagate as IEEE arithmetic gives them.
  * B: device, ldb >= K (K-major) or ldb >= N (N-major).  D: device, M x N,
  * ldd >= N; must not overlap the inputs.
  */

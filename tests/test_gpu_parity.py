@@ -336,3 +336,38 @@ def test_empty_problem_is_a_no_op():
     V, meta = sp24.sp24_compress(A)
     B = torch.zeros((16, 64), dtype=torch.float16, device="cuda")
     assert sp24.sp24_spmm(V, meta, B, torch.float32).shape == (0, 16)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("out", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("shape", [(64, 64, 64), (256, 320, 128)])          # the general kernel, the tiled kernel
+def test_special_values_reach_the_output_as_ieee_conversion_gives_them(dtype, out, shape):
+    """Small integers (sums exact in any order), a NaN weight, infinities and sums beyond the 16-bit ranges: the stored
+    result is the exact sum converted once, round to nearest even -- NaN stays NaN, overflow becomes infinity."""
+    M, N, K = shape
+    rng = np.random.default_rng(31)
+    A = rng.integers(-3, 4, size=(M, K)).astype(np.float64)
+    B = rng.integers(-4, 5, size=(K, N)).astype(np.float64)
+    A[5, 0:4] = [np.nan, 1.0, 0.0, 0.0]                  # a kept NaN: the whole row of D is NaN
+    A[9, 0:4] = [3.0e4, 3.0e4, 0.0, 0.0]                 # products around 1e5: beyond fp16, inside bf16 and fp32
+    B[0, :] = 4.0
+    B[1, :] = 4.0
+    A[12, 8:12] = [np.inf, 0.0, 0.0, 2.0]                # an infinite weight: row 12 of D is +-inf by the sign of B's row 8
+    B[8, :] = np.where(np.arange(N) % 2 == 0, 3.0, -2.0)  # (an infinity in B instead would meet the zeros that the dense
+    #                                                      product multiplies and the sparse one skips: 0 * inf differs)
+    Abits, Bbits = synth.to_bits(A, dtype), synth.to_bits(np.ascontiguousarray(B.T), dtype)      # B stored K-major
+    P = oracle.prune(Abits, dtype)
+    V, meta = sp24.sp24_compress(to_gpu(Abits, dtype))
+    D = sp24.sp24_spmm(V, meta, to_gpu(Bbits, dtype), OUT_DT[out])
+    Dd = sp24.sp24_gemm_dense(to_gpu(P, dtype), to_gpu(Bbits, dtype), OUT_DT[out])
+    torch.cuda.synchronize()
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.gemm(P, synth.to_bits(B, dtype), dtype)                                      # fp64
+    want = torch.from_numpy(ref).to(torch.float32).to(OUT_DT[out])   # every finite sum here is exact in fp32
+    for got in (D, Dd):
+        g = got.cpu()
+        assert torch.equal(torch.isnan(g), torch.isnan(want))
+        assert torch.equal(torch.nan_to_num(g.float(), nan=0.0), torch.nan_to_num(want.float(), nan=0.0))
+    assert torch.isnan(D[5]).all() and torch.isinf(D[12]).all() and D[12, 0] > 0 and D[12, 1] < 0
+    if out == "f16":
+        assert torch.isinf(D[9]).all()
