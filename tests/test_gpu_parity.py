@@ -371,3 +371,28 @@ def test_special_values_reach_the_output_as_ieee_conversion_gives_them(dtype, ou
     assert torch.isnan(D[5]).all() and torch.isinf(D[12]).all() and D[12, 0] > 0 and D[12, 1] < 0
     if out == "f16":
         assert torch.isinf(D[9]).all()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [(64, 64, 64), (64, 16, 128), (256, 320, 128)])   # general, skinny and tiled kernels
+def test_removed_positions_take_no_part_in_the_sum(dtype, shape):
+    """Sec. 3.2: the products with removed weights are skipped, not computed -- an infinity in B opposite a removed
+    position leaves the result finite (the dense product of the pruned matrix has 0 * inf = NaN there)."""
+    M, N, K = shape
+    rng = np.random.default_rng(37)
+    A = rng.integers(1, 4, size=(M, K)).astype(np.float64) * rng.choice([-1.0, 1.0], size=(M, K))
+    B = rng.integers(-4, 5, size=(K, N)).astype(np.float64)
+    A[:, 20] = 0.0                                        # three non-zeros beside it in the group: always removed
+    A[:, 21] = 0.0                                        # ... and so is this one: the group keeps columns 22, 23
+    Binf = B.copy()
+    Binf[20, :] = np.inf
+    Binf[21, :] = np.nan
+    Abits = synth.to_bits(A, dtype)
+    for layout in ("canonical", "tiled"):
+        if layout == "tiled" and (M % 32 or K % 64):
+            continue
+        V, meta = sp24.sp24_compress(to_gpu(Abits, dtype), layout=layout)
+        D = sp24.sp24_spmm(V, meta, to_gpu(synth.to_bits(np.ascontiguousarray(Binf.T), dtype), dtype), torch.float32, layout=layout)
+        torch.cuda.synchronize()
+        ref = oracle.gemm(oracle.prune(Abits, dtype), synth.to_bits(B, dtype), dtype)     # the finite B: rows 20, 21 never count
+        assert torch.equal(D.cpu(), torch.from_numpy(ref).to(torch.float32)), (dtype, shape, layout)
