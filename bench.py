@@ -63,6 +63,9 @@ def parse():
     p.add_argument("--sweep", action="store_true",
                    help="add the counterpart of the paper's speedup plot (Sec. 3.2, Fig. 3): M = N = 8192, the inner dimension "
                         "swept, sparse product against the own and the vendor's dense product (bf16 and int8 workloads)")
+    p.add_argument("--few-tiles", action="store_true",
+                   help="add products with few output tiles (32 < N <= 128 at large M and K; small M x N with a long K) in this "
+                        "workload's types: as they are and with the inner dimension split across workgroups")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one 1 GiB device copy, so that a counter profile of this run holds a kernel of known traffic")
     return p.parse_args()
@@ -227,6 +230,62 @@ def sweep(name, steps):
         del As, Bs, VM, Ps, D
         torch.cuda.empty_cache()
     return {"M": M, "N": N, "rows": rows}
+
+
+def few_tiles(name, steps):
+    """Products with few output tiles -- 32 < N <= 128 at large M and K, and small M x N with a long K: the sparse
+    and the dense product as they are, and with the inner dimension split across workgroups (partial products in a
+    workspace, second kernel adds them), beside the vendor library's dense product.  Inputs as in sweep()."""
+    import torch
+    from paper_2104_08378_amd import sp24, synth
+    from util import OUT_DT
+    w = synth.WORKLOADS[name]
+    dt, out_dt = w["dtype"], OUT_DT[w["out"]]
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    tdt = {"i8": torch.int8, "bf16": torch.bfloat16, "f16": torch.float16}[dt]
+
+    def draw(rows, cols, sigma):
+        if dt == "i8":
+            return torch.randint(-127, 128, (rows, cols), dtype=torch.int8, device="cuda", generator=gen)
+        return (torch.randn((rows, cols), dtype=torch.float32, device="cuda", generator=gen) * sigma).to(tdt)
+
+    def timed(fn):
+        for i in range(5):
+            fn(i)
+        batches = []
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(steps):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            batches.append(e0.elapsed_time(e1) / steps)
+        return sorted(batches)[1] * 1e3
+
+    rows = []
+    for M, N, K in ((8192, 64, 8192), (8192, 128, 8192), (512, 512, 8192), (256, 256, 16384), (2048, 256, 4096)):
+        es = 1 if dt == "i8" else 2
+        R = max(2, min(24, int(600e6 // ((M + N) * K * es)) + 1))
+        As = [draw(M, K, 0.02) for _ in range(R)]
+        Bs = [draw(N, K, 1.0) for _ in range(R)]
+        VM = [sp24.sp24_compress(a, layout="tiled") for a in As]
+        Ps = [sp24.sp24_prune(a) for a in As]
+        D = torch.empty((M, N), dtype=out_dt, device="cuda")
+        need = sp24.sp24_splitk_workspace_bytes(M, N, K, tdt)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        t_sp = timed(lambda i: sp24.sp24_spmm(VM[i % R][0], VM[i % R][1], Bs[i % R], out_dt, layout="tiled", out=D))
+        t_sps = timed(lambda i: sp24.sp24_spmm_splitk(VM[i % R][0], VM[i % R][1], Bs[i % R], out_dt, layout="tiled", workspace=ws, out=D))
+        t_dn = timed(lambda i: sp24.sp24_gemm_dense(Ps[i % R], Bs[i % R], out_dt, out=D))
+        t_dns = timed(lambda i: sp24.sp24_gemm_dense_splitk(Ps[i % R], Bs[i % R], out_dt, workspace=ws, out=D))
+        mm = (lambda a, b: torch._int_mm(a, b.t())) if dt == "i8" else (lambda a, b: torch.matmul(a, b.t()))
+        t_v = timed(lambda i: mm(Ps[i % R], Bs[i % R]))
+        rows.append({"M": M, "N": N, "K": K, "workspace_MiB": need / 2 ** 20, "sparse_us": t_sp, "sparse_split_us": t_sps,
+                     "dense_us": t_dn, "dense_split_us": t_dns, "vendor_dense_us": t_v})
+        del As, Bs, VM, Ps, D, ws
+        torch.cuda.empty_cache()
+    return rows
 
 
 def main():
@@ -443,6 +502,8 @@ def main():
     }
     if args.sweep and name in ("ffn_bf16", "square_i8"):
         line["sweep_over_K"] = sweep(name, max(5, args.steps // 2))
+    if args.few_tiles:
+        line["few_tiles"] = few_tiles(name, args.steps)
     if args.extras:
         line["extras"] = extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A, args.steps, conv)
     if args.cpu_seconds > 0:

@@ -238,6 +238,36 @@ sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, in
                             sp24_border bo, void* stream);
 
 /*
+ * Sec. 3.2, Fig. 2: the same two products for shapes with too few output
+ * tiles to occupy the chip (32 < N <= 128 at large M and K, or small M x N
+ * with a long K): the inner dimension is cut into slices, one workgroup per
+ * tile and slice writes a partial product in the accumulator type (fp32 or
+ * int32) to `workspace`, and a second kernel adds the slices in slice order
+ * and converts to `out`.  int8 results equal sp24_spmm's bit for bit;
+ * results of 16-bit inputs differ from it by the order of the fp32 additions
+ * only, and are the same from call to call.
+ * How many slices -- a function of M, N, K and `in` alone -- follows from
+ * sp24_splitk_workspace_bytes(M, N, K, in): the bytes `workspace` must hold
+ * (device, 16-byte aligned, not overlapping any operand; contents before the
+ * call are ignored, contents after it unspecified), or 0 when the shape would
+ * not be split (or is not legal).  With 0 the call is sp24_spmm /
+ * sp24_gemm_dense and `workspace` may be NULL; so it is for operands the
+ * tiled kernels do not take (alignment of B).  Errors as for sp24_spmm, and
+ * SP24_ERR_NULL / SP24_ERR_ALIGN for a missing or misaligned workspace,
+ * SP24_ERR_SHAPE when workspace_bytes is too small or it overlaps an operand.
+ * Calls sharing one workspace must not overlap in time.
+ */
+size_t sp24_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, sp24_dtype in);
+sp24_status sp24_spmm_splitk(const void* V, const void* meta, const void* B, void* D, int64_t M,
+                             int64_t N, int64_t K, int64_t ldb, int64_t ldd, sp24_dtype in,
+                             sp24_dtype out, sp24_border bo, sp24_layout l, void* workspace,
+                             size_t workspace_bytes, void* stream);
+sp24_status sp24_gemm_dense_splitk(const void* A, const void* B, void* D, int64_t M, int64_t N,
+                                   int64_t K, int64_t lda, int64_t ldb, int64_t ldd, sp24_dtype in,
+                                   sp24_dtype out, sp24_border bo, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+
+/*
  * Convolution as a GEMM-like operation whose first argument is the sparse
  * tensor (Sec. 3.2; inner dimension C x R x S, Sec. 4.2), computed as an
  * implicit GEMM: the second operand is never formed in memory.

@@ -115,7 +115,6 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
     return launch_decompress(V, meta, P, M, K, ldp, t, l, static_cast<hipStream_t>(stream));
 }
 
-// x_bytes: extent of the NHWC input when a.conv.on (a.B then points at it), else unused
 sp24_status sp24_prune_transposable(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, sp24_dtype t, void* stream)
 {
     if (!is_input_type(t)) return SP24_ERR_DTYPE;
@@ -226,8 +225,11 @@ sp24_status sp24_retained_magnitude(const void* A, const int32_t* perm, double* 
     return launch_retained_magnitude(A, perm, total, M, K, lda, t, static_cast<hipStream_t>(stream));
 }
 
-static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
+// Argument checks of every product entry point.  *empty: nothing to compute (M or N is 0).
+// x_bytes: extent of the NHWC input when a.conv.on (a.B then points at it), else unused
+static sp24_status mm_validate(const MmArgs& a, size_t x_bytes, bool* empty)
 {
+    *empty = false;
     if (!is_input_type(a.in) || !out_legal(a.in, a.out, a.epi.on != 0)) return SP24_ERR_DTYPE;
     if (a.bo != SP24_B_KMAJOR && a.bo != SP24_B_NMAJOR) return SP24_ERR_LAYOUT;
     if (a.M < 0 || a.N < 0 || !k_legal(a.K, a.in)) return SP24_ERR_SHAPE;
@@ -235,7 +237,10 @@ static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
         if (!is_layout(a.layout)) return SP24_ERR_LAYOUT;
         if (!layout_fits(a.M, a.K, a.layout)) return SP24_ERR_LAYOUT;
     }
-    if (a.M == 0 || a.N == 0) return SP24_OK;
+    if (a.M == 0 || a.N == 0) {
+        *empty = true;
+        return SP24_OK;
+    }
     int es = esize_of(a.in), os = esize_of(a.out);
     sp24_status s;
     if (a.epi.on) {
@@ -267,7 +272,14 @@ static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
     if (a.epi.on && (ranges_overlap(a.D, nd, a.epi.w_scale, (size_t)a.M * 4) ||
                      (a.epi.bias && ranges_overlap(a.D, nd, a.epi.bias, (size_t)a.M * 4))))
         return SP24_ERR_SHAPE;
+    return SP24_OK;
+}
+
+// The kernel for a checked product: streaming (N <= 32), tiled, or general.
+static sp24_status mm_dispatch(const MmArgs& a, hipStream_t st)
+{
     bool handled = false;
+    sp24_status s;
     if (!a.conv.on) {
         s = launch_mm_skinny(a, st, &handled);
         if (handled) return s;
@@ -275,6 +287,106 @@ static sp24_status mm_common(MmArgs& a, hipStream_t st, size_t x_bytes = 0)
     s = launch_mm_tiled(a, st, &handled);
     if (handled) return s;
     return launch_mm_simple(a, st);
+}
+
+static sp24_status mm_common(const MmArgs& a, hipStream_t st, size_t x_bytes = 0)
+{
+    bool empty;
+    const sp24_status s = mm_validate(a, x_bytes, &empty);
+    if (s != SP24_OK || empty) return s;
+    return mm_dispatch(a, st);
+}
+
+// K split across workgroups.  The number of slices is a function of the shape and the input type alone: the one
+// with the least estimated time among 1 .. min(8, compute units / tiles of 128x128, steps / 4), where a workgroup
+// takes 300 ns per 128-byte step (measured on the 128x128 tiles, either type, operands from HBM) and splitting costs 6 us (the second
+// kernel and the shorter pipelines) plus the partial images written and read once at 4 TB/s.  A split must win
+// by a tenth.  1 (no split) for shapes that other kernels take (N <= 32: streaming; M < 64: general).
+struct SplitPlan {
+    int slices, slice_steps;
+    int64_t ldw;            // values per row of a partial image
+    size_t bytes;           // workspace: slices images of M x ldw accumulator values
+};
+static SplitPlan split_plan(int64_t M, int64_t N, int64_t K, sp24_dtype in)
+{
+    SplitPlan p = {1, 0, 0, 0};
+    if (M < 64 || N <= 32) return p;
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    const int64_t steps = K * esize_of(in) / 128;
+    const int64_t ldw = (N + 3) / 4 * 4;
+    int64_t most = 256 / tiles;
+    if (most > steps / 4) most = steps / 4;
+    if (most > 8) most = 8;
+    int64_t best_ns = steps * 300 * 9 / 10, best = 1, best_per = steps;
+    for (int64_t want = 2; want <= most; ++want) {
+        const int64_t per = (steps + want - 1) / want;
+        const int64_t slices = (steps + per - 1) / per;      // no slice is empty
+        const int64_t ns = per * 300 + 6000 + slices * M * ldw / 500;
+        if (ns < best_ns) {
+            best_ns = ns;
+            best = slices;
+            best_per = per;
+        }
+    }
+    if (best <= 1) return p;
+    p.slices = (int)best;
+    p.slice_steps = (int)best_per;
+    p.ldw = ldw;
+    p.bytes = (size_t)p.slices * (size_t)M * (size_t)ldw * 4;
+    return p;
+}
+
+static sp24_status mm_splitk(const MmArgs& a, void* workspace, size_t workspace_bytes, hipStream_t st)
+{
+    bool empty;
+    sp24_status s = mm_validate(a, 0, &empty);
+    if (s != SP24_OK || empty) return s;
+    const SplitPlan plan = split_plan(a.M, a.N, a.K, a.in);
+    if (plan.slices <= 1) return mm_dispatch(a, st);
+    if (!workspace) return SP24_ERR_NULL;
+    if (!aligned16(workspace)) return SP24_ERR_ALIGN;
+    if (workspace_bytes < plan.bytes) return SP24_ERR_SHAPE;
+    const int es = esize_of(a.in);
+    const size_t nd = ((size_t)(a.M - 1) * a.ldd + a.N) * esize_of(a.out);
+    const size_t nb = (a.bo == SP24_B_KMAJOR) ? ((size_t)(a.N - 1) * a.ldb + a.K) * es : ((size_t)(a.K - 1) * a.ldb + a.N) * es;
+    const size_t nA = a.sparse ? sp24_values_bytes(a.M, a.K, a.in) : ((size_t)(a.M - 1) * a.lda + a.K) * es;
+    if (ranges_overlap(workspace, plan.bytes, a.D, nd) || ranges_overlap(workspace, plan.bytes, a.B, nb) ||
+        ranges_overlap(workspace, plan.bytes, a.A, nA))
+        return SP24_ERR_SHAPE;
+    if (a.sparse && ranges_overlap(workspace, plan.bytes, a.meta, sp24_meta_bytes(a.M, a.K, a.in, a.layout))) return SP24_ERR_SHAPE;
+    MmArgs part = a;
+    part.D = workspace;
+    part.ldd = plan.ldw;
+    part.out = (a.in == SP24_I8) ? SP24_I32 : SP24_F32;
+    part.k_slices = plan.slices;
+    part.slice_steps = plan.slice_steps;
+    bool handled = false;
+    s = launch_mm_tiled(part, st, &handled);
+    if (!handled) return mm_dispatch(a, st);             // operands the tiled kernels do not take: not split
+    if (s != SP24_OK) return s;
+    return launch_splitk_reduce(workspace, plan.slices, a.M, a.N, plan.ldw, a.D, a.ldd, a.in == SP24_I8, a.out, st);
+}
+
+size_t sp24_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, sp24_dtype in)
+{
+    if (!is_input_type(in) || M <= 0 || N <= 0 || !k_legal(K, in)) return 0;
+    return split_plan(M, N, K, in).bytes;
+}
+
+sp24_status sp24_spmm_splitk(const void* V, const void* meta, const void* B, void* D, int64_t M, int64_t N, int64_t K, int64_t ldb,
+                             int64_t ldd, sp24_dtype in, sp24_dtype out, sp24_border bo, sp24_layout l, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    MmArgs a{V, meta, B, D, M, N, K, 0, ldb, ldd, in, out, bo, l, true};
+    return mm_splitk(a, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_gemm_dense_splitk(const void* A, const void* B, void* D, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
+                                   int64_t ldd, sp24_dtype in, sp24_dtype out, sp24_border bo, void* workspace,
+                                   size_t workspace_bytes, void* stream)
+{
+    MmArgs a{A, nullptr, B, D, M, N, K, lda, ldb, ldd, in, out, bo, SP24_LAYOUT_CANONICAL, false};
+    return mm_splitk(a, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 sp24_status sp24_spmm(const void* V, const void* meta, const void* B, void* D, int64_t M, int64_t N, int64_t K, int64_t ldb,

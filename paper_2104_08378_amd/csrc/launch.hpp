@@ -46,6 +46,10 @@ struct MmArgs {
     bool sparse;
     ConvGeom conv;         // conv.on: B is the NHWC input X, N = n_img*OH*OW, K = R*S*C, bo / ldb unused
     Epilogue epi;          // epi.on: int8 inputs, scaled / re-quantised output (out = I8, F16, BF16 or F32)
+    // K split across workgroups (tiled kernels only; k_slices > 1): slice s covers slice_steps whole 128-byte steps
+    // from s * slice_steps on and writes its partial product, in the accumulator type, to image s of D
+    // (M rows of ldd values each); out must then be F32 or I32, and conv and epi off.
+    int k_slices, slice_steps;
 };
 
 // General kernel: any M, N; both layouts; both B orders.  One wavefront per 32x32 tile of D.
@@ -56,5 +60,10 @@ sp24_status launch_mm_skinny(const MmArgs& a, hipStream_t st, bool* handled);
 
 // Tiled kernels for large shapes; return false in *handled when the shape does not fit them.
 sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled);
+
+// D [M, N] (type out) = the sum, in slice order, of `slices` partial products (float or int32, M rows of ldw values
+// each, images M * ldw values apart).
+sp24_status launch_splitk_reduce(const void* partial, int slices, int64_t M, int64_t N, int64_t ldw, void* D, int64_t ldd, bool integer,
+                                 sp24_dtype out, hipStream_t st);
 
 } // namespace sp24

@@ -62,6 +62,21 @@ __device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int&
     tn = in_group / gsz;
 }
 
+// The part of the inner dimension that a workgroup covers.  Normally all of it.  With K split across gridDim.y
+// workgroups per tile, slice blockIdx.y takes the whole steps first .. first + nsteps - 1 (the last slice also the
+// partial step) and writes its partial product to image blockIdx.y of D: M rows of ldd accumulator-typed values.
+struct KRange {
+    int first, nsteps, tail;
+};
+__device__ __forceinline__ KRange k_range_of_workgroup(MmArgs& a, int total_steps, int tail)
+{
+    if (a.k_slices <= 1) return {0, total_steps, tail};
+    const int slice = blockIdx.y;
+    const int first = min(slice * a.slice_steps, total_steps);
+    a.D = reinterpret_cast<uint8_t*>(a.D) + (int64_t)slice * a.M * a.ldd * 4;
+    return {first, min(a.slice_steps, total_steps - first), slice == a.k_slices - 1 ? tail : 0};
+}
+
 // Transfer ROWS rows x 128 bytes (row r of the stage = global row min(row0 + r, limit - 1)) into a stage.
 // Offsets of the ROWS/8/NW transfer instructions (8 rows each) of one of NW wavefronts, relative to the first row.
 template <int ROWS, int NW>
@@ -428,15 +443,17 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
     const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, q = lane >> 5;
     const int64_t KB64 = a.K / 64;
-    const int nsteps = (int)(a.K / BK);                    // whole steps
-    const int tail = (int)((a.K * ES) % kRowBytes);        // bytes of K in a further, partial step (0: none)
+    // whole steps, and the bytes of K in a further, partial step (0: none), of this workgroup's share of K
+    const KRange share = k_range_of_workgroup(a, (int)(a.K / BK), (int)((a.K * ES) % kRowBytes));
+    const int nsteps = share.nsteps, tail = share.tail;
     const int64_t rb_total = a.M / 32;
 
     // ---- transfers of this wavefront ----
     const int64_t ldb_bytes = a.ldb * ES;
     // K-major: the tile's first row of B, a step is 128 bytes further; N-major: its first column, a step BK rows further
-    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (NMAJ ? (int64_t)tn * BN * ES : (int64_t)tn * BN * ldb_bytes);
     const int64_t b_step = NMAJ ? (int64_t)BK * ldb_bytes : (int64_t)kRowBytes;
+    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (NMAJ ? (int64_t)tn * BN * ES : (int64_t)tn * BN * ldb_bytes) +
+                           share.first * b_step;
     uint32_t b_off[NJB];
     conv_rows<BN, NW, ES> b_conv;
     if constexpr (CONV) b_conv.init(a.conv, (int64_t)tn * BN, a.N, wave, lane);
@@ -489,6 +506,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
             m_off[x] = lane * 4;
         }
     }
+#pragma unroll
+    for (int x = 0; x < NJV; ++x) v_base[x] += share.first * v_step;
+#pragma unroll
+    for (int x = 0; x < NJM; ++x) m_base[x] += share.first * m_step;
 
     // last, partial step (K not a whole number of steps; never with a convolution): which of this lane's transfers
     // lie past K.  A step holds tail bytes of every B row, tail/2 bytes of values and tail/(8*ES) bytes of codes
@@ -745,13 +766,15 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, q = lane >> 5;
-    const int nsteps = (int)(a.K / BK);                    // whole steps
-    const int tail = (int)((a.K * ES) % kRowBytes);        // bytes of K in a further, partial step (0: none)
+    // whole steps, and the bytes of K in a further, partial step (0: none), of this workgroup's share of K
+    const KRange share = k_range_of_workgroup(a, (int)(a.K / BK), (int)((a.K * ES) % kRowBytes));
+    const int nsteps = share.nsteps, tail = share.tail;
 
     const int64_t lda_bytes = a.lda * ES, ldb_bytes = a.ldb * ES;
-    const uint8_t* a_blk = reinterpret_cast<const uint8_t*>(a.A) + (int64_t)tm * BM * lda_bytes;
-    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (NMAJ ? (int64_t)tn * BN * ES : (int64_t)tn * BN * ldb_bytes);
     const int64_t b_step = NMAJ ? (int64_t)BK * ldb_bytes : (int64_t)kRowBytes;
+    const uint8_t* a_blk = reinterpret_cast<const uint8_t*>(a.A) + (int64_t)tm * BM * lda_bytes + (int64_t)share.first * kRowBytes;
+    const uint8_t* b_blk = reinterpret_cast<const uint8_t*>(a.B) + (NMAJ ? (int64_t)tn * BN * ES : (int64_t)tn * BN * ldb_bytes) +
+                           share.first * b_step;
     uint32_t a_off[NJA], b_off[NJB];
     dma_offsets<BM, NW>((int64_t)tm * BM, a.M, lda_bytes, wave, lane, a_off);
     conv_rows<BN, NW, ES> b_conv;
@@ -942,7 +965,7 @@ static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
 {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WM * WN);
+    const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(a.k_slices > 1 ? a.k_slices : 1)), block(64 * WM * WN);
     if (a.sparse) {
         if (a.conv.on) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 1><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
         else if (a.bo == SP24_B_NMAJOR) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 2><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);

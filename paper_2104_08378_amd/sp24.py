@@ -52,6 +52,10 @@ def lib():
         L.sp24_retained_magnitude.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
         L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
         L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
+        L.sp24_splitk_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.sp24_splitk_workspace_bytes.restype = ctypes.c_size_t
+        L.sp24_spmm_splitk.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp, ctypes.c_size_t, vp]
+        L.sp24_gemm_dense_splitk.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp, ctypes.c_size_t, vp]
         L.sp24_spmm_conv2d.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i32, i32, i32, vp]
         L.sp24_conv2d_dense.argtypes = [vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i64, i32, i32, vp]
         f32 = ctypes.c_float
@@ -63,7 +67,7 @@ def lib():
         L.sp24_status_string.restype = ctypes.c_char_p
         for name in ("sp24_prune_transposable", "sp24_mask_apply", "sp24_compress_masked", "sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
                      "sp24_conv2d_dense", "sp24_spmm_i8_scaled", "sp24_gemm_dense_i8_scaled",
-                     "sp24_spmm_conv2d_i8_scaled", "sp24_conv2d_dense_i8_scaled"):
+                     "sp24_spmm_conv2d_i8_scaled", "sp24_conv2d_dense_i8_scaled", "sp24_spmm_splitk", "sp24_gemm_dense_splitk"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -246,6 +250,48 @@ def sp24_gemm_dense(A, B, out_dtype, b_order="k", out=None):
     D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
     _check(lib().sp24_gemm_dense(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0),
                                  D.stride(0), _DT[A.dtype], _DT[D.dtype], bo, _stream()), "sp24_gemm_dense")
+    return D
+
+
+def sp24_splitk_workspace_bytes(M, N, K, dtype):
+    """Bytes of workspace the split-K products need for this shape (0: they would not split it)."""
+    return lib().sp24_splitk_workspace_bytes(M, N, K, _DT[dtype])
+
+
+def _workspace(workspace, M, N, K, dtype, device):
+    need = sp24_splitk_workspace_bytes(M, N, K, dtype)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+    _dev(workspace, "workspace")
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def sp24_spmm_splitk(V, meta, B, out_dtype, b_order="k", layout="canonical", workspace=None, out=None):
+    """sp24_spmm with the inner dimension split across workgroups (shapes with few output tiles); ``workspace``: a
+    device tensor of at least sp24_splitk_workspace_bytes(...) bytes, allocated here when None."""
+    _dev(V, "V"), _dev(meta, "meta")
+    M, K = V.shape[0], V.shape[1] * 2
+    N, Kb, bo = _b_args(B, b_order)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    ws, ws_bytes = _workspace(workspace, M, N, K, V.dtype, V.device)
+    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_spmm_splitk(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
+                                  _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], ws.data_ptr(), ws_bytes, _stream()), "sp24_spmm_splitk")
+    return D
+
+
+def sp24_gemm_dense_splitk(A, B, out_dtype, b_order="k", workspace=None, out=None):
+    """sp24_gemm_dense with the inner dimension split across workgroups."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    N, Kb, bo = _b_args(B, b_order)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    ws, ws_bytes = _workspace(workspace, M, N, K, A.dtype, A.device)
+    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    _check(lib().sp24_gemm_dense_splitk(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0), D.stride(0),
+                                        _DT[A.dtype], _DT[D.dtype], bo, ws.data_ptr(), ws_bytes, _stream()), "sp24_gemm_dense_splitk")
     return D
 
 

@@ -196,3 +196,42 @@ def test_channel_permutation_validation():
     assert h(A, 0, Pp, 64, 64, 64, 64, sp24.F16, None) == NULL and h(A, perm + 2, Pp, 64, 64, 64, 64, sp24.F16, None) == ALIGN
     assert h(A, perm, A + 128, 64, 64, 64, 64, sp24.F16, None) == SHAPE   # overlapping source and destination
     assert h(A, perm, Pp, 0, 64, 64, 64, sp24.F16, None) == OK
+
+
+def test_split_product_validation_and_workspace_size():
+    """Only paths that launch nothing: failing checks, and M = 0."""
+    L = sp24.lib()
+    w = L.sp24_splitk_workspace_bytes
+    # slices x M x (N rounded up to 4) x 4 bytes; slices: at most 8, workgroups up to one per compute unit, chosen by
+    # the documented estimate (300 ns per step and workgroup; a split costs 6 us + the images at 4 TB/s, twice)
+    assert w(8192, 64, 8192, sp24.BF16) == 4 * 8192 * 64 * 4             # 64 tiles of 128x128, 128 steps
+    assert w(256, 65, 4096, sp24.F16) == 8 * 256 * 68 * 4
+    assert w(512, 512, 8192, sp24.I8) == 6 * 512 * 512 * 4               # 64 steps: six slices of 11, ..., 11, 9
+    assert w(1024, 1024, 1024, sp24.I8) == 0                             # 8 steps: not worth a second kernel
+    assert w(2048, 256, 4096, sp24.I8) == 0                              # the images would cost more than the steps saved
+    assert w(4096, 4096, 1024, sp24.BF16) == 0                           # fills the chip: not split
+    assert w(8192, 16, 8192, sp24.BF16) == 0 and w(32, 256, 8192, sp24.I8) == 0   # other kernels' shapes
+    assert w(256, 256, 24, sp24.F16) == 0 and w(256, 256, 4096, sp24.F32) == 0 and w(-1, 256, 4096, sp24.I8) == 0
+    V, meta, B, D, ws = P, P + 0x1000000, P + 0x2000000, P + 0x3000000, P + 0x4000000
+    f = L.sp24_spmm_splitk
+    need = w(256, 64, 4096, sp24.BF16)
+    assert need > 0
+    base = (256, 64, 4096, 4096, 64, sp24.BF16, sp24.BF16, 0, sp24.CANONICAL)
+    assert f(V, meta, B, D, 256, 64, 4096, 4096, 64, sp24.BF16, sp24.I32, 0, sp24.CANONICAL, ws, need, None) == DTYPE
+    assert f(V, meta, B, D, 256, 64, 4104, 4104, 64, sp24.BF16, sp24.BF16, 0, sp24.CANONICAL, ws, need, None) == SHAPE
+    assert f(V, meta, B, D, *base, 0, need, None) == NULL
+    assert f(V, meta, B, D, *base, ws + 8, need, None) == ALIGN
+    assert f(V, meta, B, D, *base, ws, need - 1, None) == SHAPE
+    assert f(V, meta, B, D, *base, D + 64, need, None) == SHAPE           # workspace over the output
+    assert f(V, meta, B, D, *base, V, need, None) == SHAPE and f(V, meta, B, D, *base, B, need, None) == SHAPE
+    assert f(V, meta, B, D, 0, 64, 4096, 4096, 64, sp24.BF16, sp24.BF16, 0, sp24.CANONICAL, 0, 0, None) == OK
+    g = L.sp24_gemm_dense_splitk
+    A = V
+    dbase = (256, 64, 8192, 8192, 8192, 64, sp24.I8, sp24.I32, 0)
+    need8 = w(256, 64, 8192, sp24.I8)
+    assert need8 > 0
+    assert g(A, B, D, 256, 64, 8192, 8192, 8192, 64, sp24.I8, sp24.F32, 0, ws, need8, None) == DTYPE
+    assert g(A, B, D, 256, 64, 8192, 4096, 8192, 64, sp24.I8, sp24.I32, 0, ws, need8, None) == SHAPE   # lda < K
+    assert g(A, B, D, *dbase, 0, need8, None) == NULL and g(A, B, D, *dbase, ws + 4, need8, None) == ALIGN
+    assert g(A, B, D, *dbase, ws, need8 // 2, None) == SHAPE and g(A, B, D, *dbase, A + 4096, need8, None) == SHAPE
+    assert g(A, B, D, 256, 0, 8192, 8192, 8192, 64, sp24.I8, sp24.I32, 0, 0, 0, None) == OK
