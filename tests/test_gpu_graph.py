@@ -54,3 +54,42 @@ def test_path_replays_from_a_graph(name, dtype, out):
         assert total.item() == pytest.approx(want[5].item(), rel=1e-12)
         if dtype == "i8":
             assert torch.equal(D, Dd)        # sparse and dense products of the same pruned matrix: exact in int32
+
+
+@pytest.mark.parametrize("name,dtype,out", [("ffn_bf16", "bf16", torch.bfloat16), ("square_i8", "i8", torch.int32)])
+def test_split_product_replays_from_a_graph(name, dtype, out):
+    """The two kernels of a split product and their workspace, recorded once; the workspace is scrambled between replays."""
+    M, N, K = 256, 64, 8192
+    sets = [tuple(to_gpu(x, dtype) for x in synth.make(name, M=M, N=N, K=K, seed=50 + i)) for i in range(3)]
+    A, Bt = sets[0][0].clone(), sets[0][1].clone()
+    need = sp24.sp24_splitk_workspace_bytes(M, N, K, A.dtype)
+    assert need > 0
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    V = torch.empty((M, K // 2), dtype=A.dtype, device="cuda")
+    meta = torch.empty((M, K // 8), dtype=torch.uint8, device="cuda")
+    D = torch.empty((M, N), dtype=out, device="cuda")
+
+    def path():
+        sp24.sp24_compress(A, layout="tiled", out=(V, meta))
+        sp24.sp24_spmm_splitk(V, meta, Bt, out, layout="tiled", workspace=ws, out=D)
+
+    path()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            path()
+    torch.cuda.synchronize()
+    for a, b in sets[1:] + sets[:1]:
+        A.copy_(a)
+        Bt.copy_(b)
+        path()
+        torch.cuda.synchronize()
+        want = D.clone()
+        D.zero_()
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(D.view(torch.uint8), want.view(torch.uint8))
