@@ -233,7 +233,7 @@ def sweep(name, steps):
 
 
 def few_tiles(name, steps):
-    """Products with few output tiles -- 32 < N <= 128 at large M and K, and small M x N with a long K: the sparse
+    """Products with few output tiles -- 32 < N <= 128 at large M and K, small M x N with a long K, N <= 32 with few rows: the sparse
     and the dense product as they are, and with the inner dimension split across workgroups (partial products in a
     workspace, second kernel adds them), beside the vendor library's dense product.  Inputs as in sweep()."""
     import torch
@@ -265,7 +265,8 @@ def few_tiles(name, steps):
         return sorted(batches)[1] * 1e3
 
     rows = []
-    for M, N, K in ((8192, 64, 8192), (8192, 128, 8192), (512, 512, 8192), (256, 256, 16384), (2048, 256, 4096)):
+    for M, N, K in ((8192, 64, 8192), (8192, 128, 8192), (512, 512, 8192), (256, 256, 16384), (2048, 256, 4096),
+                    (4096, 16, 16384), (512, 32, 16384)):
         es = 1 if dt == "i8" else 2
         R = max(2, min(24, int(600e6 // ((M + N) * K * es)) + 1))
         As = [draw(M, K, 0.02) for _ in range(R)]

@@ -239,11 +239,11 @@ sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, in
 
 /*
  * Sec. 3.2, Fig. 2: the same two products for shapes with too few output
- * tiles to occupy the chip (32 < N <= 128 at large M and K, or small M x N
- * with a long K): the inner dimension is cut into slices, one workgroup per
- * tile and slice writes a partial product in the accumulator type (fp32 or
- * int32) to `workspace`, and a second kernel adds the slices in slice order
- * and converts to `out`.  int8 results equal sp24_spmm's bit for bit;
+ * tiles to occupy the chip (32 < N <= 128 at large M and K, a small M x N
+ * with a long K, or N <= 32 with few rows and a long K): the inner dimension
+ * is cut into slices, one workgroup per tile and slice writes a partial
+ * product in the accumulator type (fp32 or int32) to `workspace`, and a
+ * second kernel adds the slices in slice order and converts to `out`.  int8 results equal sp24_spmm's bit for bit;
  * results of 16-bit inputs differ from it by the order of the fp32 additions
  * only, and are the same from call to call.
  * How many slices -- a function of M, N, K and `in` alone -- follows from
@@ -252,7 +252,8 @@ sp24_status sp24_gemm_dense(const void* A, const void* B, void* D, int64_t M, in
  * call are ignored, contents after it unspecified), or 0 when the shape would
  * not be split (or is not legal).  With 0 the call is sp24_spmm /
  * sp24_gemm_dense and `workspace` may be NULL; so it is for operands the
- * tiled kernels do not take (alignment of B).  Errors as for sp24_spmm, and
+ * tiled and streaming kernels do not take (alignment of B; N <= 32 with an
+ * N-major B, or with the canonical layout and K % 64 != 0).  Errors as for sp24_spmm, and
  * SP24_ERR_NULL / SP24_ERR_ALIGN for a missing or misaligned workspace,
  * SP24_ERR_SHAPE when workspace_bytes is too small or it overlaps an operand.
  * Calls sharing one workspace must not overlap in time.

@@ -298,30 +298,47 @@ static sp24_status mm_common(const MmArgs& a, hipStream_t st, size_t x_bytes = 0
 }
 
 // K split across workgroups.  The number of slices is a function of the shape and the input type alone: the one
-// with the least estimated time among 1 .. min(8, compute units / tiles of 128x128, steps / 4), where a workgroup
-// takes 300 ns per 128-byte step (measured on the 128x128 tiles, either type, operands from HBM) and splitting costs 6 us (the second
-// kernel and the shorter pipelines) plus the partial images written and read once at 4 TB/s.  A split must win
-// by a tenth.  1 (no split) for shapes that other kernels take (N <= 32: streaming; M < 64: general).
+// with the least estimated time among the candidates, where splitting costs 6 us (8 us for the streaming kernel:
+// the second kernel and the shorter pipelines) plus the partial images written and read once at 4 TB/s, and must
+// win by a tenth.
+//  * N > 32, M >= 64 (tiled kernels, 128x128 tiles): 1 .. min(8, compute units / tiles, steps / 4) slices of whole
+//    128-byte steps; a workgroup takes 300 ns per step (measured, either type, operands from HBM).
+//  * N <= 32, M >= 32 (streaming kernel, one workgroup per 32 rows): 1 .. min(8, compute units / row blocks,
+//    tiles / 32) slices of whole 64-column tiles; a workgroup takes 130 ns (16-bit) or 80 ns (8-bit) per tile of
+//    its 32 rows (measured at K = 16384: latency-bound, the same whether 16 or 128 workgroups run).
+//  * M < 32: not split (the general kernel).
 struct SplitPlan {
-    int slices, slice_steps;
-    int64_t ldw;            // values per row of a partial image
-    size_t bytes;           // workspace: slices images of M x ldw accumulator values
+    int slices, slice_steps;    // slice_steps in the kernel's own unit: 128-byte steps, or 64-column tiles
+    bool streaming;             // the N <= 32 kernel
+    int64_t ldw;                // values per row of a partial image
+    size_t bytes;               // workspace: slices images of M x ldw accumulator values
 };
 static SplitPlan split_plan(int64_t M, int64_t N, int64_t K, sp24_dtype in)
 {
-    SplitPlan p = {1, 0, 0, 0};
-    if (M < 64 || N <= 32) return p;
-    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    const int64_t steps = K * esize_of(in) / 128;
+    SplitPlan p = {1, 0, N <= 32, 0, 0};
+    if (M < 32 || (N > 32 && M < 64)) return p;
+    const int es = esize_of(in);
     const int64_t ldw = (N + 3) / 4 * 4;
-    int64_t most = 256 / tiles;
-    if (most > steps / 4) most = steps / 4;
+    int64_t units, most, unit_ns, fixed_ns;                  // K in the kernel's units; slices at most; time per unit; cost of splitting
+    if (p.streaming) {
+        units = (K + 63) / 64;
+        most = 256 / ((M + 31) / 32);
+        if (most > units / 32) most = units / 32;
+        unit_ns = es == 2 ? 130 : 80;
+        fixed_ns = 8000;
+    } else {
+        units = K * es / 128;
+        most = 256 / (((M + 127) / 128) * ((N + 127) / 128));
+        if (most > units / 4) most = units / 4;
+        unit_ns = 300;
+        fixed_ns = 6000;
+    }
     if (most > 8) most = 8;
-    int64_t best_ns = steps * 300 * 9 / 10, best = 1, best_per = steps;
+    int64_t best_ns = units * unit_ns * 9 / 10, best = 1, best_per = units;
     for (int64_t want = 2; want <= most; ++want) {
-        const int64_t per = (steps + want - 1) / want;
-        const int64_t slices = (steps + per - 1) / per;      // no slice is empty
-        const int64_t ns = per * 300 + 6000 + slices * M * ldw / 500;
+        const int64_t per = (units + want - 1) / want;
+        const int64_t slices = (units + per - 1) / per;      // no slice is empty
+        const int64_t ns = per * unit_ns + fixed_ns + slices * M * ldw / 500;
         if (ns < best_ns) {
             best_ns = ns;
             best = slices;
@@ -361,8 +378,8 @@ static sp24_status mm_splitk(const MmArgs& a, void* workspace, size_t workspace_
     part.k_slices = plan.slices;
     part.slice_steps = plan.slice_steps;
     bool handled = false;
-    s = launch_mm_tiled(part, st, &handled);
-    if (!handled) return mm_dispatch(a, st);             // operands the tiled kernels do not take: not split
+    s = plan.streaming ? launch_mm_skinny(part, st, &handled) : launch_mm_tiled(part, st, &handled);
+    if (!handled) return mm_dispatch(a, st);             // operands that kernel does not take: not split
     if (s != SP24_OK) return s;
     return launch_splitk_reduce(workspace, plan.slices, a.M, a.N, plan.ldw, a.D, a.ldd, a.in == SP24_I8, a.out, st);
 }

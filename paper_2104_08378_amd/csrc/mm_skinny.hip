@@ -40,21 +40,30 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, q = lane >> 5;
     const int64_t rb = blockIdx.x;
-    const int64_t KB64 = (a.K + 63) / 64;
-    const int64_t Kbytes = a.K * ES;
-    const int64_t k_start = SPARSE ? 0 : (rb * 37) % KB64;   // this workgroup's first tile (dense only)
+    // This workgroup's share of the inner dimension, in 64-column tiles: all of them, or (K split across gridDim.y
+    // workgroups per row block) slice blockIdx.y, whose partial product goes to image blockIdx.y of D.  The operand
+    // pointers below start at the share's first tile, and tile numbers and byte offsets count from there.
+    int64_t kb_first = 0, KB64 = (a.K + 63) / 64;
+    if (a.k_slices > 1) {
+        kb_first = min((int64_t)blockIdx.y * a.slice_steps, KB64);
+        KB64 = min((int64_t)a.slice_steps, KB64 - kb_first);
+        a.D = reinterpret_cast<uint8_t*>(a.D) + (int64_t)blockIdx.y * a.M * a.ldd * 4;
+    }
+    const int64_t Kbytes = a.K * ES - kb_first * TB;
+    const int64_t k_start = (SPARSE || KB64 == 0) ? 0 : (rb * 37) % KB64;   // this workgroup's first tile (dense only)
 
     const bool n_ok = r < a.N;
-    const uint8_t* brow = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)(n_ok ? r : 0) * a.ldb * ES;
+    const uint8_t* brow = reinterpret_cast<const uint8_t*>(a.B) + (int64_t)(n_ok ? r : 0) * a.ldb * ES + kb_first * TB;
     int64_t m = rb * 32 + r;
     if (m >= a.M) m = a.M - 1;                       // ragged M (dense only): rows past the end are never stored
-    const uint8_t* arow = reinterpret_cast<const uint8_t*>(a.A) + m * a.lda * ES;
+    const uint8_t* arow = reinterpret_cast<const uint8_t*>(a.A) + m * a.lda * ES + kb_first * TB;
     const uint4v* Vp = reinterpret_cast<const uint4v*>(a.A);
     const uint32_t* Mp = reinterpret_cast<const uint32_t*>(a.meta);
+    const int64_t tile_first = rb * (a.K / 64) + kb_first;   // tiled layout: this row block's first tile of the share
     // canonical layout: lane (m % 32, h) reads its slot's 16 bytes of values and 4 bytes of codes from row m
     const bool canonical = SPARSE && a.layout == SP24_LAYOUT_CANONICAL;
-    const uint8_t* vrow = reinterpret_cast<const uint8_t*>(a.A) + m * (a.K / 2 * ES) + (ES == 1 ? 16 : 32) * q;
-    const uint8_t* mrow = reinterpret_cast<const uint8_t*>(a.meta) + m * (a.K / 8) + 4 * q;
+    const uint8_t* vrow = reinterpret_cast<const uint8_t*>(a.A) + m * (a.K / 2 * ES) + (ES == 1 ? 16 : 32) * q + kb_first * 32 * ES;
+    const uint8_t* mrow = reinterpret_cast<const uint8_t*>(a.meta) + m * (a.K / 8) + 4 * q + kb_first * 8;
 
     acc_t acc = {};
     const uint4v zero4 = {0u, 0u, 0u, 0u};
@@ -72,7 +81,7 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
                 if (kb >= KB64) kb -= KB64;
             }
             if constexpr (SPARSE) {
-                const int64_t tile = rb * (a.K / 64) + kb;
+                const int64_t tile = tile_first + kb;
                 if (canonical) {
                     codes[u] = ok ? *reinterpret_cast<const uint32_t*>(mrow + kb * 8) : 0u;
                     if constexpr (DT == SP24_I8) va[u][0] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 32) : zero4;
@@ -156,7 +165,7 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
 template <int DT, int OUT>
 static sp24_status run_skinny(const MmArgs& a, hipStream_t st)
 {
-    const dim3 grid((unsigned)((a.M + 31) / 32)), block(64 * kSkinnyWaves);
+    const dim3 grid((unsigned)((a.M + 31) / 32), (unsigned)(a.k_slices > 1 ? a.k_slices : 1)), block(64 * kSkinnyWaves);
     if (a.sparse) k_mm_skinny<DT, OUT, true><<<grid, block, 0, st>>>(a);
     else k_mm_skinny<DT, OUT, false><<<grid, block, 0, st>>>(a);
     return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;

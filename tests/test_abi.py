@@ -210,7 +210,13 @@ def test_split_product_validation_and_workspace_size():
     assert w(1024, 1024, 1024, sp24.I8) == 0                             # 8 steps: not worth a second kernel
     assert w(2048, 256, 4096, sp24.I8) == 0                              # the images would cost more than the steps saved
     assert w(4096, 4096, 1024, sp24.BF16) == 0                           # fills the chip: not split
-    assert w(8192, 16, 8192, sp24.BF16) == 0 and w(32, 256, 8192, sp24.I8) == 0   # other kernels' shapes
+    assert w(32, 256, 8192, sp24.I8) == 0                                # M < 64 at N > 32: the general kernel's shape
+    # N <= 32 (one workgroup per 32 rows): slices of whole 64-column tiles, 130 / 80 ns per tile, a split costs 8 us
+    assert w(8192, 16, 8192, sp24.BF16) == 0                             # 256 row blocks fill the chip
+    assert w(4096, 16, 16384, sp24.BF16) == 2 * 4096 * 16 * 4
+    assert w(512, 32, 16384, sp24.I8) == 8 * 512 * 32 * 4
+    assert w(96, 7, 8192, sp24.F16) == 4 * 96 * 8 * 4                    # at least 32 tiles per slice; rows padded to 8 values
+    assert w(4096, 16, 4096, sp24.BF16) == 0 and w(16, 16, 16384, sp24.I8) == 0
     assert w(256, 256, 24, sp24.F16) == 0 and w(256, 256, 4096, sp24.F32) == 0 and w(-1, 256, 4096, sp24.I8) == 0
     V, meta, B, D, ws = P, P + 0x1000000, P + 0x2000000, P + 0x3000000, P + 0x4000000
     f = L.sp24_spmm_splitk

@@ -27,6 +27,12 @@ CASES = [
     ("f16", "f16", 128, 65, 4096, "canonical", "k"),    # odd N: rows of the partial images padded to 68
     ("bf16", "bf16", 4096, 64, 8192, "tiled", "k"),     # 32 tiles, 128 steps
     ("bf16", "bf16", 320, 40, 4096, "canonical", "k"),  # ragged M and N
+    # N <= 32: the streaming kernel, slices of whole 64-column tiles
+    ("bf16", "bf16", 1024, 16, 8192, "tiled", "k"),     # 32 row blocks, 4 slices
+    ("i8", "i32", 512, 32, 16384, "canonical", "k"),    # 16 row blocks, 8 slices
+    ("f16", "f32", 96, 7, 8192, "canonical", "k"),      # ragged N; 3 row blocks
+    ("i8", "i32", 2048, 1, 12352, "tiled", "k"),        # N = 1; 193 tiles: uneven slices
+    ("f16", "f16", 128, 16, 8208, "canonical", "k"),    # K % 64 = 16: the dense product has a partial last tile, the sparse one is not split
 ]
 
 
