@@ -302,7 +302,8 @@ static sp24_status mm_common(const MmArgs& a, hipStream_t st, size_t x_bytes = 0
 // the second kernel and the shorter pipelines) plus the partial images written and read once at 4 TB/s, and must
 // win by a tenth.
 //  * N > 32, M >= 64 (tiled kernels, 128x128 tiles): 1 .. min(8, compute units / tiles, steps / 4) slices of whole
-//    128-byte steps; a workgroup takes 300 ns per step (measured, either type, operands from HBM).
+//    128-byte steps; a launch takes 5 us plus 400 ns per step of its workgroups (fitted to measurements of both
+//    types at 16 - 128 steps, operands from HBM).
 //  * N <= 32, M >= 32 (streaming kernel, one workgroup per 32 rows): 1 .. min(8, compute units / row blocks,
 //    tiles / 32) slices of whole 64-column tiles; a workgroup takes 130 ns (16-bit) or 80 ns (8-bit) per tile of
 //    its 32 rows (measured at K = 16384: latency-bound, the same whether 16 or 128 workgroups run).
@@ -319,26 +320,28 @@ static SplitPlan split_plan(int64_t M, int64_t N, int64_t K, sp24_dtype in)
     if (M < 32 || (N > 32 && M < 64)) return p;
     const int es = esize_of(in);
     const int64_t ldw = (N + 3) / 4 * 4;
-    int64_t units, most, unit_ns, fixed_ns;                  // K in the kernel's units; slices at most; time per unit; cost of splitting
+    int64_t units, most, unit_ns, base_ns, fixed_ns;         // K in the kernel's units; slices at most; time per unit; per launch; cost of splitting
     if (p.streaming) {
         units = (K + 63) / 64;
         most = 256 / ((M + 31) / 32);
         if (most > units / 32) most = units / 32;
         unit_ns = es == 2 ? 130 : 80;
+        base_ns = 0;
         fixed_ns = 8000;
     } else {
         units = K * es / 128;
         most = 256 / (((M + 127) / 128) * ((N + 127) / 128));
         if (most > units / 4) most = units / 4;
-        unit_ns = 300;
+        unit_ns = 400;
+        base_ns = 5000;
         fixed_ns = 6000;
     }
     if (most > 8) most = 8;
-    int64_t best_ns = units * unit_ns * 9 / 10, best = 1, best_per = units;
+    int64_t best_ns = (base_ns + units * unit_ns) * 9 / 10, best = 1, best_per = units;
     for (int64_t want = 2; want <= most; ++want) {
         const int64_t per = (units + want - 1) / want;
         const int64_t slices = (units + per - 1) / per;      // no slice is empty
-        const int64_t ns = per * unit_ns + fixed_ns + slices * M * ldw / 500;
+        const int64_t ns = base_ns + per * unit_ns + fixed_ns + slices * M * ldw / 500;
         if (ns < best_ns) {
             best_ns = ns;
             best = slices;

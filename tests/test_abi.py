@@ -203,12 +203,13 @@ def test_split_product_validation_and_workspace_size():
     L = sp24.lib()
     w = L.sp24_splitk_workspace_bytes
     # slices x M x (N rounded up to 4) x 4 bytes; slices: at most 8, workgroups up to one per compute unit, chosen by
-    # the documented estimate (300 ns per step and workgroup; a split costs 6 us + the images at 4 TB/s, twice)
+    # the documented estimate (5 us + 400 ns per step; a split costs 6 us + the images at 4 TB/s, twice)
     assert w(8192, 64, 8192, sp24.BF16) == 4 * 8192 * 64 * 4             # 64 tiles of 128x128, 128 steps
     assert w(256, 65, 4096, sp24.F16) == 8 * 256 * 68 * 4
-    assert w(512, 512, 8192, sp24.I8) == 6 * 512 * 512 * 4               # 64 steps: six slices of 11, ..., 11, 9
+    assert w(512, 512, 8192, sp24.I8) == 8 * 512 * 512 * 4               # 64 steps: eight slices of 8
     assert w(1024, 1024, 1024, sp24.I8) == 0                             # 8 steps: not worth a second kernel
     assert w(2048, 256, 4096, sp24.I8) == 0                              # the images would cost more than the steps saved
+    assert w(8192, 128, 8192, sp24.I8) == 4 * 8192 * 128 * 4
     assert w(4096, 4096, 1024, sp24.BF16) == 0                           # fills the chip: not split
     assert w(32, 256, 8192, sp24.I8) == 0                                # M < 64 at N > 32: the general kernel's shape
     # N <= 32 (one workgroup per 32 rows): slices of whole 64-column tiles, 130 / 80 ns per tile, a split costs 8 us
