@@ -198,22 +198,47 @@ __global__ __launch_bounds__(256) void k_prune_transposable(const uint8_t* __res
 #pragma unroll
         for (int p = 0; p < 6; ++p) r[i][p] = mag[c0[p]] + mag[c1[p]];
     }
-    int best = 0;
-    sum_t best_sum = (sum_t)-1;
-#pragma unroll
-    for (int e = 0; e < 90; ++e) {
-        const sum_t sum = ((r[0][table.pair[e][0]] + r[1][table.pair[e][1]]) + r[2][table.pair[e][2]]) + r[3][table.pair[e][3]];
-        if (sum > best_sum) {
-            best_sum = sum;
-            best = e;
-        }
-    }
-    // pair indices of the winner, 3 bits per row, looked up without indexing memory by a lane-dependent value
+    // pair indices of the winner, 3 bits per row
     uint32_t win = 0;
+    if constexpr (DT == SP24_I8) {
+        // Integer sums (at most 8 * 128) do not depend on the order of addition, so the rows are added in two halves
+        // shared between patterns, and sum and pattern travel in one word: the sum above 12 bits that hold 4095 minus
+        // the pattern's row pairs in visiting order (row 0's pair in the top three bits).  The largest word is the
+        // largest sum and, among equal sums, the pattern visited first.
+        int top[6][6], bottom[6][6];
 #pragma unroll
-    for (int e = 0; e < 90; ++e) {
-        const uint32_t packed = table.pair[e][0] | (table.pair[e][1] << 3) | (table.pair[e][2] << 6) | (table.pair[e][3] << 9);
-        win = (best == e) ? packed : win;
+        for (int p = 0; p < 6; ++p)
+#pragma unroll
+            for (int t = 0; t < 6; ++t) {
+                top[p][t] = (r[0][p] + r[1][t]) << 12;
+                bottom[p][t] = (r[2][p] + r[3][t]) << 12;
+            }
+        uint32_t best_word = 0;
+#pragma unroll
+        for (int e = 0; e < 90; ++e) {
+            const uint32_t visit = (table.pair[e][0] << 9) | (table.pair[e][1] << 6) | (table.pair[e][2] << 3) | table.pair[e][3];
+            const uint32_t word = (uint32_t)(top[table.pair[e][0]][table.pair[e][1]] + bottom[table.pair[e][2]][table.pair[e][3]]) + (4095u - visit);
+            best_word = max(best_word, word);
+        }
+        const uint32_t visit = 4095u - (best_word & 4095u);
+        win = (visit >> 9) | (((visit >> 6) & 7u) << 3) | (((visit >> 3) & 7u) << 6) | ((visit & 7u) << 9);
+    } else {
+        int best = 0;
+        sum_t best_sum = (sum_t)-1;
+#pragma unroll
+        for (int e = 0; e < 90; ++e) {
+            const sum_t sum = ((r[0][table.pair[e][0]] + r[1][table.pair[e][1]]) + r[2][table.pair[e][2]]) + r[3][table.pair[e][3]];
+            if (sum > best_sum) {
+                best_sum = sum;
+                best = e;
+            }
+        }
+        // looked up without indexing memory by a lane-dependent value
+#pragma unroll
+        for (int e = 0; e < 90; ++e) {
+            const uint32_t packed = table.pair[e][0] | (table.pair[e][1] << 3) | (table.pair[e][2] << 6) | (table.pair[e][3] << 9);
+            win = (best == e) ? packed : win;
+        }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {

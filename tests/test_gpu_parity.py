@@ -145,6 +145,20 @@ def test_transposable_pruning_bit_exact(dtype):
     assert torch.equal(sp24.sp24_prune(Pt).view(torch.uint8), Pt.view(torch.uint8))
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_transposable_pruning_breaks_ties_as_the_search_order_says(dtype):
+    """Blocks made of very few distinct magnitudes: most of the 90 patterns tie, and the first one visited must win."""
+    rng = np.random.default_rng(91)
+    M, K = 64, 256
+    if dtype == "i8":
+        A = rng.choice(np.array([-1, 0, 1, 1, -128], dtype=np.int8), size=(M, K))
+    else:
+        one = 0x3C00 if dtype == "f16" else 0x3F80
+        A = rng.choice(np.array([0x0000, one, one | 0x8000, 0x8000], dtype=np.uint16), size=(M, K))
+    P = sp24.sp24_prune_transposable(to_gpu(A, dtype))
+    assert np.array_equal(to_bits(P), oracle.prune_transposable(A, dtype))
+
+
 MM_CASES = [
     # dtype, out, M, N, K
     ("f16", "f32", 32, 32, 64),
