@@ -159,6 +159,8 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
                             lambda: oracle.permute_columns(sample, perm_h, dt)),
         "retained_magnitude": (lambda i: sp24.sp24_retained_magnitude(As[i % R], perm_d, out=total), 1.0 * M * K * es + 4.0 * K,
                                lambda: oracle.retained_magnitude(sample, dt, perm=perm_h)),
+        "retained_magnitude_given_order": (lambda i: sp24.sp24_retained_magnitude(As[i % R], out=total), 1.0 * M * K * es,
+                                           lambda: oracle.retained_magnitude(sample, dt)),
         "permute_rows": (lambda i: sp24.sp24_permute_rows(As[i % R], rperm_d, out=Pm), 2.0 * M * K * es + 4.0 * M,
                          lambda: oracle.permute_rows(sample, np.random.default_rng(1).permutation(rows).astype(np.int32), dt)),
     }

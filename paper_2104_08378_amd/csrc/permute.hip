@@ -158,6 +158,17 @@ __global__ __launch_bounds__(64 * kPermWaves) void k_permute_columns(const uint8
 // magnitudes the selection rule of sp24_prune keeps does not change the sum, so the two largest keys (the
 // magnitudes as unsigned integers, every NaN one key above infinity) are found with a min/max network and turned
 // into exact doubles; a NaN among them makes the sum NaN.
+template <int DT>
+__device__ __forceinline__ double kept_of_keys(const uint32_t (&key)[4])
+{
+    const uint32_t hi01 = max(key[0], key[1]), lo01 = min(key[0], key[1]);
+    const uint32_t hi23 = max(key[2], key[3]), lo23 = min(key[2], key[3]);
+    const uint32_t first = max(hi01, hi23), second = max(min(hi01, hi23), max(lo01, lo23));
+    if constexpr (DT == SP24_I8) return (double)(first + second);
+    else if constexpr (DT == SP24_F16)
+        return (double)(float)__builtin_bit_cast(_Float16, (uint16_t)first) + (double)(float)__builtin_bit_cast(_Float16, (uint16_t)second);
+    else return (double)__uint_as_float(first << 16) + (double)__uint_as_float(second << 16);
+}
 template <int DT, typename ROW, typename ORDER>
 __device__ __forceinline__ double kept_of_group(ROW row, const ORDER& col, int64_t g)
 {
@@ -169,13 +180,31 @@ __device__ __forceinline__ double kept_of_group(ROW row, const ORDER& col, int64
         if constexpr (DT == SP24_I8) key[i] = mag_key8(bits);
         else key[i] = mag_key16<DT>(bits);
     }
-    const uint32_t hi01 = max(key[0], key[1]), lo01 = min(key[0], key[1]);
-    const uint32_t hi23 = max(key[2], key[3]), lo23 = min(key[2], key[3]);
-    const uint32_t first = max(hi01, hi23), second = max(min(hi01, hi23), max(lo01, lo23));
-    if constexpr (DT == SP24_I8) return (double)(first + second);
-    else if constexpr (DT == SP24_F16)
-        return (double)(float)__builtin_bit_cast(_Float16, (uint16_t)first) + (double)(float)__builtin_bit_cast(_Float16, (uint16_t)second);
-    else return (double)__uint_as_float(first << 16) + (double)__uint_as_float(second << 16);
+    return kept_of_keys<DT>(key);
+}
+// The same for the groups of 16 bytes of a row in its given order: four groups of 8-bit, two of 16-bit elements.
+template <int DT>
+__device__ __forceinline__ double kept_of_chunk(const uint4v& w)
+{
+    double sum = 0.0;
+    if constexpr (DT == SP24_I8) {
+        uint32_t total = 0;                                 // integers: one conversion per chunk
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t k0 = mag_key8(w[g] & 0xFFu), k1 = mag_key8((w[g] >> 8) & 0xFFu), k2 = mag_key8((w[g] >> 16) & 0xFFu), k3 = mag_key8(w[g] >> 24);
+            const uint32_t hi01 = max(k0, k1), lo01 = min(k0, k1), hi23 = max(k2, k3), lo23 = min(k2, k3);
+            total += max(hi01, hi23) + max(min(hi01, hi23), max(lo01, lo23));
+        }
+        sum = (double)total;
+    } else {
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const uint32_t key[4] = {mag_key16<DT>(w[2 * g] & 0xFFFFu), mag_key16<DT>(w[2 * g] >> 16), mag_key16<DT>(w[2 * g + 1] & 0xFFFFu),
+                                     mag_key16<DT>(w[2 * g + 1] >> 16)};
+            sum += kept_of_keys<DT>(key);
+        }
+    }
+    return sum;
 }
 
 __global__ void k_zero_double(double* out) { *out = 0.0; }
@@ -196,7 +225,24 @@ __global__ __launch_bounds__(64 * kPermWaves) void k_retained_magnitude(const ui
     const lds_row region = (lds_row)lds + (2 * K + wave * K * ES);
     double sum = 0.0;
     const int64_t first = (int64_t)blockIdx.x * kPermWaves + wave, stride = (int64_t)gridDim.x * kPermWaves;
-    if (staged) {
+    if (perm == nullptr) {
+        // the given order: every group lies in place, nothing to stage or gather; eight loads in flight per lane
+        const int64_t chunks = K * ES / 16;
+        for (int64_t row = first; row < M; row += stride) {
+            const uint4v* src = reinterpret_cast<const uint4v*>(A + row * lda * ES);
+            for (int64_t c0 = 0; c0 < chunks; c0 += 8 * 64) {
+                uint4v part[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int64_t c = c0 + 64 * j + lane;
+                    if (c < chunks) part[j] = src[c];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (c0 + 64 * j + lane < chunks) sum += kept_of_chunk<DT>(part[j]);
+            }
+        }
+    } else if (staged) {
         RowInFlight next;
         if (first < M) next.load(A + first * lda * ES, K * ES, lane);
         stage_order(perm, K, in_lds.order);
@@ -312,7 +358,7 @@ sp24_status launch_retained_magnitude(const void* A, const void* perm, double* o
         const dim3 grid(grid_for_rows(M)), block(64 * kPermWaves);
         const uint8_t* a = static_cast<const uint8_t*>(A);
         const int32_t* p = static_cast<const int32_t*>(perm);
-        const size_t lds = staged_lds_bytes(K, esize_of(t));
+        const size_t lds = p ? staged_lds_bytes(K, esize_of(t)) : 0;   // the given order needs no staging
         if (t == SP24_F16) k_retained_magnitude<SP24_F16><<<grid, block, lds, st>>>(a, p, out, M, K, lda);
         else if (t == SP24_BF16) k_retained_magnitude<SP24_BF16><<<grid, block, lds, st>>>(a, p, out, M, K, lda);
         else k_retained_magnitude<SP24_I8><<<grid, block, lds, st>>>(a, p, out, M, K, lda);
