@@ -223,21 +223,21 @@ __global__ __launch_bounds__(256) void k_prune_transposable(const uint8_t* __res
         const uint32_t visit = 4095u - (best_word & 4095u);
         win = (visit >> 9) | (((visit >> 6) & 7u) << 3) | (((visit >> 3) & 7u) << 6) | ((visit & 7u) << 9);
     } else {
-        int best = 0;
+        // sums in the stated order; r0 + r1 is shared by the patterns that agree in their first two rows, and the
+        // winner's row pairs (constants of the unrolled loop) are carried along instead of its number
+        sum_t top[6][6];
+#pragma unroll
+        for (int p = 0; p < 6; ++p)
+#pragma unroll
+            for (int t = 0; t < 6; ++t) top[p][t] = r[0][p] + r[1][t];
         sum_t best_sum = (sum_t)-1;
 #pragma unroll
         for (int e = 0; e < 90; ++e) {
-            const sum_t sum = ((r[0][table.pair[e][0]] + r[1][table.pair[e][1]]) + r[2][table.pair[e][2]]) + r[3][table.pair[e][3]];
-            if (sum > best_sum) {
-                best_sum = sum;
-                best = e;
-            }
-        }
-        // looked up without indexing memory by a lane-dependent value
-#pragma unroll
-        for (int e = 0; e < 90; ++e) {
+            const sum_t sum = (top[table.pair[e][0]][table.pair[e][1]] + r[2][table.pair[e][2]]) + r[3][table.pair[e][3]];
             const uint32_t packed = table.pair[e][0] | (table.pair[e][1] << 3) | (table.pair[e][2] << 6) | (table.pair[e][3] << 9);
-            win = (best == e) ? packed : win;
+            const bool better = sum > best_sum;
+            best_sum = better ? sum : best_sum;
+            win = better ? packed : win;
         }
     }
 #pragma unroll
