@@ -109,3 +109,27 @@ def test_shapes_that_are_not_split_take_the_unsplit_path(dtype, out, M, N, K):
     U = sp24.sp24_spmm(V, meta, Bd, OUT_DT[out])
     torch.cuda.synchronize()
     assert torch.equal(D.view(torch.uint8), U.view(torch.uint8))
+
+
+@pytest.mark.parametrize("dtype,out,M,N,K", [("bf16", "bf16", 8192, 64, 8192), ("i8", "i32", 8192, 128, 8192), ("bf16", "bf16", 512, 32, 16384)])
+def test_split_products_at_the_sizes_bench_times(dtype, out, M, N, K):
+    """The shapes of bench.py --few-tiles, tiled layout, K-major B: sampled rows x columns that the oracle computes one by one."""
+    assert sp24.sp24_splitk_workspace_bytes(M, N, K, IN_DT[dtype]) > 0
+    A, Bt = synth.make(NAME_OF[dtype], M=M, N=N, K=K, seed=31)
+    Ad, Bd = to_gpu(A, dtype), to_gpu(Bt, dtype)
+    V, meta = sp24.sp24_compress(Ad, layout="tiled")
+    P = sp24.sp24_prune(Ad)
+    D = sp24.sp24_spmm_splitk(V, meta, Bd, OUT_DT[out], layout="tiled")
+    Dd = sp24.sp24_gemm_dense_splitk(P, Bd, OUT_DT[out])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 127, 128, M - 1], rng.integers(0, M, 40)]))
+    cols = np.unique(np.concatenate([[0, 1, 31, N - 1], rng.integers(0, N, 24)]))
+    Prows = oracle.prune(np.ascontiguousarray(A[rows]), dtype)
+    ref = oracle.gemm(Prows, np.ascontiguousarray(Bt[cols].T), dtype)
+    for got_t in (D, Dd):
+        got = got_t[torch.as_tensor(rows, device="cuda")][:, torch.as_tensor(cols, device="cuda")]
+        if dtype == "i8":
+            assert np.array_equal(got.cpu().numpy(), ref)
+        else:
+            assert rel_err(out_to_f64(got), ref) <= REL_TOL
