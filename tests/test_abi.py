@@ -242,3 +242,23 @@ def test_split_product_validation_and_workspace_size():
     assert g(A, B, D, *dbase, 0, need8, None) == NULL and g(A, B, D, *dbase, ws + 4, need8, None) == ALIGN
     assert g(A, B, D, *dbase, ws, need8 // 2, None) == SHAPE and g(A, B, D, *dbase, A + 4096, need8, None) == SHAPE
     assert g(A, B, D, 256, 0, 8192, 8192, 8192, 64, sp24.I8, sp24.I32, 0, 0, 0, None) == OK
+
+
+def test_split_workspace_is_a_whole_number_of_images():
+    """Over random legal shapes: 0, or between 2 and 8 images of M x (N rounded up to 4) accumulator values."""
+    import random
+    L = sp24.lib()
+    rnd = random.Random(5)
+    seen = set()
+    for _ in range(4000):
+        t = rnd.choice([sp24.F16, sp24.BF16, sp24.I8])
+        unit = 32 if t == sp24.I8 else 16
+        M = rnd.choice([1, 31, 32, 63, 64, 100, 256, 1000, 4096, 8192, 20000])
+        N = rnd.choice([1, 7, 16, 32, 33, 64, 100, 128, 256, 1000, 4096])
+        K = unit * rnd.randint(1, 2048)
+        b = L.sp24_splitk_workspace_bytes(M, N, K, t)
+        image = M * ((N + 3) // 4 * 4) * 4
+        assert b % image == 0
+        assert b == 0 or 2 <= b // image <= 8, (M, N, K, t, b)
+        seen.add(b // image)
+    assert {0, 2, 4, 8} <= seen
