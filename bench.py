@@ -66,6 +66,9 @@ def parse():
     p.add_argument("--few-tiles", action="store_true",
                    help="add products with few output tiles (32 < N <= 128 at large M and K; small M x N with a long K) in this "
                         "workload's types: as they are and with the inner dimension split across workgroups")
+    p.add_argument("--operand-dependence", action="store_true",
+                   help="add the workload's products on operands of other values (zeros, ones, values near zero): the share of "
+                        "the time that depends on the data through the power cap (ffn_bf16 and square_i8)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one 1 GiB device copy, so that a counter profile of this run holds a kernel of known traffic")
     return p.parse_args()
@@ -291,6 +294,62 @@ def few_tiles(name, steps):
     return rows
 
 
+def operand_dependence(name, steps):
+    """The workload's sparse and dense product, and the vendor library's dense product, on operands of other
+    values -- same shapes, kernels and bytes: all zeros, all ones, and values concentrated near zero (a normal
+    distribution with a tenth of the workload's spread; for int8, sigma = 12).  What changes is how many bits toggle
+    in the data paths, hence the clock the power cap allows.  The pattern of A is the workload's own in every row."""
+    import torch
+    from paper_2104_08378_amd import sp24, synth
+    from util import OUT_DT, to_gpu
+    w = synth.WORKLOADS[name]
+    dt, M, K, N, out_dt = w["dtype"], w["M"], w["K"], w["N"], OUT_DT[w["out"]]
+    A, Bt = synth.make(name)
+    Ad, Bd = to_gpu(A, dt), to_gpu(Bt, dt)
+    V, meta = sp24.sp24_compress(Ad, layout="tiled")
+    D = torch.empty((M, N), dtype=out_dt, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(3)
+
+    def like(t, kind, spread):
+        if kind == "workload":
+            return t
+        if kind == "zeros":
+            return torch.zeros_like(t)
+        if kind == "ones":
+            return torch.ones_like(t)
+        x = torch.randn(t.shape, dtype=torch.float32, device="cuda", generator=gen) * spread
+        return x.round().clamp(-127, 127).to(torch.int8) if dt == "i8" else x.to(t.dtype)
+
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        batches = []
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            batches.append(e0.elapsed_time(e1) / steps)
+        return sorted(batches)[1] * 1e3
+
+    spread_a = 12.0 if dt == "i8" else float(Ad.float().std()) * 0.1
+    spread_b = 12.0 if dt == "i8" else float(Bd.float().std()) * 0.1
+    rows = []
+    for ka, kb in (("workload", "workload"), ("workload", "zeros"), ("zeros", "workload"), ("zeros", "zeros"), ("ones", "ones"),
+                   ("narrow", "narrow")):
+        Vk, Bk = like(V, ka, spread_a), like(Bd, kb, spread_b)
+        P = sp24.sp24_decompress(Vk, meta, layout="tiled")
+        mm = (lambda: torch._int_mm(P, Bk.t())) if dt == "i8" else (lambda: torch.matmul(P, Bk.t()))
+        rows.append({"A": ka, "B": kb,
+                     "sparse_us": timed(lambda: sp24.sp24_spmm(Vk, meta, Bk, out_dt, layout="tiled", out=D)),
+                     "dense_us": timed(lambda: sp24.sp24_gemm_dense(P, Bk, out_dt, out=D)),
+                     "vendor_dense_us": timed(mm)})
+    return rows
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -507,6 +566,8 @@ def main():
         line["sweep_over_K"] = sweep(name, max(5, args.steps // 2))
     if args.few_tiles:
         line["few_tiles"] = few_tiles(name, args.steps)
+    if args.operand_dependence and name in ("ffn_bf16", "square_i8"):
+        line["operand_dependence"] = operand_dependence(name, args.steps)
     if args.extras:
         line["extras"] = extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A, args.steps, conv)
     if args.cpu_seconds > 0:
