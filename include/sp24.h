@@ -136,7 +136,7 @@ sp24_status sp24_decompress(const void* V, const void* meta, void* P, int64_t M,
                             sp24_dtype t, sp24_layout l, void* stream);
 
 /*
- * Sec. 4.1, Step 2 (channel permutations; Fig. 5): the matrix with its columns
+ * Sec. 4.1, Step 2 (channel permutations; Fig. 6): the matrix with its columns
  * taken in the order perm, P[m][k] = A[m][perm[k]], bit for bit.  Permuting
  * the columns of the weights before pruning -- and the rows of the second
  * operand alike: for a K-major B those are the columns of the stored array,
@@ -161,7 +161,7 @@ sp24_status sp24_permute_rows(const void* A, const int32_t* perm, void* P, int64
                               int64_t lda, int64_t ldp, sp24_dtype t, void* stream);
 
 /*
- * Fig. 5's figure of merit for a column order: *total (one double in device
+ * Fig. 6's figure of merit for a column order: *total (one double in device
  * memory, 8-byte aligned, overwritten) = the sum of |a| over the elements that
  * sp24_prune would keep if the groups of four were formed from columns
  * perm[4g] .. perm[4g+3] (perm == NULL: the columns as they are).  Magnitudes

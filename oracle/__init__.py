@@ -180,7 +180,7 @@ def permute_rows(A, perm, dtype):
 
 
 def retained_magnitude(A, dtype, perm=None):
-    """Fig. 5: the total magnitude that 2:4 pruning keeps when the groups of four are taken in the column order perm."""
+    """Fig. 6: the total magnitude that 2:4 pruning keeps when the groups of four are taken in the column order perm."""
     _check(A, dtype)
     out = np.zeros(1, dtype=np.float64)
     if perm is not None:

@@ -109,8 +109,8 @@ static int mag_equal(mag_t a, mag_t b)
 /*
  * keep[i] = 1 for the two elements of the group that survive: element i is
  * removed when at least two others come before it in the order
- * (magnitude descending, column ascending).  "Removes the two smallest
- * weights in each group of four."
+ * (magnitude descending, column ascending): of every group of four the two
+ * entries of least magnitude go (Sec. 4.1, Step 2).
  */
 static void select_two(const double x[4], int keep[4])
 {
@@ -311,7 +311,7 @@ int sp24o_conv2d_i32(const int8_t *P, const int8_t *X, int32_t *D, long M, long 
 
 /*
  * ---- O7: keeping the pattern during retraining (Sec. 4.1, Step 3) ---------
- * "Maintain the sparsity pattern computed in Step 2": after an optimizer
+ * Retraining keeps the pattern that Step 2 chose: after an optimizer
  * step on the dense weights W, every position that Step 2 removed is set back
  * to +0 (mask_apply), and the compressed values are refreshed from W at the
  * positions the metadata records, without selecting again (compress_masked).
@@ -363,7 +363,7 @@ int sp24o_compress_masked(const void *W, const uint8_t *meta, void *V, long M, l
  * ---- O8: patterns that also hold for the transposed matrix -----------------
  * To use the sparse product in the backward pass the 2:4 constraint must hold
  * along rows and along columns (Sec. 6).  The paper names an exhaustive search
- * "that seeks to minimize the weight magnitude lost" and gives no listing; this
+ * whose aim is the least loss of weight magnitude and gives no listing; this
  * is that search written out: every aligned 4 x 4 block keeps the entries of
  * the one pattern, among those with exactly two kept entries in each row and
  * each column (there are 90), whose kept magnitudes sum highest.
@@ -484,7 +484,7 @@ int sp24o_requant_i8(const int32_t *acc, int8_t *Q, long M, long N, const float 
     return 0;
 }
 
-/* ---- channel permutations (Sec. 4.1, Step 2; Fig. 5) -------------------- */
+/* ---- channel permutations (Sec. 4.1, Step 2; Fig. 6) -------------------- */
 
 /*
  * The matrix with its columns taken in the order perm: P[m][k] = A[m][perm[k]]
@@ -540,8 +540,8 @@ int sp24o_permute_rows(const void *A, const int32_t *perm, void *P, long M, long
 }
 
 /*
- * The figure of merit of a column order (Fig. 5: "total weight magnitude"
- * after pruning): the sum of |a| over the elements that the selection rule of
+ * The figure of merit of a column order (Fig. 6: the magnitude that is left
+ * after pruning, summed over the matrix): the sum of |a| over the elements that the selection rule of
  * Step 2 keeps when the groups of four are formed from columns perm[4g] ..
  * perm[4g+3] (perm == NULL: the columns as they are).  Plain double sum, rows
  * then groups then positions in ascending order; a kept NaN makes it NaN.

@@ -15,7 +15,7 @@
 //     metadata words already in lane order (Sec. 3.1: no indirection,
 //     full-width reads), so a wavefront reads its A operands back with one
 //     conflict-free 16-byte and one 4-byte LDS read per lane;
-//   - two s_barriers per step and no fence: a wavefront awaits its own
+//   - one s_barrier per step and no fence: a wavefront awaits its own
 //     transfers with s_waitcnt vmcnt, the barrier then makes everybody's visible;
 //   - memory instructions are dealt out between the matrix-core instructions
 //     (sched_group_barrier) so that their issue time overlaps the arithmetic;
@@ -983,7 +983,8 @@ static sp24_status pick_tile(const MmArgs& a, hipStream_t st)
 {
     // 256x256 tiles when they still fill the 256 compute units, else 128x128
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-    // eight wavefronts of 64x128 each (two per SIMD, so that one computes while the other waits); measured
+    // one workgroup of eight wavefronts of 64x128 each per compute unit (its wavefronts sit two to a SIMD, so that
+    // one computes while the other waits); measured
     // faster than four of 128x128 on the short-K transformer shape and equal on the long-K square one
     if (big >= 200) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
     // 128x128 tiles, four wavefronts.  With few tiles one workgroup per compute unit is all there is, and a short

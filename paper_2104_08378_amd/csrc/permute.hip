@@ -1,4 +1,4 @@
-// Channel permutations (Sec. 4.1, Step 2; Fig. 5): a weight matrix with its columns taken in another order, and
+// Channel permutations (Sec. 4.1, Step 2; Fig. 6): a weight matrix with its columns taken in another order, and
 // the figure of merit of such an order -- the total magnitude that 2:4 pruning keeps when the groups of four are
 // formed from the reordered columns.
 //

@@ -1,4 +1,4 @@
-"""GPU parity of the channel-permutation operations (Sec. 4.1 Step 2, Fig. 5) against the CPU oracle: the column
+"""GPU parity of the channel-permutation operations (Sec. 4.1 Step 2, Fig. 6) against the CPU oracle: the column
 gather bit-exact, the retained magnitude to 1e-12 relative (its terms are exact doubles, only their order of
 addition differs: the sum of n non-negative terms is off by at most n * 2^-53 relative, n < 2^14 per partial sum
 and 2^11 partial sums)."""

@@ -610,7 +610,7 @@ def test_transposable_pruning_tie_rule_and_fixed_points():
     assert (oracle.prune_transposable(D, "i8")[[0, 1, 2, 3], [2, 0, 3, 1]] == 100).all()
 
 
-# --- channel permutations (Sec. 4.1 Step 2, Fig. 5) -------------------------
+# --- channel permutations (Sec. 4.1 Step 2, Fig. 6) -------------------------
 @pytest.mark.parametrize("dt", DTYPES)
 def test_permute_columns_is_numpy_fancy_indexing(dt):
     name = {"f16": "tiny_f16", "bf16": "ffn_bf16", "i8": "square_i8"}[dt]
@@ -633,7 +633,7 @@ def test_retained_magnitude_closed_forms():
     # one group 1 2 3 4 keeps 3 + 4; signs do not matter; a second group of equal values keeps any two
     A = np.array([[1, -2, 3, -4, 5, 5, 5, 5]], dtype=np.int8)
     assert oracle.retained_magnitude(A, "i8") == 7 + 10
-    # Fig. 5's point in miniature: both large values of a row in one group, plus one more large value there,
+    # Fig. 6's point in miniature: both large values of a row in one group, plus one more large value there,
     # lose one of them; dealing the columns out over the groups keeps all three
     B = np.array([[9, 8, 7, 0, 1, 0, 0, 0]], dtype=np.int8)
     assert oracle.retained_magnitude(B, "i8") == 9 + 8 + 1 + 0
