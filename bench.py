@@ -26,7 +26,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 # MI355X published peaks: dense matrix cores per input type, and HBM3E
 PEAK_DENSE = {"f16": 2.5e15, "bf16": 2.5e15, "i8": 5.0e15}
@@ -189,7 +188,7 @@ def sweep(name, steps):
     enough rotating sets that the operands do not stay in the last-level cache."""
     import torch
     from paper_2104_08378_amd import sp24, synth
-    from util import OUT_DT
+    from paper_2104_08378_amd.bits import OUT_DT
     w = synth.WORKLOADS[name]
     dt, out_dt = w["dtype"], OUT_DT[w["out"]]
     M = N = 8192
@@ -243,7 +242,7 @@ def few_tiles(name, steps):
     workspace, second kernel adds them), beside the vendor library's dense product.  Inputs as in sweep()."""
     import torch
     from paper_2104_08378_amd import sp24, synth
-    from util import OUT_DT
+    from paper_2104_08378_amd.bits import OUT_DT
     w = synth.WORKLOADS[name]
     dt, out_dt = w["dtype"], OUT_DT[w["out"]]
     gen = torch.Generator(device="cuda").manual_seed(0)
@@ -301,7 +300,7 @@ def operand_dependence(name, steps):
     in the data paths, hence the clock the power cap allows.  The pattern of A is the workload's own in every row."""
     import torch
     from paper_2104_08378_amd import sp24, synth
-    from util import OUT_DT, to_gpu
+    from paper_2104_08378_amd.bits import OUT_DT, to_gpu
     w = synth.WORKLOADS[name]
     dt, M, K, N, out_dt = w["dtype"], w["M"], w["K"], w["N"], OUT_DT[w["out"]]
     A, Bt = synth.make(name)
@@ -358,7 +357,7 @@ def main():
     import numpy as np
     import torch
     from paper_2104_08378_amd import sp24, synth
-    from util import OUT_DT, to_gpu
+    from paper_2104_08378_amd.bits import OUT_DT, to_gpu
 
     name = args.workload
     w = synth.WORKLOADS[name]

@@ -102,6 +102,40 @@ def _rowmajor(t, name):
     return t
 
 
+def _out(out, shape, dtype, device, name="out"):
+    """The result tensor: a new one, or the caller's, which must have exactly the result's shape and type (the C ABI
+    sees a pointer and a row stride only, so a smaller tensor would be written past its end)."""
+    if out is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    _rowmajor(out, name)
+    if tuple(out.shape) != tuple(shape) or out.dtype != dtype:
+        raise ValueError(f"{name} must be a {tuple(shape)} tensor of {dtype}, got {tuple(out.shape)} of {out.dtype}")
+    return out
+
+
+def _compressed(V, meta):
+    """The compressed pair as sp24_compress returns it: V [M, K/2] contiguous, meta M*K/8 contiguous bytes."""
+    _dev(V, "V"), _dev(meta, "meta")
+    if V.dim() != 2 or not V.is_contiguous():
+        raise ValueError("V must be a contiguous 2-d tensor [M, K/2]")
+    if V.dtype not in (torch.float16, torch.bfloat16, torch.int8):
+        raise ValueError("V must be float16, bfloat16 or int8")
+    M, K = V.shape[0], V.shape[1] * 2
+    _meta_arg(meta, M, K)
+    return M, K
+
+
+def _meta_arg(meta, M, K):
+    _dev(meta, "meta")
+    if not meta.is_contiguous() or meta.numel() * meta.element_size() != M * (K // 8):
+        raise ValueError("meta must be contiguous and hold M*K/8 bytes")
+
+
+def _same_type(B, ref, name="B"):
+    if B.dtype != ref.dtype:
+        raise ValueError(f"{name} must have the first operand's type {ref.dtype}, got {B.dtype}")
+
+
 def _check(status, where):
     if status != 0:
         raise Sp24Error(status, where)
@@ -110,8 +144,8 @@ def _check(status, where):
 def sp24_prune(A, out=None):
     """P = A with the two smallest-magnitude entries of each group of 4 zeroed; out may be A."""
     _rowmajor(A, "A")
-    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
     M, K = A.shape
+    P = _out(out, (M, K), A.dtype, A.device)
     _check(lib().sp24_prune(A.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype], _stream()),
            "sp24_prune")
     return P
@@ -126,17 +160,17 @@ def sp24_compress(A, layout="canonical", out=None):
         meta = torch.empty((M, K // 8), dtype=torch.uint8, device=A.device)
     else:
         V, meta = _dev(out[0], "V"), _dev(out[1], "meta")
-        if V.numel() != M * (K // 2) or V.dtype != A.dtype or meta.numel() * meta.element_size() != M * (K // 8):
-            raise ValueError("out buffers have the wrong size")
+        if (V.numel() != M * (K // 2) or V.dtype != A.dtype or meta.numel() * meta.element_size() != M * (K // 8)
+                or not V.is_contiguous() or not meta.is_contiguous()):
+            raise ValueError("out buffers must be contiguous and hold M*K/2 values and M*K/8 metadata bytes")
     _check(lib().sp24_compress(A.data_ptr(), V.data_ptr(), meta.data_ptr(), M, K, A.stride(0), _DT[A.dtype],
                                _LAYOUT[layout], _stream()), "sp24_compress")
     return V, meta
 
 
 def sp24_decompress(V, meta, layout="canonical", out=None):
-    _dev(V, "V"), _dev(meta, "meta")
-    M, K = V.shape[0], V.shape[1] * 2
-    P = torch.empty((M, K), dtype=V.dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    M, K = _compressed(V, meta)
+    P = _out(out, (M, K), V.dtype, V.device)
     _check(lib().sp24_decompress(V.data_ptr(), meta.data_ptr(), P.data_ptr(), M, K, P.stride(0), _DT[V.dtype],
                                  _LAYOUT[layout], _stream()), "sp24_decompress")
     return P
@@ -146,7 +180,7 @@ def sp24_prune_transposable(A, out=None):
     """2:4 along rows and along columns: per 4x4 block the two-per-row-and-column pattern that keeps the most magnitude."""
     _rowmajor(A, "A")
     M, K = A.shape
-    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
+    P = _out(out, (M, K), A.dtype, A.device)
     _check(lib().sp24_prune_transposable(A.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype], _stream()),
            "sp24_prune_transposable")
     return P
@@ -164,7 +198,7 @@ def sp24_permute_columns(A, perm, out=None):
     _rowmajor(A, "A")
     M, K = A.shape
     _perm_arg(perm, K)
-    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
+    P = _out(out, (M, K), A.dtype, A.device)
     _check(lib().sp24_permute_columns(A.data_ptr(), perm.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype],
                                       _stream()), "sp24_permute_columns")
     return P
@@ -175,7 +209,7 @@ def sp24_permute_rows(A, perm, out=None):
     _rowmajor(A, "A")
     M, K = A.shape
     _perm_arg(perm, M)
-    P = torch.empty_like(A) if out is None else _rowmajor(out, "out")
+    P = _out(out, (M, K), A.dtype, A.device)
     _check(lib().sp24_permute_rows(A.data_ptr(), perm.data_ptr(), P.data_ptr(), M, K, A.stride(0), P.stride(0), _DT[A.dtype],
                                    _stream()), "sp24_permute_rows")
     return P
@@ -198,9 +232,10 @@ def sp24_retained_magnitude(A, perm=None, out=None):
 
 def sp24_mask_apply(W, meta, layout="canonical", out=None):
     """W with every position that the metadata does not record set to +0 (the pattern is kept, not re-selected)."""
-    _rowmajor(W, "W"), _dev(meta, "meta")
+    _rowmajor(W, "W")
     M, K = W.shape
-    P = torch.empty_like(W) if out is None else _rowmajor(out, "out")
+    _meta_arg(meta, M, K)
+    P = _out(out, (M, K), W.dtype, W.device)
     _check(lib().sp24_mask_apply(W.data_ptr(), meta.data_ptr(), P.data_ptr(), M, K, W.stride(0), P.stride(0), _DT[W.dtype],
                                  _LAYOUT[layout], _stream()), "sp24_mask_apply")
     return P
@@ -208,9 +243,12 @@ def sp24_mask_apply(W, meta, layout="canonical", out=None):
 
 def sp24_compress_masked(W, meta, layout="canonical", out=None):
     """Compressed values of W at the positions the metadata records."""
-    _rowmajor(W, "W"), _dev(meta, "meta")
+    _rowmajor(W, "W")
     M, K = W.shape
+    _meta_arg(meta, M, K)
     V = torch.empty((M, K // 2), dtype=W.dtype, device=W.device) if out is None else _dev(out, "out")
+    if V.numel() != M * (K // 2) or V.dtype != W.dtype or not V.is_contiguous():
+        raise ValueError("out must be contiguous and hold M*K/2 values of W's type")
     _check(lib().sp24_compress_masked(W.data_ptr(), meta.data_ptr(), V.data_ptr(), M, K, W.stride(0), _DT[W.dtype],
                                       _LAYOUT[layout], _stream()), "sp24_compress_masked")
     return V
@@ -229,12 +267,12 @@ def _b_args(B, b_order):
 
 def sp24_spmm(V, meta, B, out_dtype, b_order="k", layout="canonical", out=None):
     """D [M, N] = decompress(V, meta) @ B.  B is [N, K] for b_order "k", [K, N] for "n"."""
-    _dev(V, "V"), _dev(meta, "meta")
-    M, K = V.shape[0], V.shape[1] * 2
+    M, K = _compressed(V, meta)
     N, Kb, bo = _b_args(B, b_order)
     if Kb != K:
         raise ValueError("inner dimensions differ")
-    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _same_type(B, V)
+    D = _out(out, (M, N), out_dtype, V.device)
     _check(lib().sp24_spmm(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0),
                            D.stride(0), _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], _stream()), "sp24_spmm")
     return D
@@ -247,7 +285,8 @@ def sp24_gemm_dense(A, B, out_dtype, b_order="k", out=None):
     N, Kb, bo = _b_args(B, b_order)
     if Kb != K:
         raise ValueError("inner dimensions differ")
-    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    _same_type(B, A)
+    D = _out(out, (M, N), out_dtype, A.device)
     _check(lib().sp24_gemm_dense(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0),
                                  D.stride(0), _DT[A.dtype], _DT[D.dtype], bo, _stream()), "sp24_gemm_dense")
     return D
@@ -263,19 +302,21 @@ def _workspace(workspace, M, N, K, dtype, device):
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
     _dev(workspace, "workspace")
+    if not workspace.is_contiguous():
+        raise ValueError("workspace must be contiguous")
     return workspace, workspace.numel() * workspace.element_size()
 
 
 def sp24_spmm_splitk(V, meta, B, out_dtype, b_order="k", layout="canonical", workspace=None, out=None):
     """sp24_spmm with the inner dimension split across workgroups (shapes with few output tiles); ``workspace``: a
     device tensor of at least sp24_splitk_workspace_bytes(...) bytes, allocated here when None."""
-    _dev(V, "V"), _dev(meta, "meta")
-    M, K = V.shape[0], V.shape[1] * 2
+    M, K = _compressed(V, meta)
     N, Kb, bo = _b_args(B, b_order)
     if Kb != K:
         raise ValueError("inner dimensions differ")
+    _same_type(B, V)
     ws, ws_bytes = _workspace(workspace, M, N, K, V.dtype, V.device)
-    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    D = _out(out, (M, N), out_dtype, V.device)
     _check(lib().sp24_spmm_splitk(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
                                   _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], ws.data_ptr(), ws_bytes, _stream()), "sp24_spmm_splitk")
     return D
@@ -288,8 +329,9 @@ def sp24_gemm_dense_splitk(A, B, out_dtype, b_order="k", workspace=None, out=Non
     N, Kb, bo = _b_args(B, b_order)
     if Kb != K:
         raise ValueError("inner dimensions differ")
+    _same_type(B, A)
     ws, ws_bytes = _workspace(workspace, M, N, K, A.dtype, A.device)
-    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    D = _out(out, (M, N), out_dtype, A.device)
     _check(lib().sp24_gemm_dense_splitk(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0), D.stride(0),
                                         _DT[A.dtype], _DT[D.dtype], bo, ws.data_ptr(), ws_bytes, _stream()), "sp24_gemm_dense_splitk")
     return D
@@ -310,10 +352,10 @@ def _conv_args(X, K, R, S, pad, stride):
 def sp24_spmm_conv2d(V, meta, X, out_dtype, R, S, pad=(0, 0), stride=(1, 1), layout="canonical", out=None):
     """D [M, n_img*OH*OW] = decompress(V, meta) applied as a bank of M filters to the NHWC input X, with no
     im2col matrix in memory.  Filter column k = (r*S + s)*C + c."""
-    _dev(V, "V"), _dev(meta, "meta")
-    M, K = V.shape[0], V.shape[1] * 2
+    M, K = _compressed(V, meta)
     geom, N = _conv_args(X, K, R, S, pad, stride)
-    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    _same_type(X, V, "X")
+    D = _out(out, (M, N), out_dtype, V.device)
     _check(lib().sp24_spmm_conv2d(V.data_ptr(), meta.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, D.stride(0),
                                   _DT[V.dtype], _DT[D.dtype], _LAYOUT[layout], _stream()), "sp24_spmm_conv2d")
     return D
@@ -324,7 +366,8 @@ def sp24_conv2d_dense(A, X, out_dtype, R, S, pad=(0, 0), stride=(1, 1), out=None
     _rowmajor(A, "A")
     M, K = A.shape
     geom, N = _conv_args(X, K, R, S, pad, stride)
-    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    _same_type(X, A, "X")
+    D = _out(out, (M, N), out_dtype, A.device)
     _check(lib().sp24_conv2d_dense(A.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, A.stride(0), D.stride(0),
                                    _DT[A.dtype], _DT[D.dtype], _stream()), "sp24_conv2d_dense")
     return D
@@ -345,13 +388,13 @@ def sp24_spmm_i8_scaled(V, meta, B, out_dtype, w_scale, x_scale, bias=None, relu
                         layout="canonical", out=None):
     """int8 sparse product with the quantised path's epilogue fused into the store: per-row weight scale,
     per-tensor activation scale, optional bias and ReLU; out_dtype int8 (re-quantised by inv_y_scale) or a float type."""
-    _dev(V, "V"), _dev(meta, "meta")
-    M, K = V.shape[0], V.shape[1] * 2
+    M, K = _compressed(V, meta)
     N, Kb, bo = _b_args(B, b_order)
     if Kb != K:
         raise ValueError("inner dimensions differ")
+    _same_type(B, V)
     ws, bs = _scale_args(M, w_scale, bias)
-    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    D = _out(out, (M, N), out_dtype, V.device)
     _check(lib().sp24_spmm_i8_scaled(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
                                      ws, float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], bo, _LAYOUT[layout],
                                      _stream()), "sp24_spmm_i8_scaled")
@@ -365,8 +408,9 @@ def sp24_gemm_dense_i8_scaled(A, B, out_dtype, w_scale, x_scale, bias=None, relu
     N, Kb, bo = _b_args(B, b_order)
     if Kb != K:
         raise ValueError("inner dimensions differ")
+    _same_type(B, A)
     ws, bs = _scale_args(M, w_scale, bias)
-    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    D = _out(out, (M, N), out_dtype, A.device)
     _check(lib().sp24_gemm_dense_i8_scaled(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0), D.stride(0),
                                            ws, float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], bo, _stream()),
            "sp24_gemm_dense_i8_scaled")
@@ -376,11 +420,11 @@ def sp24_gemm_dense_i8_scaled(A, B, out_dtype, w_scale, x_scale, bias=None, relu
 def sp24_spmm_conv2d_i8_scaled(V, meta, X, out_dtype, R, S, w_scale, x_scale, bias=None, relu=False, inv_y_scale=1.0,
                                pad=(0, 0), stride=(1, 1), layout="canonical", out=None):
     """int8 sparse convolution (implicit GEMM) with the quantised path's epilogue; w_scale per output channel."""
-    _dev(V, "V"), _dev(meta, "meta")
-    M, K = V.shape[0], V.shape[1] * 2
+    M, K = _compressed(V, meta)
     geom, N = _conv_args(X, K, R, S, pad, stride)
+    _same_type(X, V, "X")
     ws, bs = _scale_args(M, w_scale, bias)
-    D = torch.empty((M, N), dtype=out_dtype, device=V.device) if out is None else _rowmajor(out, "out")
+    D = _out(out, (M, N), out_dtype, V.device)
     _check(lib().sp24_spmm_conv2d_i8_scaled(V.data_ptr(), meta.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, D.stride(0), ws,
                                             float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], _LAYOUT[layout],
                                             _stream()), "sp24_spmm_conv2d_i8_scaled")
@@ -393,8 +437,9 @@ def sp24_conv2d_dense_i8_scaled(A, X, out_dtype, R, S, w_scale, x_scale, bias=No
     _rowmajor(A, "A")
     M, K = A.shape
     geom, N = _conv_args(X, K, R, S, pad, stride)
+    _same_type(X, A, "X")
     ws, bs = _scale_args(M, w_scale, bias)
-    D = torch.empty((M, N), dtype=out_dtype, device=A.device) if out is None else _rowmajor(out, "out")
+    D = _out(out, (M, N), out_dtype, A.device)
     _check(lib().sp24_conv2d_dense_i8_scaled(A.data_ptr(), X.data_ptr(), D.data_ptr(), M, *geom, A.stride(0), D.stride(0), ws,
                                              float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], _stream()),
            "sp24_conv2d_dense_i8_scaled")

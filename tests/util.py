@@ -1,34 +1,8 @@
-"""Helpers shared by the GPU parity tests: numpy bit patterns <-> torch tensors,
-and an independent statement of the tiled layout written from the header text."""
+"""Helpers shared by the GPU parity tests: an independent statement of the tiled layout written from the header
+text (the bit-pattern marshalling lives in the package, paper_2104_08378_amd/bits.py)."""
 import numpy as np
-import torch
 
-TORCH_DT = {"f16": torch.float16, "bf16": torch.bfloat16, "i8": torch.int8}
-OUT_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32}
-
-
-def to_gpu(bits, dtype):
-    """numpy uint16 bit patterns / int8 -> GPU tensor of the matching torch dtype (same bits)."""
-    if dtype == "i8":
-        return torch.from_numpy(np.ascontiguousarray(bits)).cuda()
-    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
-    return t.view(TORCH_DT[dtype])
-
-
-def to_bits(t):
-    """GPU tensor -> numpy array of raw storage (uint16 for 16-bit floats)."""
-    t = t.detach().cpu().contiguous()
-    if t.dtype in (torch.float16, torch.bfloat16):
-        return t.view(torch.int16).numpy().view(np.uint16)
-    return t.numpy()
-
-
-def out_to_f64(t):
-    """Exact float64 value of a GPU result tensor."""
-    t = t.detach().cpu()
-    if t.dtype == torch.int32:
-        return t.numpy().astype(np.float64)
-    return t.to(torch.float64).numpy()
+from paper_2104_08378_amd.bits import OUT_DT, TORCH_DT, out_to_f64, to_bits, to_gpu  # noqa: F401  (re-exported for the tests)
 
 
 def tiled_from_canonical(V, meta, dtype):
