@@ -1,6 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the 2:4 sparse matrix-multiply hot path on one MI355X.
 
+The line is for the large int8 product (8192 x 8192 x 8192, `square_i8`) unless
+--workload names another; the other configurations follow as extra keys of the
+same line (`other_workloads`: kernels back to back and the vendor's dense
+product only).
+
 A step is one pass of the whole path over one batch of synthetic input:
 prune -> compress (tiled layout) -> decompress -> sparse product -> same-shape
 dense product.  All inputs are resident in HBM before the timed region; every
@@ -10,12 +15,15 @@ footprint of the loop exceeds the 256 MB last-level cache.
 Prints one JSON line.  `value` is the metric: dense-equivalent TFLOP/s of the
 sparse product, 2*M*N*K divided by its mean duration, measured with HIP events
 on the launch stream: the whole-path steps give `ms_per_step` (wall time of a
-step) and `step_ms` (event pair around every launch), and the two products are
+step) and `step_ms` (event pair around every launch), and every operation is
 then timed as back-to-back launches on the same rotating inputs
 (`kernel_ms_back_to_back`: five batches, the median), which is the duration
-`value`, `speedup_vs_dense` and `roofline` use; `kernel_ms_cache_warm` is the
+`value`, the speedups and `roofline` use; `kernel_ms_cache_warm` is the
 same on one input set (operands resident in the last-level cache), for
-comparison only.  `roofline` describes the sparse product kernel,
+comparison only.  `speedup_vs_dense` is over the faster of the own dense kernel
+and the vendor library's dense product on the same inputs (both ratios are
+kept beside it).  `roofline` describes the sparse product kernel (`traffic`
+is read from the counter sections of profiles/<workload>_path_rocprofv3.txt),
 `cpu_baseline` the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
@@ -34,15 +42,6 @@ PEAK_HBM = 8.0e12
 # dense-equivalent op/s of v_smfmac_*_32x32 in a register-only loop on all compute units, random operands (sp24_probe)
 MEASURED_SPARSE_ISSUE = {"f16": 3.105e15, "bf16": 3.221e15, "i8": 6.656e15}
 
-# HBM bytes per launch of the sparse product kernel from rocprofv3 counter runs of this file
-# (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a 1 GiB device copy;
-# summaries under profiles/).  None where not measured.
-MEASURED_TRAFFIC = {
-    "ffn_bf16": (2.0 * 31689.9 + 65676.0) * 1024,      # profiles/ffn_bf16_path_rocprofv3.txt    (algorithmic: 88.6 MB)
-    "square_i8": (2.0 * 295235.2 + 262556.3) * 1024,   # profiles/square_i8_path_rocprofv3.txt   (algorithmic: 377.5 MB)
-    "skinny_bf16": (2.0 * 37924.6 + 256.0) * 1024,     # profiles/skinny_bf16_path_rocprofv3.txt  (algorithmic: 76.0 MB)
-    "conv3x3_f16": (2.0 * 5982.6 + 6272.0) * 1024,     # profiles/conv3x3_f16_path_rocprofv3.txt  (algorithmic: 13.5 MB, implicit gather)
-}
 
 
 def parse():
@@ -50,8 +49,11 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=3)
-    p.add_argument("--workload", default="ffn_bf16", help="tiny_f16 | ffn_bf16 | conv3x3_f16 | square_i8 | skinny_bf16")
-    p.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
+    p.add_argument("--workload", default="square_i8",
+                   help="tiny_f16 | ffn_bf16 | conv3x3_f16 | square_i8 | skinny_bf16: the workload of the line "
+                        "(default: the large int8 product the target is stated on); the others follow under `other_workloads`")
+    p.add_argument("--no-others", action="store_true", help="the one workload only (profiling aid)")
+    p.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the CPU-oracle leg (0 = skip)")
     p.add_argument("--only", default="", help="comma list of ops to run in a step (profiling aid); default all")
     p.add_argument("--materialised", action="store_true",
                    help="conv3x3_f16 only: multiply by the im2col matrix built beforehand instead of gathering it implicitly")
@@ -82,25 +84,33 @@ def cpu_baseline(name, A, Bt, budget_s):
     w = synth.WORKLOADS[name]
     dt, K = w["dtype"], w["K"]
     rows, cols = 32, min(w["N"], 1024)
-    Bs = np.ascontiguousarray(Bt[:cols].T)
 
-    def run(r):
+    def run(r, c):
         As = np.ascontiguousarray(A[:r])
+        Bs = np.ascontiguousarray(Bt[:c].T)
         t0 = time.perf_counter()
         V, meta = oracle.compress(As, dt)
         P = oracle.decompress(V, meta, dt)
         oracle.gemm(P, Bs, dt)
         return time.perf_counter() - t0
 
-    t = run(rows)
-    rows = int(max(rows, min(w["M"], rows * budget_s / max(t, 1e-3))))   # scale the sample to the budget
-    rows -= rows % 32
-    t = run(rows)
+    t = run(rows, cols)
+    for _ in range(3):                                       # grow the sample towards the budget: rows first, then columns of B
+        grow = min(16.0, budget_s / max(t, 1e-3))
+        if grow < 1.5:
+            break
+        if rows < w["M"]:
+            rows = int(min(w["M"], rows * grow)) // 32 * 32
+        elif cols < w["N"]:
+            cols = int(min(w["N"], cols * grow)) // 64 * 64
+        else:
+            break
+        t = run(rows, cols)
     cores = oracle.threads()
     # the same on one thread, on a sample cut down by the thread count
     rows1 = max(32, rows // max(cores, 1) // 32 * 32)
     before = oracle.set_threads(1)
-    t1 = run(rows1)
+    t1 = run(rows1, cols)
     oracle.set_threads(before)
     return {"value": 2.0 * rows * cols * K / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "sample": f"first {rows} rows of A x first {cols} columns of B, K={K}: compress + decompress + "
@@ -349,23 +359,51 @@ def operand_dependence(name, steps):
     return rows
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported", file=sys.stderr)
-        sys.exit(2)
+def measured_traffic(name):
+    """HBM bytes per launch of the workload's sparse product kernel, from the counter sections of the committed
+    rocprofv3 summary profiles/<workload>_path_rocprofv3.txt: FETCH_SIZE and WRITE_SIZE of that kernel, each scaled by
+    what the same counter read for the 1 GiB device copy of the same run (2^20 KiB read, 2^20 KiB written).
+    None when the summary is missing or does not hold those lines."""
+    import ast
+    path = os.path.join(ROOT, "profiles", name + "_path_rocprofv3.txt")
+    if not os.path.exists(path):
+        return None
+    got = {}
+    section = None
+    for ln in open(path):
+        if ln.startswith("== counters"):
+            section = "FETCH_SIZE" if "--pmc FETCH_SIZE" in ln else "WRITE_SIZE" if "--pmc WRITE_SIZE" in ln else None
+            continue
+        if ln.startswith("=="):
+            section = None
+        if section is None or "{" not in ln:
+            continue
+        kernel = ln[:ln.index("{")]
+        sparse = "k_spmm_pipe" in kernel or ("k_mm_skinny" in kernel and "true" in kernel)
+        who = "kernel" if sparse else "copy" if "copyBuffer" in kernel else None
+        if who and (who, section) not in got:
+            got[(who, section)] = float(ast.literal_eval(ln[ln.index("{"):ln.index("}") + 1])[section])
+    try:
+        kib = (got[("kernel", "FETCH_SIZE")] * 2 ** 20 / got[("copy", "FETCH_SIZE")] +
+               got[("kernel", "WRITE_SIZE")] * 2 ** 20 / got[("copy", "WRITE_SIZE")])
+    except KeyError:
+        return None
+    return kib * 1024.0
+
+
+def measure(name, args, brief=False):
+    """All measurements of one workload.  brief: the kernels back to back and the vendor's dense product only (no
+    whole-path steps with an event pair per launch, no cache-warm leg, no options)."""
     import numpy as np
     import torch
     from paper_2104_08378_amd import sp24, synth
     from paper_2104_08378_amd.bits import OUT_DT, to_gpu
 
-    name = args.workload
     w = synth.WORKLOADS[name]
     dt, M, K, N = w["dtype"], w["M"], w["K"], w["N"]
     es = 1 if dt == "i8" else 2
     out_dt = OUT_DT[w["out"]]
     os_ = torch.empty((), dtype=out_dt).element_size()
-    torch.cuda.set_device(0)
     A, Bt = synth.make(name)
     # the convolution workload runs as its title says, an implicit GEMM on the NHWC activations (no im2col matrix
     # in device memory); --materialised times the product with the im2col matrix built beforehand instead
@@ -380,7 +418,7 @@ def main():
     D = torch.empty((M, N), dtype=out_dt, device="cuda")
     Dd = torch.empty((M, N), dtype=out_dt, device="cuda")
     ops = ["prune", "compress", "decompress", "spmm", "dense"]
-    only = [o for o in args.only.split(",") if o] or ops
+    only = ([o for o in args.only.split(",") if o] if not brief else []) or list(ops)
     V, meta = sp24.sp24_compress(As[0], layout="tiled")
     sp24.sp24_prune(As[0], out=P)
 
@@ -419,16 +457,20 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, events[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    ms, ms_per_step = None, None
+    if not brief:
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, events[i])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms = {o: float(np.mean([events[i][j].elapsed_time(events[i][j + 1]) for i in range(args.steps)])) for j, o in enumerate(ops)}
+        ms_per_step = wall * 1e3 / args.steps
 
     # Kernel durations.  An event pair around a single launch also counts the dispatch latency of that launch
-    # (about 3.5 us here, a fifth of the skinny product); a kernel profiler does not.  So the two products are
-    # timed once more as `steps` back-to-back launches each, on the same rotating inputs, one event pair around
+    # (about 3.5 us here, a fifth of the skinny product); a kernel profiler does not.  So every operation is
+    # timed once more as `steps` back-to-back launches, on the same rotating inputs, one event pair around
     # the batch: the mean of that is what rocprofv3 --kernel-trace reports as the kernel's average duration.
     # Five batches each, the median reported.  `same_inputs`: every launch on input set 0, i.e. operands resident in
     # the 256 MB last-level cache -- reported separately (`kernel_ms_cache_warm`), never used for `value`.
@@ -451,12 +493,12 @@ def main():
             batches.append(e0.elapsed_time(e1) / args.steps)
         only[:] = saved
         return float(np.median(batches))
-    ms_b2b = {"spmm": back_to_back("spmm"), "dense": back_to_back("dense")}
-    ms_warm = {"spmm": back_to_back("spmm", True), "dense": back_to_back("dense", True)}
+    ms_b2b = {o: back_to_back(o) for o in ops}
+    ms_warm = None if brief else {"spmm": back_to_back("spmm", True), "dense": back_to_back("dense", True)}
 
-    # Context, not the product: the vendor library's dense GEMM on the same shape and the same rotating inputs
-    # (torch.matmul / torch._int_mm, i.e. hipBLASLt or rocBLAS), the counterpart of the paper's dense denominator
-    # (Sec. 3.2, Fig. 3 use the vendor's dense library).  Output type: the input type (int32 for int8 inputs).
+    # The vendor library's dense GEMM on the same shape and the same rotating inputs (torch.matmul / torch._int_mm,
+    # i.e. hipBLASLt or rocBLAS), the counterpart of the paper's dense denominator (Sec. 3.2, Fig. 3 use the
+    # vendor's dense library).  Output type: the input type (int32 for int8 inputs).
     def vendor_dense():
         if "dense" not in only or "spmm" not in only or (name == "conv3x3_f16" and not conv):
             return None
@@ -471,16 +513,19 @@ def main():
                 run = lambda i: torch._int_mm(P, Bs[i % R].t())
             else:
                 run = lambda i: torch.matmul(P, Bs[i % R].t())
-            for i in range(3):
+            for i in range(5):
                 run(i)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record()
-            for i in range(args.steps):
-                run(i)
-            e1.record()
-            torch.cuda.synchronize()
-            t = e0.elapsed_time(e1) / args.steps
+            batches = []
+            for rep in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(args.steps):
+                    run(i)
+                e1.record()
+                torch.cuda.synchronize()
+                batches.append(e0.elapsed_time(e1) / args.steps)
+            t = float(np.median(batches))
             return {"ms": t, "speedup_of_sparse": t / ms_b2b["spmm"], "own_dense_over_vendor": ms_b2b["dense"] / t,
                     "library": "torch %s (%s)" % (torch.__version__, "conv2d, channels-last" if conv else "torch._int_mm" if dt == "i8" else "torch.matmul")}
         except Exception as e:                               # a shape the library call does not take
@@ -508,18 +553,16 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (5 * args.steps) * 1e3
     graph_us = graph_replay()
-    if args.calibrate_copy:
+    if args.calibrate_copy and not brief:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
-    ms = {o: float(np.mean([events[i][j].elapsed_time(events[i][j + 1]) for i in range(args.steps)])) for j, o in enumerate(ops)}
-    ms_per_step = wall * 1e3 / args.steps
 
     flops_equiv = 2.0 * M * N * K
     # (--only without an operation: its time is taken as infinite, so that its rates read 0 instead of dividing by 0)
-    t_sp = ms_b2b["spmm"] * 1e-3 if "spmm" in only else float("inf")
-    t_dn = ms_b2b["dense"] * 1e-3 if "dense" in only else float("inf")
+    t_of = {o: (ms_b2b[o] * 1e-3 if o in only else float("inf")) for o in ops}
+    t_sp, t_dn = t_of["spmm"], t_of["dense"]
     value = flops_equiv / t_sp / 1e12 if "spmm" in only else 0.0
     bytes_pc = M * K * es * 1.5 + M * K / 8                  # fused prune+compress: read A, write V + meta
     b_bytes = Bsrc.nbytes                                    # the second operand as it lies in memory
@@ -540,7 +583,12 @@ def main():
         # context: what a register-only loop of the same sparse instruction sustains on this chip with random
         # operands (profiles/chip_ceilings_sp24_probe.txt; the part clocks down under real toggle rates)
         roof["frac_of_measured_issue_rate"] = flops_equiv / t_sp / MEASURED_SPARSE_ISSUE[dt]
-    roof["traffic"] = None if (name == "conv3x3_f16" and not conv) else MEASURED_TRAFFIC.get(name)
+    roof["traffic"] = None if (name == "conv3x3_f16" and not conv) else measured_traffic(name)
+    # the speedup the paper plots (Sec. 3.2, Fig. 3) is over the best dense product available: the own dense kernel
+    # or the vendor library's, whichever is faster on this shape
+    both = "dense" in only and "spmm" in only
+    t_vendor = vendor["ms"] * 1e-3 if vendor and "ms" in vendor else float("inf")
+    t_best = min(t_dn, t_vendor)
     line = {
         "metric": "2:4 SpGEMM dense-equiv TFLOP/s on 1 MI355X; speedup vs same-shape dense GEMM",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -550,27 +598,54 @@ def main():
                    "b_order": "implicit im2col of NHWC 64x14x14x256, 3x3, pad 1" if conv else "k-major",
                    "rotating_input_sets": R},
         "step_ms": ms, "kernel_ms_back_to_back": ms_b2b, "kernel_ms_cache_warm": ms_warm,
-        "speedup_vs_dense": (t_dn / t_sp) if ("dense" in only and "spmm" in only) else None,
+        "speedup_vs_dense": (t_best / t_sp) if both else None,
+        "speedup_vs_dense_is_over": None if not both else ("own dense kernel" if t_dn <= t_vendor else "vendor dense library"),
+        "speedup_vs_own_dense": (t_dn / t_sp) if both else None,
+        "speedup_vs_vendor_dense": (t_vendor / t_sp) if both and t_vendor != float("inf") else None,
         "dense_tflops": flops_equiv / t_dn / 1e12 if "dense" in only else None,
         "vendor_dense": vendor,
         "graph_replay_us_per_spmm": graph_us,
         "spmm_GBps": bytes_spmm / t_sp / 1e9 if "spmm" in only else None,
         "dense_GBps": bytes_dense / t_dn / 1e9 if "dense" in only else None,
-        "prune_GBps": 2.0 * M * K * es / (ms["prune"] * 1e-3) / 1e9 if "prune" in only else None,
-        "compress_GBps": bytes_pc / (ms["compress"] * 1e-3) / 1e9 if "compress" in only else None,
-        "decompress_GBps": bytes_pc / (ms["decompress"] * 1e-3) / 1e9 if "decompress" in only else None,
+        "prune_GBps": 2.0 * M * K * es / t_of["prune"] / 1e9 if "prune" in only else None,
+        "compress_GBps": bytes_pc / t_of["compress"] / 1e9 if "compress" in only else None,
+        "decompress_GBps": bytes_pc / t_of["decompress"] / 1e9 if "decompress" in only else None,
         "roofline": roof,
     }
-    if args.sweep and name in ("ffn_bf16", "square_i8"):
-        line["sweep_over_K"] = sweep(name, max(5, args.steps // 2))
-    if args.few_tiles:
-        line["few_tiles"] = few_tiles(name, args.steps)
-    if args.operand_dependence and name in ("ffn_bf16", "square_i8"):
-        line["operand_dependence"] = operand_dependence(name, args.steps)
-    if args.extras:
-        line["extras"] = extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A, args.steps, conv)
-    if args.cpu_seconds > 0:
-        line["cpu_baseline"] = cpu_baseline(name, A, Bt, args.cpu_seconds)
+    if brief:
+        keep = ("value", "unit", "dtype", "config", "kernel_ms_back_to_back", "speedup_vs_dense", "speedup_vs_dense_is_over",
+                "speedup_vs_own_dense", "speedup_vs_vendor_dense", "vendor_dense", "graph_replay_us_per_spmm", "spmm_GBps",
+                "prune_GBps", "compress_GBps", "decompress_GBps", "roofline")
+        line = {k: line[k] for k in keep}
+        line["roofline"] = {k: roof[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")}
+    else:
+        if args.sweep and name in ("ffn_bf16", "square_i8"):
+            line["sweep_over_K"] = sweep(name, max(5, args.steps // 2))
+        if args.few_tiles:
+            line["few_tiles"] = few_tiles(name, args.steps)
+        if args.operand_dependence and name in ("ffn_bf16", "square_i8"):
+            line["operand_dependence"] = operand_dependence(name, args.steps)
+        if args.extras:
+            line["extras"] = extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A, args.steps, conv)
+        if args.cpu_seconds > 0:
+            line["cpu_baseline"] = cpu_baseline(name, A, Bt, args.cpu_seconds)
+    del As, Bs, P, P2, D, Dd, V, meta
+    torch.cuda.empty_cache()
+    return line
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2104_08378_amd import synth
+    torch.cuda.set_device(0)
+    line = measure(args.workload, args)
+    if not args.only and not args.no_others:
+        # the other configurations, kernels back to back only, as extra keys of the same line
+        line["other_workloads"] = {n: measure(n, args, brief=True) for n in synth.WORKLOADS if n != args.workload}
     print(json.dumps(line))
 
 
