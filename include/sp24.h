@@ -58,7 +58,8 @@ typedef enum {
     SP24_ERR_ALIGN = 3,  /* pointer or leading dimension not 16-byte aligned    */
     SP24_ERR_DTYPE = 4,  /* unknown type or unsupported in/out combination      */
     SP24_ERR_LAYOUT = 5, /* unknown layout, or shape not legal for that layout  */
-    SP24_ERR_LAUNCH = 6  /* the HIP runtime rejected a launch                   */
+    SP24_ERR_LAUNCH = 6, /* the HIP runtime rejected a launch                   */
+    SP24_ERR_WORKSPACE = 7 /* sp24_spmm_splitk_static: the shape needs more than SP24_STATIC_SCRATCH_BYTES */
 } sp24_status;
 
 typedef enum {
@@ -267,6 +268,27 @@ sp24_status sp24_gemm_dense_splitk(const void* A, const void* B, void* D, int64_
                                    int64_t K, int64_t lda, int64_t ldb, int64_t ldd, sp24_dtype in,
                                    sp24_dtype out, sp24_border bo, void* workspace,
                                    size_t workspace_bytes, void* stream);
+
+/*
+ * sp24_spmm_splitk for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments (minus the workspace), same kernels and
+ * the same results bit for bit; the partial products go to an array of
+ * SP24_STATIC_SCRATCH_BYTES bytes that the library holds in device memory
+ * itself (one copy on every GPU it runs on, for the life of the process).
+ * The call allocates and frees nothing.  A shape whose split needs more --
+ * sp24_splitk_workspace_bytes(M, N, K, in) > SP24_STATIC_SCRATCH_BYTES -- is
+ * refused with SP24_ERR_WORKSPACE before anything is launched; a shape that
+ * is not split (0 bytes) runs as sp24_spmm and touches no scratch.  All calls
+ * on one GPU share the one array: calls that overlap in time on the same GPU
+ * (two streams, two threads) race and give unspecified results; calls on one
+ * stream are ordered and safe.  Nothing in the array needs clearing between
+ * calls (every value read was written by the same call).
+ */
+#define SP24_STATIC_SCRATCH_BYTES (8u << 20)
+sp24_status sp24_spmm_splitk_static(const void* V, const void* meta, const void* B, void* D, int64_t M,
+                                    int64_t N, int64_t K, int64_t ldb, int64_t ldd, sp24_dtype in,
+                                    sp24_dtype out, sp24_border bo, sp24_layout l, void* stream);
 
 /*
  * Convolution as a GEMM-like operation whose first argument is the sparse

@@ -1,9 +1,18 @@
 // C ABI of libsp24: argument validation on the host, then kernel selection.
 // Nothing here allocates, synchronises or touches the current device.
+#include <atomic>
+
 #include "common.hpp"
 #include "launch.hpp"
 
 using namespace sp24;
+
+// Memory of the library's own for sp24_spmm_splitk_static, whose callers cannot allocate or pass a workspace: the
+// partial products of the split product live here instead.  Every GPU the library runs on holds its own copy of
+// the array until the process ends.  In host code the array's name stands for the symbol, it is not a device
+// address: the address on the current device comes from hipGetSymbolAddress (static_scratch() below), and only
+// that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[SP24_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -356,13 +365,36 @@ static SplitPlan split_plan(int64_t M, int64_t N, int64_t K, sp24_dtype in)
     return p;
 }
 
-static sp24_status mm_splitk(const MmArgs& a, void* workspace, size_t workspace_bytes, hipStream_t st)
+// Address of `scratch` on the current device, looked up once per device (with that device current) and kept.
+static sp24_status static_scratch(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> ptr_of_device[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SP24_ERR_LAUNCH;
+    void* p = ptr_of_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SP24_ERR_LAUNCH;
+        ptr_of_device[dev].store(p, std::memory_order_release);   // two first callers store the same address
+    }
+    *out = p;
+    return SP24_OK;
+}
+
+// use_static: the partial products go to the library's own scratch array instead of a caller's workspace
+static sp24_status mm_splitk(const MmArgs& a, void* workspace, size_t workspace_bytes, hipStream_t st, bool use_static = false)
 {
     bool empty;
     sp24_status s = mm_validate(a, 0, &empty);
     if (s != SP24_OK || empty) return s;
     const SplitPlan plan = split_plan(a.M, a.N, a.K, a.in);
     if (plan.slices <= 1) return mm_dispatch(a, st);
+    if (use_static) {
+        if (plan.bytes > (size_t)SP24_STATIC_SCRATCH_BYTES) return SP24_ERR_WORKSPACE;
+        s = static_scratch(&workspace);
+        if (s != SP24_OK) return s;
+        workspace_bytes = SP24_STATIC_SCRATCH_BYTES;
+    }
     if (!workspace) return SP24_ERR_NULL;
     if (!aligned16(workspace)) return SP24_ERR_ALIGN;
     if (workspace_bytes < plan.bytes) return SP24_ERR_SHAPE;
@@ -399,6 +431,14 @@ sp24_status sp24_spmm_splitk(const void* V, const void* meta, const void* B, voi
 {
     MmArgs a{V, meta, B, D, M, N, K, 0, ldb, ldd, in, out, bo, l, true};
     return mm_splitk(a, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+sp24_status sp24_spmm_splitk_static(const void* V, const void* meta, const void* B, void* D, int64_t M, int64_t N, int64_t K,
+                                    int64_t ldb, int64_t ldd, sp24_dtype in, sp24_dtype out, sp24_border bo, sp24_layout l,
+                                    void* stream)
+{
+    MmArgs a{V, meta, B, D, M, N, K, 0, ldb, ldd, in, out, bo, l, true};
+    return mm_splitk(a, nullptr, 0, static_cast<hipStream_t>(stream), true);
 }
 
 sp24_status sp24_gemm_dense_splitk(const void* A, const void* B, void* D, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
@@ -511,6 +551,7 @@ const char* sp24_status_string(sp24_status s)
     case SP24_ERR_DTYPE: return "unknown or unsupported element type";
     case SP24_ERR_LAYOUT: return "unknown layout or shape not legal for the layout";
     case SP24_ERR_LAUNCH: return "HIP launch failed";
+    case SP24_ERR_WORKSPACE: return "the shape needs more scratch memory than the library's static buffer holds";
     }
     return "unknown status";
 }

@@ -55,6 +55,7 @@ def lib():
         L.sp24_splitk_workspace_bytes.argtypes = [i64, i64, i64, i32]
         L.sp24_splitk_workspace_bytes.restype = ctypes.c_size_t
         L.sp24_spmm_splitk.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp, ctypes.c_size_t, vp]
+        L.sp24_spmm_splitk_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
         L.sp24_gemm_dense_splitk.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp, ctypes.c_size_t, vp]
         L.sp24_spmm_conv2d.argtypes = [vp, vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i32, i32, i32, vp]
         L.sp24_conv2d_dense.argtypes = [vp, vp, vp] + [i64] * 5 + [i32] * 6 + [i64, i64, i32, i32, vp]
@@ -67,7 +68,7 @@ def lib():
         L.sp24_status_string.restype = ctypes.c_char_p
         for name in ("sp24_prune_transposable", "sp24_mask_apply", "sp24_compress_masked", "sp24_prune", "sp24_compress", "sp24_decompress", "sp24_spmm", "sp24_gemm_dense", "sp24_spmm_conv2d",
                      "sp24_conv2d_dense", "sp24_spmm_i8_scaled", "sp24_gemm_dense_i8_scaled",
-                     "sp24_spmm_conv2d_i8_scaled", "sp24_conv2d_dense_i8_scaled", "sp24_spmm_splitk", "sp24_gemm_dense_splitk"):
+                     "sp24_spmm_conv2d_i8_scaled", "sp24_conv2d_dense_i8_scaled", "sp24_spmm_splitk", "sp24_gemm_dense_splitk", "sp24_spmm_splitk_static"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -319,6 +320,24 @@ def sp24_spmm_splitk(V, meta, B, out_dtype, b_order="k", layout="canonical", wor
     D = _out(out, (M, N), out_dtype, V.device)
     _check(lib().sp24_spmm_splitk(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
                                   _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], ws.data_ptr(), ws_bytes, _stream()), "sp24_spmm_splitk")
+    return D
+
+
+STATIC_SCRATCH_BYTES = 8 << 20     # SP24_STATIC_SCRATCH_BYTES of the header
+
+
+def sp24_spmm_splitk_static(V, meta, B, out_dtype, b_order="k", layout="canonical", out=None):
+    """sp24_spmm_splitk with the partial products in the library's own static device array (no workspace, nothing
+    allocated by the call itself when ``out`` is given); raises Sp24Error with status 7 for shapes whose split needs
+    more than STATIC_SCRATCH_BYTES."""
+    M, K = _compressed(V, meta)
+    N, Kb, bo = _b_args(B, b_order)
+    if Kb != K:
+        raise ValueError("inner dimensions differ")
+    _same_type(B, V)
+    D = _out(out, (M, N), out_dtype, V.device)
+    _check(lib().sp24_spmm_splitk_static(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
+                                         _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], _stream()), "sp24_spmm_splitk_static")
     return D
 
 

@@ -42,7 +42,7 @@ def test_size_functions_follow_the_storage_closed_forms():
 
 def test_status_strings():
     assert sp24.status_string(0) == "ok"
-    for s in range(1, 7):
+    for s in range(1, 8):
         assert sp24.status_string(s) not in ("ok", "unknown status")
 
 
@@ -262,3 +262,20 @@ def test_split_workspace_is_a_whole_number_of_images():
         assert b == 0 or 2 <= b // image <= 8, (M, N, K, t, b)
         seen.add(b // image)
     assert {0, 2, 4, 8} <= seen
+
+
+def test_static_scratch_variant_checks_on_the_host():
+    # sp24_spmm_splitk_static validates like sp24_spmm_splitk and refuses, before any device call, a shape whose
+    # split needs more than the static array holds
+    L = sp24.lib()
+    f = L.sp24_spmm_splitk_static
+    V, META, B, D = P, P + 0x4000000, P + 0x8000000, P + 0x10000000
+    M, N, K = 8192, 128, 8192
+    assert L.sp24_splitk_workspace_bytes(M, N, K, sp24.BF16) > sp24.STATIC_SCRATCH_BYTES
+    assert f(V, META, B, D, M, N, K, K, N, sp24.BF16, sp24.BF16, sp24.B_KMAJOR, sp24.TILED, None) == 7
+    assert f(0, META, B, D, M, N, K, K, N, sp24.BF16, sp24.BF16, sp24.B_KMAJOR, sp24.TILED, None) == NULL
+    assert f(V, META, B, D, M, N, K + 8, K + 8, N, sp24.BF16, sp24.BF16, sp24.B_KMAJOR, sp24.TILED, None) == SHAPE
+    assert f(V, META, B, D, M, N, K, K, N, sp24.BF16, sp24.I32, sp24.B_KMAJOR, sp24.TILED, None) == DTYPE
+    assert f(V, META, B, D, 0, N, K, K, N, sp24.BF16, sp24.BF16, sp24.B_KMAJOR, sp24.TILED, None) == OK     # empty
+    header = open(HEADER).read()
+    assert "#define SP24_STATIC_SCRATCH_BYTES (8u << 20)" in header and sp24.STATIC_SCRATCH_BYTES == 8 << 20
