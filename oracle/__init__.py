@@ -51,6 +51,7 @@ def _load():
         lib.sp24o_permute_columns.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_permute_rows.argtypes = [vp, vp, vp, i64, i64, i32]
         lib.sp24o_retained_magnitude.argtypes = [vp, vp, i64, i64, i32, vp]
+        lib.sp24o_permute_search.argtypes = [vp, vp, i64, i64, i32, i32]
         f32 = ctypes.c_float
         lib.sp24o_dequant_f64.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32]
         lib.sp24o_requant_i8.argtypes = [vp, vp, i64, i64, vp, f32, vp, i32, f32]
@@ -192,6 +193,21 @@ def retained_magnitude(A, dtype, perm=None):
     if rc:
         raise ValueError(f"oracle retained_magnitude failed ({rc})")
     return float(out[0])
+
+
+def permute_search(A, dtype, sweeps=1, perm=None):
+    """Sec. 4.1 Step 2 (the search the paper defers): a column order, found by a bounded pairwise exchange between
+    groups of four starting from perm (default: the columns as they are), under which 2:4 pruning keeps at least as
+    much magnitude.  Returns the new order (int32 [K])."""
+    _check(A, dtype)
+    K = A.shape[1]
+    perm = np.arange(K, dtype=np.int32) if perm is None else np.array(perm, dtype=np.int32)
+    if perm.shape != (K,):
+        raise ValueError("perm must hold K entries")
+    rc = _load().sp24o_permute_search(_ptr(A), _ptr(perm), A.shape[0], K, _TYPES[dtype], int(sweeps))
+    if rc:
+        raise ValueError(f"oracle permute_search failed ({rc})")
+    return perm
 
 
 def gemm(P, B, dtype):

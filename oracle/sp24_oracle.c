@@ -570,6 +570,133 @@ int sp24o_retained_magnitude(const void *A, const int32_t *perm, long M, long K,
     return 0;
 }
 
+/*
+ * ---- search for a column order (Sec. 4.1, Step 2; Fig. 6) ------------------
+ * The paper states the aim -- a column order under which pruning keeps more
+ * magnitude -- and defers the method to a separate publication, so the search
+ * below is this build's own: bounded, deterministic, and never worse than
+ * the order it starts from.
+ *
+ * The order perm is read as K/4 groups of four columns (group g = perm[4g] ..
+ * perm[4g+3]).  The score of a group is the magnitude pruning keeps in it:
+ * the sum over the rows of the row's two largest magnitudes among the group's
+ * four columns (NaN counts as +infinity).  A step takes two groups g < h, i.e.
+ * eight columns in the order perm[4g..4g+3], perm[4h..4h+3], and tries the 35
+ * ways of dealing them out as two groups of four; a way is named by the three
+ * positions 0 < a < b < c that share a group with position 0, ways are visited
+ * in lexicographic order of (a, b, c) -- the first, (1, 2, 3), is the present
+ * arrangement -- and a later way replaces the best so far only with a strictly
+ * higher sum of the two scores.  The winner's columns are written back with
+ * position 0's group in g and the other in h, each in ascending position.
+ * A round r = 0, 1, ... pairs every group g whose bit r is clear with
+ * h = g + 2^r (where h exists); the pairs of a round are disjoint.  A sweep is
+ * the rounds r = 0 .. ceil(log2(K/4)) - 1 in that order; `sweeps` sweeps run.
+ *
+ * Arithmetic, fixed so that the result is unique: everything in binary64; a
+ * row contributes the sum of its two largest magnitudes (one addition); the
+ * rows are added in 256 interleaved partial sums (row m into partial m mod
+ * 256, in row order) which are then added as a balanced binary tree over
+ * neighbours (partial j + partial j+1, then j + j+2, ...); the two scores of a
+ * way are added last.
+ *
+ * perm: in/out, K entries, a permutation of 0 .. K-1 (else 2).
+ */
+static double search_magnitude(const void *A, long i, int t)
+{
+    double x = elem_to_double(A, i, t);
+    return isnan(x) ? INFINITY : fabs(x);
+}
+
+static double search_group_score(const void *A, long M, long K, int t, const int32_t col[4])
+{
+    double partial[256];
+    for (int j = 0; j < 256; ++j)
+        partial[j] = 0.0;
+    for (long m = 0; m < M; ++m) {
+        double first = 0.0, second = 0.0; /* the two largest of the four magnitudes */
+        for (int i = 0; i < 4; ++i) {
+            double x = search_magnitude(A, m * K + col[i], t);
+            if (x > first) {
+                second = first;
+                first = x;
+            } else if (x > second) {
+                second = x;
+            }
+        }
+        partial[m % 256] += first + second;
+    }
+    for (int w = 1; w < 256; w *= 2)
+        for (int j = 0; j < 256; j += 2 * w)
+            partial[j] += partial[j + w];
+    return partial[0];
+}
+
+int sp24o_permute_search(const void *A, int32_t *perm, long M, long K, int t, int sweeps)
+{
+    if (esize(t) == 0 || K % 4 || sweeps < 0)
+        return 1;
+    char *seen = (char *)calloc((size_t)(K > 0 ? K : 1), 1);
+    if (!seen)
+        return 3;
+    for (long k = 0; k < K; ++k) {
+        if (perm[k] < 0 || perm[k] >= K || seen[perm[k]]) {
+            free(seen);
+            return 2;
+        }
+        seen[perm[k]] = 1;
+    }
+    free(seen);
+    const long G = K / 4;
+    int rounds = 0;
+    while (((long)1 << rounds) < G)
+        ++rounds;
+    for (int sweep = 0; sweep < sweeps; ++sweep)
+        for (int r = 0; r < rounds; ++r) {
+            const long step = (long)1 << r;
+#pragma omp parallel for schedule(dynamic)
+            for (long g = 0; g < G; ++g) {
+                const long h = g + step;
+                if ((g & step) || h >= G)
+                    continue;
+                int32_t col[8];
+                for (int i = 0; i < 4; ++i) {
+                    col[i] = perm[4 * g + i];
+                    col[4 + i] = perm[4 * h + i];
+                }
+                int best[8] = {0, 1, 2, 3, 4, 5, 6, 7}; /* positions: first four -> g, last four -> h */
+                double best_sum = 0.0;
+                int have = 0;
+                for (int a = 1; a < 8; ++a)
+                    for (int b = a + 1; b < 8; ++b)
+                        for (int c = b + 1; c < 8; ++c) {
+                            int way[8], n0 = 0, n1 = 4;
+                            for (int p = 0; p < 8; ++p) {
+                                if (p == 0 || p == a || p == b || p == c)
+                                    way[n0++] = p;
+                                else
+                                    way[n1++] = p;
+                            }
+                            int32_t c0[4], c1[4];
+                            for (int i = 0; i < 4; ++i) {
+                                c0[i] = col[way[i]];
+                                c1[i] = col[way[4 + i]];
+                            }
+                            double sum = search_group_score(A, M, K, t, c0) + search_group_score(A, M, K, t, c1);
+                            if (!have || sum > best_sum) {
+                                have = 1;
+                                best_sum = sum;
+                                memcpy(best, way, sizeof way);
+                            }
+                        }
+                for (int i = 0; i < 4; ++i) {
+                    perm[4 * g + i] = col[best[i]];
+                    perm[4 * h + i] = col[best[4 + i]];
+                }
+            }
+        }
+    return 0;
+}
+
 /* number of OpenMP threads the row loops use from now on (n >= 1); returns the previous maximum */
 int sp24o_set_threads(int n)
 {
