@@ -180,6 +180,28 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
         t = timed(fn)
         out[op] = {"us": t * 1e6, "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / PEAK_HBM,
                    "cpu_oracle_us_scaled_from_%d_rows" % rows: cpu(cfn) * 1e6}
+    # the search for a column order (one sweep from the columns as they are): time of the sweep, what it gains in
+    # retained magnitude, and the oracle's sweep on the first rows scaled to the whole matrix
+    perm_s = torch.arange(K, dtype=torch.int32, device="cuda")
+    sp24.sp24_permute_search(As[0], sweeps=1, perm=perm_s.clone())          # warm-up
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    sp24.sp24_permute_search(As[0], sweeps=1, perm=perm_s)
+    e1.record()
+    torch.cuda.synchronize()
+    srows = min(M, 64)
+    ssample = np.ascontiguousarray(A_host[:srows])
+    t0 = time.perf_counter()
+    oracle.permute_search(ssample, dt, sweeps=1)
+    t_cpu = (time.perf_counter() - t0) * M / srows
+    rounds = max(1, int(np.ceil(np.log2(K // 4))))
+    out["permute_search_one_sweep"] = {
+        "us": e0.elapsed_time(e1) * 1e3, "rounds": rounds,
+        "GBps_one_read_of_A_per_round": rounds * 1.0 * M * K * es / (e0.elapsed_time(e1) * 1e-3) / 1e9,
+        "retained_magnitude_before": float(sp24.sp24_retained_magnitude(As[0]).cpu()[0]),
+        "retained_magnitude_after": float(sp24.sp24_retained_magnitude(As[0], perm_s).cpu()[0]),
+        "cpu_oracle_us_scaled_from_%d_rows" % srows: t_cpu * 1e6}
     if dt == "i8" and not conv:
         ws = torch.full((M,), 1.0e-3, dtype=torch.float32, device="cuda")
         bs = torch.zeros(M, dtype=torch.float32, device="cuda")

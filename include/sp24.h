@@ -175,6 +175,41 @@ sp24_status sp24_retained_magnitude(const void* A, const int32_t* perm, double* 
                                     int64_t lda, sp24_dtype t, void* stream);
 
 /*
+ * Sec. 4.1, Step 2 / Fig. 6: the search for a column order under which
+ * pruning keeps more magnitude.  The paper states the aim and defers the
+ * method; this one is the library's own -- bounded, the same result on every
+ * run, and never worse than the order it starts from:
+ *   - perm (device, K int32, in/out) is read as K/4 groups of four columns;
+ *     on entry it must hold a permutation of 0 .. K-1 (0, 1, 2, ... for a
+ *     fresh search; an entry outside that range reads column 0, never out of
+ *     bounds, and the result is then unspecified);
+ *   - the score of a group is the sum over the rows of the row's two largest
+ *     magnitudes among its four columns (magnitudes as in sp24_prune, NaN
+ *     counting as +infinity);
+ *   - a step takes two groups g < h, eight columns (positions 0-3 those of
+ *     g), and tries the 35 ways of dealing them out as two groups: a way is
+ *     the positions a < b < c that share a group with position 0; ways are
+ *     visited in lexicographic order of (a, b, c), the first being the present
+ *     arrangement, and a later way wins only with a strictly higher sum of its
+ *     two scores; the winner goes back with position 0's group in g, the other
+ *     in h, both in ascending position;
+ *   - round r = 0, 1, .. pairs every group whose bit r is clear with the group
+ *     2^r further on, where that exists; a sweep is the rounds r = 0 ..
+ *     ceil(log2(K/4)) - 1; `sweeps` (0 .. 64) sweeps run, one launch per round.
+ * Sums are binary64 (exact integers for int8): a row contributes the sum of
+ * its two largest magnitudes; rows are added in 256 interleaved partial sums
+ * (row m into partial m mod 256, in row order), the partials as a balanced
+ * binary tree over neighbours, the two scores of a way last.
+ * sp24_retained_magnitude of the result is never below that of the input
+ * order.  Apply the result with sp24_permute_columns to the weights and to a
+ * K-major second operand (or sp24_permute_rows to the producing layer).
+ * A as for sp24_prune; perm 4-byte aligned, not overlapping A.  M == 0 leaves
+ * perm as it is.
+ */
+sp24_status sp24_permute_search(const void* A, int32_t* perm, int64_t M, int64_t K, int64_t lda,
+                                sp24_dtype t, int sweeps, void* stream);
+
+/*
  * Sec. 6: a pattern that satisfies the 2:4 constraint along rows and along
  * columns, so that the transposed matrix (the backward pass) can use the
  * sparse product too.  The exhaustive search the paper names, per aligned

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsp24.so")
 PROBE = os.path.join(HERE, "sp24_probe")        # stand-alone measurement of the chip's ceilings (csrc/probe.hip)
-SOURCES = ["api.hip", "prune_compress.hip", "permute.hip", "splitk.hip", "mm_simple.hip", "mm_skinny.hip", "mm_tiled.hip"] + [
+SOURCES = ["api.hip", "prune_compress.hip", "permute.hip", "permute_search.hip", "splitk.hip", "mm_simple.hip", "mm_skinny.hip", "mm_tiled.hip"] + [
     "mm_tiled_%s_%s.hip" % (i, o) for i, o in
     [("f16", "f32"), ("f16", "f16"), ("f16", "bf16"), ("bf16", "f32"), ("bf16", "f16"), ("bf16", "bf16"),
      ("i8", "i32"), ("i8", "i8"), ("i8", "f32"), ("i8", "f16"), ("i8", "bf16")]]

@@ -234,6 +234,19 @@ sp24_status sp24_retained_magnitude(const void* A, const int32_t* perm, double* 
     return launch_retained_magnitude(A, perm, total, M, K, lda, t, static_cast<hipStream_t>(stream));
 }
 
+sp24_status sp24_permute_search(const void* A, int32_t* perm, int64_t M, int64_t K, int64_t lda, sp24_dtype t, int sweeps, void* stream)
+{
+    if (!is_input_type(t)) return SP24_ERR_DTYPE;
+    if (M < 0 || !k_legal(K, t) || K > 0x7FFFFFFF || sweeps < 0 || sweeps > 64) return SP24_ERR_SHAPE;
+    int es = esize_of(t);
+    sp24_status s = check_matrix(A, M, K, lda, es);
+    if (s != SP24_OK) return s;
+    if (!perm) return SP24_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(perm) % 4 != 0) return SP24_ERR_ALIGN;
+    if (M > 0 && ranges_overlap(A, ((size_t)(M - 1) * lda + K) * es, perm, (size_t)K * 4)) return SP24_ERR_SHAPE;
+    return launch_permute_search(A, perm, M, K, lda, t, sweeps, static_cast<hipStream_t>(stream));
+}
+
 // Argument checks of every product entry point.  *empty: nothing to compute (M or N is 0).
 // x_bytes: extent of the NHWC input when a.conv.on (a.B then points at it), else unused
 static sp24_status mm_validate(const MmArgs& a, size_t x_bytes, bool* empty)

@@ -18,6 +18,7 @@ sp24_status launch_permute_rows(const void* A, const void* perm, void* P, int64_
                                 hipStream_t st);
 sp24_status launch_retained_magnitude(const void* A, const void* perm, double* out, int64_t M, int64_t K, int64_t lda, sp24_dtype t,
                                       hipStream_t st);
+sp24_status launch_permute_search(const void* A, int32_t* perm, int64_t M, int64_t K, int64_t lda, sp24_dtype t, int sweeps, hipStream_t st);
 sp24_status launch_compress_masked(const void* W, const void* meta, void* V, int64_t M, int64_t K, int64_t ldw, sp24_dtype t,
                                    sp24_layout l, hipStream_t st);
 sp24_status launch_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp, sp24_dtype t, sp24_layout l, hipStream_t st);

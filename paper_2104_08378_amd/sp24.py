@@ -50,6 +50,8 @@ def lib():
         L.sp24_permute_columns.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp]
         L.sp24_permute_rows.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp]
         L.sp24_retained_magnitude.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
+        L.sp24_permute_search.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp]
+        L.sp24_permute_search.restype = i32
         L.sp24_spmm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, vp]
         L.sp24_gemm_dense.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i32, i32, i32, vp]
         L.sp24_splitk_workspace_bytes.argtypes = [i64, i64, i64, i32]
@@ -229,6 +231,19 @@ def sp24_retained_magnitude(A, perm=None, out=None):
     _check(lib().sp24_retained_magnitude(A.data_ptr(), perm.data_ptr() if perm is not None else None, total.data_ptr(), M, K,
                                          A.stride(0), _DT[A.dtype], _stream()), "sp24_retained_magnitude")
     return total
+
+
+def sp24_permute_search(A, sweeps=1, perm=None):
+    """Search for a column order under which 2:4 pruning keeps more magnitude, starting from ``perm`` (refined in
+    place; default: a new tensor holding 0, 1, 2, ...).  Returns the int32 device tensor of K column numbers."""
+    _rowmajor(A, "A")
+    M, K = A.shape
+    if perm is None:
+        perm = torch.arange(K, dtype=torch.int32, device=A.device)
+    _perm_arg(perm, K)
+    _check(lib().sp24_permute_search(A.data_ptr(), perm.data_ptr(), M, K, A.stride(0), _DT[A.dtype], int(sweeps), _stream()),
+           "sp24_permute_search")
+    return perm
 
 
 def sp24_mask_apply(W, meta, layout="canonical", out=None):

@@ -279,3 +279,20 @@ def test_static_scratch_variant_checks_on_the_host():
     assert f(V, META, B, D, 0, N, K, K, N, sp24.BF16, sp24.BF16, sp24.B_KMAJOR, sp24.TILED, None) == OK     # empty
     header = open(HEADER).read()
     assert "#define SP24_STATIC_SCRATCH_BYTES (8u << 20)" in header and sp24.STATIC_SCRATCH_BYTES == 8 << 20
+
+
+def test_permute_search_validation():
+    f = sp24.lib().sp24_permute_search
+    A, PERM = P, P + 0x4000000
+    assert f(0, PERM, 64, 64, 64, sp24.F16, 1, None) == NULL
+    assert f(A, 0, 64, 64, 64, sp24.F16, 1, None) == NULL
+    assert f(A, PERM + 2, 64, 64, 64, sp24.F16, 1, None) == ALIGN
+    assert f(A, PERM, 64, 40, 64, sp24.F16, 1, None) == SHAPE           # K % 16
+    assert f(A, PERM, 64, 48, 64, sp24.I8, 1, None) == SHAPE            # K % 32
+    assert f(A, PERM, 64, 64, 32, sp24.F16, 1, None) == SHAPE           # lda < K
+    assert f(A, PERM, 64, 64, 64, sp24.F16, -1, None) == SHAPE
+    assert f(A, PERM, 64, 64, 64, sp24.F16, 65, None) == SHAPE
+    assert f(A, A + 64, 64, 64, 64, sp24.F16, 1, None) == SHAPE         # perm inside A
+    assert f(A, PERM, 64, 64, 64, sp24.F32, 1, None) == DTYPE
+    assert f(A, PERM, 0, 64, 64, sp24.F16, 3, None) == OK               # empty: nothing to do
+    assert f(A, PERM, 64, 64, 64, sp24.F16, 0, None) == OK              # no sweeps: nothing launched

@@ -123,3 +123,77 @@ def test_joint_permutation_leaves_the_dense_product_unchanged():
     torch.cuda.synchronize()
     assert torch.equal(D0, D1)
     assert np.array_equal(D0.cpu().numpy(), oracle.gemm(A, np.ascontiguousarray(Bt.T), "i8"))
+
+
+# --- the search for a column order: the order found must equal the oracle's entry for entry -------------------
+# rows x columns: K/4 a power of two and not (groups that sit out rounds); fewer rows than lanes, a ragged last pass
+# over the rows, several passes
+SEARCH_SHAPES = [(40, 32), (300, 48), (256, 64), (1000, 96), (17, 160), (2100, 128)]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_permute_search_order_equals_the_oracle(dtype):
+    for i, (M, K) in enumerate(SEARCH_SHAPES):
+        if dtype == "i8" and K % 32:
+            K += 16                                             # int8 needs K % 32 == 0; 48 -> 64 etc. keeps a mix of group counts
+        A = adversarial(dtype, M, K, 170 + i) if i in (1, 4) else synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=160 + i)[0]
+        Ad = to_gpu(A, dtype)
+        for sweeps in (1, 2):
+            got = sp24.sp24_permute_search(Ad, sweeps=sweeps)
+            torch.cuda.synchronize()
+            want = oracle.permute_search(A, dtype, sweeps=sweeps)
+            assert np.array_equal(got.cpu().numpy(), want), (dtype, M, K, sweeps)
+        # the figure of merit does not fall (both evaluated on the GPU), and the order is a permutation
+        before = float(sp24.sp24_retained_magnitude(Ad).cpu()[0])
+        after = float(sp24.sp24_retained_magnitude(Ad, got).cpu()[0])
+        assert sorted(got.cpu().tolist()) == list(range(K))
+        if not np.isnan(before):
+            assert after >= before * (1 - 1e-12)
+
+
+def test_permute_search_starts_from_a_given_order_and_takes_pitched_rows():
+    dtype, M, K = "bf16", 500, 96
+    A = synth.make(NAME_OF[dtype], M=M, N=16, K=K, seed=181)[0]
+    rng = np.random.default_rng(182)
+    start = rng.permutation(K).astype(np.int32)
+    big = torch.zeros((M, K + 40), dtype=torch.bfloat16, device="cuda")
+    big[:, :K] = to_gpu(A, dtype)
+    perm = dev_perm(start)
+    out = sp24.sp24_permute_search(big[:, :K], sweeps=2, perm=perm)
+    torch.cuda.synchronize()
+    assert out.data_ptr() == perm.data_ptr()                    # refined in place
+    assert np.array_equal(out.cpu().numpy(), oracle.permute_search(A, dtype, sweeps=2, perm=start))
+    # zero sweeps and an empty matrix leave the order alone
+    perm2 = dev_perm(start)
+    sp24.sp24_permute_search(to_gpu(A, dtype), sweeps=0, perm=perm2)
+    sp24.sp24_permute_search(to_gpu(A, dtype)[:0], sweeps=3, perm=perm2)
+    torch.cuda.synchronize()
+    assert np.array_equal(perm2.cpu().numpy(), start)
+
+
+def test_permute_search_ties_heavy_int8_and_equal_columns():
+    # few distinct magnitudes: most ways tie and the first must win; all columns equal: nothing moves
+    rng = np.random.default_rng(183)
+    A = rng.integers(-2, 3, size=(700, 128)).astype(np.int8)
+    got = sp24.sp24_permute_search(to_gpu(A, "i8"), sweeps=2)
+    E = np.full((64, 64), 7, dtype=np.int8)
+    same = sp24.sp24_permute_search(to_gpu(E, "i8"), sweeps=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.permute_search(A, "i8", sweeps=2))
+    assert np.array_equal(same.cpu().numpy(), np.arange(64))
+
+
+def test_permute_search_leaves_the_sparse_product_path_consistent():
+    # the order found, applied to the weights' columns and to the K-major second operand alike, gives a pruned
+    # product that the oracle reproduces from the same permuted operands (Sec. 4.1: the result of the layer is kept)
+    dtype, M, K, N = "i8", 128, 256, 64
+    A, Bt = synth.make(NAME_OF[dtype], M=M, N=N, K=K, seed=184)
+    Ad, Bd = to_gpu(A, dtype), to_gpu(Bt, dtype)
+    perm = sp24.sp24_permute_search(Ad, sweeps=1)
+    Ap, Bp = sp24.sp24_permute_columns(Ad, perm), sp24.sp24_permute_columns(Bd, perm)
+    V, meta = sp24.sp24_compress(Ap, layout="tiled")
+    D = sp24.sp24_spmm(V, meta, Bp, torch.int32, layout="tiled")
+    torch.cuda.synchronize()
+    p = perm.cpu().numpy()
+    ref = oracle.gemm(oracle.prune(np.ascontiguousarray(A[:, p]), dtype), np.ascontiguousarray(Bt[:, p].T), dtype)
+    assert np.array_equal(D.cpu().numpy(), ref)
