@@ -7,7 +7,8 @@ check and the benchmark's cpu_baseline leg may import this package; it shares
 nothing with the GPU library and does not import it.
 
 Arrays are numpy: 16-bit floats travel as ``uint16`` bit patterns, int8 as
-``int8``.  ``dtype`` is one of "f16", "bf16", "i8".
+``int8``.  ``dtype`` is one of "f16", "bf16", "i8", "f8" (the 8-bit float with 4 exponent
+and 3 fraction bits, as ``uint8`` bit patterns).
 """
 import ctypes
 import os
@@ -18,7 +19,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sp24_oracle.c")
 _LIB = os.path.join(_HERE, "libsp24_oracle.so")
-_TYPES = {"f16": 0, "bf16": 1, "i8": 2}
+_TYPES = {"f16": 0, "bf16": 1, "i8": 2, "f8": 3}
 _lib = None
 _decode_tables = {}
 
@@ -59,12 +60,14 @@ def _load():
         lib.sp24o_f16_to_double.restype = ctypes.c_double
         lib.sp24o_bf16_to_double.argtypes = [ctypes.c_uint16]
         lib.sp24o_bf16_to_double.restype = ctypes.c_double
+        lib.sp24o_f8_to_double.argtypes = [ctypes.c_uint8]
+        lib.sp24o_f8_to_double.restype = ctypes.c_double
         _lib = lib
     return _lib
 
 
 def _np_dtype(dtype):
-    return np.int8 if dtype == "i8" else np.uint16
+    return np.int8 if dtype == "i8" else np.uint8 if dtype == "f8" else np.uint16
 
 
 def _check(a, dtype, ndim=2):
@@ -300,6 +303,10 @@ def to_double(bits, dtype):
     """Exact value of 16-bit patterns (or int8) as float64, element by element."""
     if dtype == "i8":
         return bits.astype(np.float64)
+    if dtype == "f8":
+        if dtype not in _decode_tables:
+            _decode_tables[dtype] = np.array([_load().sp24o_f8_to_double(b) for b in range(256)], dtype=np.float64)
+        return _decode_tables[dtype][np.asarray(bits, dtype=np.uint8)]
     if dtype not in _decode_tables:   # the C decoder applied once to each of the 65536 patterns
         fn = _load().sp24o_f16_to_double if dtype == "f16" else _load().sp24o_bf16_to_double
         _decode_tables[dtype] = np.array([fn(b) for b in range(65536)], dtype=np.float64)

@@ -12,8 +12,11 @@
  * K contiguous.  Groups are 4 consecutive elements of a row, aligned to
  * column 0.  V is the M x K/2 array of kept values, meta the 2-bit positions.
  *
- * Element types: 0 = fp16 (IEEE binary16), 1 = bf16, 2 = int8.  The 16-bit
- * types are passed as raw uint16_t bit patterns.
+ * Element types: 0 = fp16 (IEEE binary16), 1 = bf16, 2 = int8, 3 = fp8 (the
+ * 8-bit float with 4 exponent and 3 fraction bits, no infinities; one of the
+ * further input formats of Table 1's kind that the target chip multiplies in
+ * its sparse form).  The float types are passed as raw bit patterns
+ * (uint16_t, uint8_t for fp8).
  *
  * Readings where the paper is silent (all listed again in the design notes):
  *   - ties in magnitude: the lower column index wins (is kept);
@@ -36,7 +39,7 @@
 #include <omp.h>
 #endif
 
-enum { T_F16 = 0, T_BF16 = 1, T_I8 = 2 };
+enum { T_F16 = 0, T_BF16 = 1, T_I8 = 2, T_F8 = 3 };
 
 /* ---- exact conversion of the 16-bit storage formats to double ---------- */
 
@@ -72,8 +75,30 @@ double sp24o_bf16_to_double(uint16_t b)
     return sign ? -v : v;
 }
 
+/*
+ * 8-bit float, 1 sign, 4 exponent (bias 7), 3 fraction bits, the "finite" variant: no infinities, the one NaN is
+ * exponent and fraction all ones, so the largest finite value is 1.75 * 2^8 = 448; exponent 0 holds the
+ * subnormals f * 2^-9.
+ */
+double sp24o_f8_to_double(uint8_t b)
+{
+    int sign = (b >> 7) & 1;
+    int e = (b >> 3) & 0xf;
+    int f = b & 0x7;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -9);
+    else if (e == 15 && f == 7)
+        v = NAN;
+    else
+        v = ldexp(1.0 + (double)f / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
 static double elem_to_double(const void *p, long i, int t)
 {
+    if (t == T_F8)
+        return sp24o_f8_to_double(((const uint8_t *)p)[i]);
     if (t == T_F16)
         return sp24o_f16_to_double(((const uint16_t *)p)[i]);
     if (t == T_BF16)
@@ -137,12 +162,12 @@ static void group_keep(const void *A, long base, int t, int keep[4])
     select_two(x, keep);
 }
 
-static long esize(int t) { return t == T_I8 ? 1 : 2; }
+static long esize(int t) { return (t == T_I8 || t == T_F8) ? 1 : (t == T_F16 || t == T_BF16) ? 2 : 0; }
 
 /* ---- O1: prune (dense -> dense, Sec. 4.1 Step 2; pattern of Sec. 3) ---- */
 int sp24o_prune(const void *A, void *P, long M, long K, int t)
 {
-    if (K % 4 || t < 0 || t > 2)
+    if (K % 4 || esize(t) == 0)
         return 1;
     long es = esize(t);
     for (long m = 0; m < M; ++m)
@@ -165,7 +190,7 @@ int sp24o_prune(const void *A, void *P, long M, long K, int t)
 /* ---- O2: compress (Sec. 3.1: value array + 2-bit positions) ------------ */
 int sp24o_compress(const void *A, void *V, uint8_t *meta, long M, long K, int t)
 {
-    if (K % 8 || t < 0 || t > 2)
+    if (K % 8 || esize(t) == 0)
         return 1;
     long es = esize(t);
     memset(meta, 0, (size_t)(M * K / 8));
@@ -189,7 +214,7 @@ int sp24o_compress(const void *A, void *V, uint8_t *meta, long M, long K, int t)
 /* ---- O3: decompress (inverse scatter) ---------------------------------- */
 int sp24o_decompress(const void *V, const uint8_t *meta, void *P, long M, long K, int t)
 {
-    if (K % 8 || t < 0 || t > 2)
+    if (K % 8 || esize(t) == 0)
         return 1;
     long es = esize(t);
     memset(P, 0, (size_t)(M * K * es));
@@ -210,14 +235,14 @@ int sp24o_decompress(const void *V, const uint8_t *meta, void *P, long M, long K
  * ---- O4: the product, by definition (Sec. 3.2, Fig. 2) -------------------
  * D[m][n] = sum_k P[m][k] * B[k][n] over the full, decompressed P (zeros are
  * multiplied out, not skipped).  B is K x N row-major, D is M x N row-major.
- * 16-bit inputs are converted exactly to double and accumulated in double;
+ * Float inputs (16-bit, fp8) are converted exactly to double and accumulated in double;
  * int8 accumulates in int32.  The k loop runs in ascending order for every
  * output; rows are independent, which is all the OpenMP pragma uses.
  */
-int sp24o_gemm_f64(const uint16_t *P, const uint16_t *B, double *D,
+int sp24o_gemm_f64(const void *P, const void *B, double *D,
                    long M, long N, long K, int t)
 {
-    if (t != T_F16 && t != T_BF16)
+    if (t != T_F16 && t != T_BF16 && t != T_F8)
         return 1;
 #pragma omp parallel for schedule(static)
     for (long m = 0; m < M; ++m) {
@@ -287,10 +312,10 @@ int sp24o_gemm_i32(const int8_t *P, const int8_t *B, int32_t *D,
                 }                                                                            \
     return 0;
 
-int sp24o_conv2d_f64(const uint16_t *P, const uint16_t *X, double *D, long M, long n_img,
+int sp24o_conv2d_f64(const void *P, const void *X, double *D, long M, long n_img,
                      long H, long W, long C, long R, long S, long ph, long pw, long sh, long sw, int t)
 {
-    if (t != T_F16 && t != T_BF16)
+    if (t != T_F16 && t != T_BF16 && t != T_F8)
         return 1;
 #define LP(i) elem_to_double(P, (i), t)
 #define LX(i) elem_to_double(X, (i), t)

@@ -35,11 +35,31 @@ def f64_to_bf16_bits(x):
     return out
 
 
+def f64_to_f8_bits(x):
+    """Round-to-nearest-even to the 8-bit float with 4 exponent bits (bias 7) and 3 fraction bits (no infinities,
+    largest finite value 448); values beyond it saturate to +-448, NaN becomes the one NaN pattern.  uint8 bits."""
+    x = np.asarray(x, dtype=np.float64)
+    a = np.minimum(np.abs(np.where(np.isnan(x), 0.0, x)), 448.0)
+    e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.clip(e, -6, 8)                                  # exponent of the binade the value is rounded in
+    q = np.rint(a / np.exp2(e - 3))                        # in units of the binade's spacing; rint rounds half to even
+    v = np.minimum(q * np.exp2(e - 3), 448.0)              # q = 16 moves up one binade by itself
+    e2 = np.clip(np.floor(np.log2(np.where(v > 0, v, 1.0))), -6, 8)
+    normal = v >= 2.0 ** -6
+    frac = np.where(normal, np.rint((v / np.exp2(e2) - 1.0) * 8.0), np.rint(v * 512.0)).astype(np.uint8)
+    expo = np.where(normal, e2 + 7, 0).astype(np.uint8)
+    bits = (expo << 3) | frac
+    bits = np.where(np.signbit(x), bits | 0x80, bits).astype(np.uint8)
+    return np.where(np.isnan(x), np.uint8(0x7F), bits).astype(np.uint8)
+
+
 def to_bits(x, dtype):
     if dtype == "f16":
         return f64_to_f16_bits(x)
     if dtype == "bf16":
         return f64_to_bf16_bits(x)
+    if dtype == "f8":
+        return f64_to_f8_bits(x)
     raise ValueError(dtype)
 
 

@@ -867,3 +867,77 @@ def test_permute_search_score_arithmetic_is_the_stated_one():
         if best is None or s > best[0]:
             best = (s, list(first) + rest)
     assert list(oracle.permute_search(A, "bf16", sweeps=1)) == best[1]
+
+
+# --- the 8-bit float input type (one of the further formats of the kind Table 1 lists; its encoding is the
+# published 4-exponent-bit, 3-fraction-bit "finite" one) ------------------------------------------------------
+def f8_value(bits):
+    """Independent decode through torch's own float8 type."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint8)).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+
+
+def test_f8_decode_matches_torch_for_every_pattern_and_the_closed_forms():
+    allbits = np.arange(256, dtype=np.uint8)
+    got, want = oracle.to_double(allbits, "f8"), f8_value(allbits)
+    assert np.array_equal(np.isnan(got), np.isnan(want)) and np.isnan(got).sum() == 2          # 0x7F and 0xFF only
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok], want[ok]) and np.array_equal(np.signbit(got[ok]), np.signbit(want[ok]))
+    # literals: 1.0, the largest finite value (1.75 * 2^8), the smallest subnormal and normal, minus zero
+    assert got[0x38] == 1.0 and got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
+    assert got[0x80] == 0.0 and np.signbit(got[0x80]) and not np.isinf(got).any()
+
+
+def test_f8_rounding_of_inputs_is_nearest_even_and_saturating():
+    rng = np.random.default_rng(41)
+    x = np.concatenate([rng.standard_normal(50000) * np.exp(rng.normal(0, 3, 50000)),
+                        [0.0, -0.0, 2.0 ** -10, 3 * 2.0 ** -10, 2.0 ** -9 * 2.5, 15.0, 15.5, 17.0, 18.0, 447.9, 460.0, -1e9]])
+    b = synth.to_bits(x, "f8")
+    import torch
+    want = torch.from_numpy(np.clip(x, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(b, want)
+    # ties: 2^-10 is half the smallest subnormal -> 0 (even); 3 * 2^-10 -> 2 * 2^-9; 17 is halfway 16 .. 18 -> 16
+    v = oracle.to_double(synth.to_bits(np.array([2.0 ** -10, 3 * 2.0 ** -10, 17.0, 15.5, 460.0]), "f8"), "f8")
+    assert list(v) == [0.0, 2.0 ** -8, 16.0, 16.0, 448.0]
+
+
+def test_f8_prune_equals_brute_force_and_compress_round_trips():
+    # every group over a pool with ties, both zeros, the largest finite value and the NaN pattern (which ranks highest)
+    pool = [0x00, 0x80, 0x01, 0x81, 0x38, 0xB8, 0x3C, 0x7E, 0x7F]
+    groups = np.array(list(itertools.product(pool, repeat=4)), dtype=np.uint8)
+    A = np.ascontiguousarray(np.concatenate([groups, np.zeros_like(groups)], axis=1))
+    P = oracle.prune(A, "f8")
+    V, meta = oracle.compress(A, "f8")
+    val = oracle.to_double(A, "f8")
+    for row in range(0, len(groups), 5):
+        mags = [float("inf") if np.isnan(v) else abs(v) for v in val[row, :4]]
+        nan_rank = [2 if np.isnan(v) else 1 for v in val[row, :4]]     # NaN above everything, infinity does not exist here
+        best = None
+        for pair in itertools.combinations(range(4), 2):
+            key = (sum(nan_rank[i] == 2 for i in pair), sum(mags[i] for i in pair if nan_rank[i] != 2))
+            if best is None or key > best[0]:
+                best = (key, pair)
+        i0, i1 = best[1]
+        want = np.zeros(8, dtype=np.uint8)
+        want[i0], want[i1] = A[row, i0], A[row, i1]
+        assert np.array_equal(P[row], want), (groups[row], P[row])
+        assert meta[row, 0] & 0xF == (i0 | (i1 << 2)) and V[row, 0] == A[row, i0] and V[row, 1] == A[row, i1]
+    assert np.array_equal(oracle.decompress(V, meta, "f8"), P)
+    assert np.array_equal(oracle.prune(P, "f8"), P)
+    assert V.nbytes + meta.nbytes == A.size * (1 / 2 + 1 / 8)          # Sec. 3.1: 38 % saved for an 8-bit type
+
+
+def test_f8_product_matches_numpy_float64_matmul():
+    rng = np.random.default_rng(42)
+    A = synth.to_bits(rng.standard_normal((24, 64)) * 0.5, "f8")
+    Bt = synth.to_bits(rng.standard_normal((40, 64)), "f8")
+    P = oracle.prune(A, "f8")
+    got = oracle.gemm(P, np.ascontiguousarray(Bt.T), "f8")
+    want = f8_value(P) @ f8_value(Bt).T
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
+    V, meta = oracle.compress(A, "f8")
+    assert np.array_equal(oracle.spmm(V, meta, np.ascontiguousarray(Bt.T), "f8"), got)
+    # one-hot second operand picks single columns of the pruned matrix
+    E = np.zeros((64, 64), dtype=np.uint8)
+    E[np.arange(64), np.arange(64)] = 0x38
+    assert np.array_equal(oracle.gemm(P, E, "f8"), f8_value(P))
