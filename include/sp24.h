@@ -33,7 +33,7 @@
  *     SP24_ERR_ALIGN.  (The fast product kernels are chosen when B and D rows
  *     are 16-byte aligned too -- for N-major B also N * element size a
  *     multiple of 16; other cases run a general kernel.)
- *   - K must be a multiple of 16 for 16-bit types and of 32 for int8
+ *   - K must be a multiple of 16 for 16-bit types and of 32 for the 8-bit types
  *     (the dimension rule of Sec. 3.2 / Sec. 4.2, applied to the inner
  *     dimension), else SP24_ERR_SHAPE.  M and N may be any positive value; a
  *     zero M or N is accepted and does nothing.
@@ -67,7 +67,12 @@ typedef enum {
     SP24_BF16 = 1, /* bfloat16                                        */
     SP24_I8 = 2,   /* signed 8-bit integer (as output: sp24_*_i8_scaled only) */
     SP24_F32 = 3,  /* output only                                     */
-    SP24_I32 = 4   /* output only (required for SP24_I8 inputs)       */
+    SP24_I32 = 4,  /* output only (required for SP24_I8 inputs)       */
+    SP24_F8 = 5    /* input only: 8-bit float, 1 sign, 4 exponent (bias 7), 3 fraction bits, no
+                      infinities, NaN = 0x7F / 0xFF, largest finite value 448.  Not one of the
+                      formats of the paper's Table 1: the further input format this chip's
+                      sparse matrix instruction takes; products accumulate in fp32 like the
+                      16-bit types and are written as SP24_F32, SP24_F16 or SP24_BF16 */
 } sp24_dtype;
 
 /*

@@ -17,7 +17,7 @@ PROBE = os.path.join(HERE, "sp24_probe")        # stand-alone measurement of the
 SOURCES = ["api.hip", "prune_compress.hip", "permute.hip", "permute_search.hip", "splitk.hip", "mm_simple.hip", "mm_skinny.hip", "mm_tiled.hip"] + [
     "mm_tiled_%s_%s.hip" % (i, o) for i, o in
     [("f16", "f32"), ("f16", "f16"), ("f16", "bf16"), ("bf16", "f32"), ("bf16", "f16"), ("bf16", "bf16"),
-     ("i8", "i32"), ("i8", "i8"), ("i8", "f32"), ("i8", "f16"), ("i8", "bf16")]]
+     ("i8", "i32"), ("i8", "i8"), ("i8", "f32"), ("i8", "f16"), ("i8", "bf16"), ("f8", "f32"), ("f8", "f16"), ("f8", "bf16")]]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # hipcc must not form packed-fp32 instructions by itself on this target

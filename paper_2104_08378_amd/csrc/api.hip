@@ -16,12 +16,12 @@ static __device__ __align__(256) unsigned char scratch[SP24_STATIC_SCRATCH_BYTES
 
 namespace {
 
-bool is_input_type(sp24_dtype t) { return t == SP24_F16 || t == SP24_BF16 || t == SP24_I8; }
+bool is_input_type(sp24_dtype t) { return t == SP24_F16 || t == SP24_BF16 || t == SP24_I8 || t == SP24_F8; }
 bool is_layout(sp24_layout l) { return l == SP24_LAYOUT_CANONICAL || l == SP24_LAYOUT_TILED; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Dimension rule of Sec. 3.2 / Sec. 4.2 on the inner dimension.
-bool k_legal(int64_t K, sp24_dtype t) { return K > 0 && K % (t == SP24_I8 ? 32 : 16) == 0; }
+bool k_legal(int64_t K, sp24_dtype t) { return K > 0 && K % (esize_of(t) == 1 ? 32 : 16) == 0; }
 
 bool layout_fits(int64_t M, int64_t K, sp24_layout l)
 {

@@ -22,8 +22,13 @@ typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 
 __host__ __device__ inline int esize_of(sp24_dtype t)
 {
-    return (t == SP24_I8) ? 1 : (t == SP24_F16 || t == SP24_BF16) ? 2 : 4;
+    return (t == SP24_I8 || t == SP24_F8) ? 1 : (t == SP24_F16 || t == SP24_BF16) ? 2 : 4;
 }
+
+// one-byte input types: they share every data path (64 columns of A per 32x32 sparse instruction, 32 bytes of
+// compressed values per row and 64 columns); they differ in the magnitude that pruning compares and in the
+// matrix-core instruction (integer or float accumulation)
+template <int DT> constexpr bool is8 = (DT == SP24_I8 || DT == SP24_F8);
 
 // ---------------------------------------------------------------------------
 // Selection rule (Sec. 4.1 Step 2: drop the two smallest magnitudes of four).
@@ -44,6 +49,19 @@ __device__ __forceinline__ uint32_t mag_key8(uint32_t byte)
 {
     int v = (int)(int8_t)byte;
     return (uint32_t)(v < 0 ? -v : v);
+}
+
+// 8-bit float (4 exponent bits, bias 7, 3 fraction bits, no infinities): the bit pattern without its sign orders
+// the magnitudes, and the one NaN pattern (0x7F) is the largest key by itself
+__device__ __forceinline__ uint32_t mag_key_f8(uint32_t byte) { return byte & 0x7Fu; }
+
+// its magnitude as a number (NaN counts as +infinity, as for the other float types where sums of magnitudes are formed)
+__device__ __forceinline__ float magnitude_f8(uint32_t byte)
+{
+    const uint32_t a = byte & 0x7Fu, e = a >> 3, f = a & 7u;
+    if (a == 0x7Fu) return __builtin_inff();
+    if (e == 0u) return (float)f * 0.001953125f;                       // subnormal: f * 2^-9
+    return __uint_as_float(((e + 120u) << 23) | (f << 20));             // 2^(e - 7) * (1 + f / 8)
 }
 
 // Returns the 4-bit keep mask (bit i set = column i survives); exactly two bits set.

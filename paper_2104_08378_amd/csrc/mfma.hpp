@@ -15,7 +15,7 @@
 //       idx: 4 codes x 4 bits (pos0 | pos1<<2), code p for values 2p, 2p+1,
 //          taken from bits 0..15 (abid = 0) or 16..31 (abid = 1) of the lane;
 //       B: 16 values per lane: value e is row k = 16*(e/8) + 8*q + e%8.
-//   sparse v_smfmac_i32_32x32x64_i8 (A is 32 x 64, stored 32 x 32):
+//   sparse v_smfmac_i32_32x32x64_i8 and v_smfmac_f32_32x32x64_fp8_fp8 (A is 32 x 64, stored 32 x 32):
 //       A: 16 compressed values per lane = 8 groups: columns 32*q .. 32*q+31;
 //       idx: 8 codes in all 32 bits of the lane;
 //       B: 32 values per lane: value e is row k = 32*(e/16) + 16*q + e%16.
@@ -38,6 +38,8 @@ __device__ __forceinline__ typename acc_of<DT>::type smfmac32(const int4v& a, co
         return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half16, b), c, idx, 0, ABID);
     else if constexpr (DT == SP24_BF16)
         return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf16x16, b), c, idx, 0, ABID);
+    else if constexpr (DT == SP24_F8)
+        return __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(a, b, c, idx, 0, ABID);
     else
         return __builtin_amdgcn_smfmac_i32_32x32x64_i8(a, b, c, idx, 0, ABID);
 }
@@ -49,7 +51,14 @@ __device__ __forceinline__ typename acc_of<DT>::type mfma32(const int4v& a, cons
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
     else if constexpr (DT == SP24_BF16)
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), c, 0, 0, 0);
-    else
+    else if constexpr (DT == SP24_F8) {
+        // the 16 bytes per lane are two operands of the 8-byte form; which 8 values of K a lane holds does not
+        // matter as long as A and B pair up the same bytes
+        typedef long long2v __attribute__((ext_vector_type(2)));
+        const long2v a2 = __builtin_bit_cast(long2v, a), b2 = __builtin_bit_cast(long2v, b);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[0], b2[0], c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[1], b2[1], c, 0, 0, 0);
+    } else
         return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 

@@ -63,7 +63,7 @@ __device__ __forceinline__ void gather_conv(const MmArgs& a, int64_t k0, int64_t
 template <int DT, int OUT, bool SPARSE>
 __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
 {
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     using acc_t = typename acc_of<DT>::type;
     const int lane = threadIdx.x, r = lane & 31, q = lane >> 5;
     const int64_t row0 = (int64_t)blockIdx.y * 32, col0 = (int64_t)blockIdx.x * 32;
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
                     if (m_ok && byte < K / 8) codes |= (uint32_t)mrow[byte] << (8 * b);
                 }
             }
-            if constexpr (DT == SP24_I8) {
+            if constexpr (is8<DT>) {
                 int4v av;
                 int8v bv;
                 int tmp[8];
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(64) void k_mm_simple(MmArgs a)
                 }
             }
         } else {
-            constexpr int PERK = (DT == SP24_I8) ? 32 : 16; // k per dense instruction
+            constexpr int PERK = is8<DT> ? 32 : 16; // k per dense instruction (the 8-bit float form takes its 16 bytes as two)
 #pragma unroll
             for (int j = 0; j < 64 / PERK; ++j) {
                 int4v av, bv;
@@ -175,6 +175,11 @@ sp24_status launch_mm_simple(const MmArgs& a, hipStream_t st)
         if (a.out == SP24_F32) return launch_t<SP24_I8, SP24_F32>(a, st);
         if (a.out == SP24_F16) return launch_t<SP24_I8, SP24_F16>(a, st);
         return launch_t<SP24_I8, SP24_BF16>(a, st);
+    }
+    if (a.in == SP24_F8) {
+        if (a.out == SP24_F32) return launch_t<SP24_F8, SP24_F32>(a, st);
+        if (a.out == SP24_F16) return launch_t<SP24_F8, SP24_F16>(a, st);
+        return launch_t<SP24_F8, SP24_BF16>(a, st);
     }
     if (a.in == SP24_F16) {
         if (a.out == SP24_F32) return launch_t<SP24_F16, SP24_F32>(a, st);

@@ -30,9 +30,9 @@ constexpr int kSkinnyUnroll = 4;   // tiles whose loads are in flight together, 
 template <int DT, int OUT, bool SPARSE>
 __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
 {
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     constexpr int TB = 64 * ES;                      // bytes of a B (or dense A) row per 64-column tile
-    constexpr int NI = SPARSE ? ((DT == SP24_I8) ? 1 : 2) : TB / 32;   // matrix-core instructions per tile
+    constexpr int NI = SPARSE ? (is8<DT> ? 1 : 2) : TB / 32;   // matrix-core instructions per tile
     using acc_t = typename acc_of<DT>::type;
     __shared__ uint32_t red[kSkinnyWaves][16][64];
 
@@ -84,14 +84,14 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
                 const int64_t tile = tile_first + kb;
                 if (canonical) {
                     codes[u] = ok ? *reinterpret_cast<const uint32_t*>(mrow + kb * 8) : 0u;
-                    if constexpr (DT == SP24_I8) va[u][0] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 32) : zero4;
+                    if constexpr (is8<DT>) va[u][0] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 32) : zero4;
                     else {
                         va[u][0] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 64) : zero4;
                         va[u][1] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 64 + 16) : zero4;
                     }
                 } else {
                     codes[u] = ok ? Mp[tile * 64 + lane] : 0u;
-                    if constexpr (DT == SP24_I8) va[u][0] = ok ? Vp[tile * 64 + lane] : zero4;
+                    if constexpr (is8<DT>) va[u][0] = ok ? Vp[tile * 64 + lane] : zero4;
                     else {
                         va[u][0] = ok ? Vp[(tile * 2) * 64 + lane] : zero4;
                         va[u][1] = ok ? Vp[(tile * 2 + 1) * 64 + lane] : zero4;
@@ -117,8 +117,8 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
                 // instruction j takes the pieces at K-byte offsets (int8) 32h + 16q, (16-bit) 64h + 32j + 16q
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
-                    const uint4v lo = (DT == SP24_I8) ? vb[u][0] : vb[u][j];
-                    const uint4v hi = (DT == SP24_I8) ? vb[u][1] : vb[u][2 + j];
+                    const uint4v lo = is8<DT> ? vb[u][0] : vb[u][j];
+                    const uint4v hi = is8<DT> ? vb[u][1] : vb[u][2 + j];
                     int8v bv;
                     bv[0] = lo[0]; bv[1] = lo[1]; bv[2] = lo[2]; bv[3] = lo[3];
                     bv[4] = hi[0]; bv[5] = hi[1]; bv[6] = hi[2]; bv[7] = hi[3];
@@ -186,6 +186,11 @@ sp24_status launch_mm_skinny(const MmArgs& a, hipStream_t st, bool* handled)
         if (a.out == SP24_F32) return run_skinny<SP24_I8, SP24_F32>(a, st);
         if (a.out == SP24_F16) return run_skinny<SP24_I8, SP24_F16>(a, st);
         return run_skinny<SP24_I8, SP24_BF16>(a, st);
+    }
+    if (a.in == SP24_F8) {
+        if (a.out == SP24_F32) return run_skinny<SP24_F8, SP24_F32>(a, st);
+        if (a.out == SP24_F16) return run_skinny<SP24_F8, SP24_F16>(a, st);
+        return run_skinny<SP24_F8, SP24_BF16>(a, st);
     }
     if (a.in == SP24_F16) {
         if (a.out == SP24_F32) return run_skinny<SP24_F16, SP24_F32>(a, st);

@@ -17,6 +17,9 @@ sp24_status tiled_i8_i8(const MmArgs& a, hipStream_t st);
 sp24_status tiled_i8_f32(const MmArgs& a, hipStream_t st);
 sp24_status tiled_i8_f16(const MmArgs& a, hipStream_t st);
 sp24_status tiled_i8_bf16(const MmArgs& a, hipStream_t st);
+sp24_status tiled_f8_f32(const MmArgs& a, hipStream_t st);
+sp24_status tiled_f8_f16(const MmArgs& a, hipStream_t st);
+sp24_status tiled_f8_bf16(const MmArgs& a, hipStream_t st);
 
 constexpr int kStepBytes = 128;   // bytes of one operand row consumed per step (kRowBytes of the kernels)
 
@@ -56,6 +59,11 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
         if (a.out == SP24_F32) return tiled_i8_f32(a, st);
         if (a.out == SP24_F16) return tiled_i8_f16(a, st);
         return tiled_i8_bf16(a, st);
+    }
+    if (a.in == SP24_F8) {
+        if (a.out == SP24_F32) return tiled_f8_f32(a, st);
+        if (a.out == SP24_F16) return tiled_f8_f16(a, st);
+        return tiled_f8_bf16(a, st);
     }
     if (a.in == SP24_F16) {
         if (a.out == SP24_F32) return tiled_f16_f32(a, st);

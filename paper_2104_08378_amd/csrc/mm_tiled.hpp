@@ -417,7 +417,7 @@ template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, int BSRC>
 __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr bool CONV = BSRC == 1, NMAJ = BSRC == 2;
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     constexpr int BK = kRowBytes / ES;        // K elements per step
     constexpr int T64 = BK / 64;              // 32x64 A tiles per step and row block (2 for int8, 1 for 16-bit)
     constexpr int NW = WM * WN;
@@ -597,13 +597,13 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             xa[i] = *reinterpret_cast<const int4v*>(base + va_off + (i * 2 + j) * 1024);
-            if (with_codes) xm[i] = *reinterpret_cast<const int*>(base + ma_off + (i * T64 + (DT == SP24_I8 ? j : 0)) * 256);
+            if (with_codes) xm[i] = *reinterpret_cast<const int*>(base + ma_off + (i * T64 + (is8<DT> ? j : 0)) * 256);
         }
     };
     auto read_frag = [&](const uint8_t* base, int t, int8v& bv) {
         const int j = t / TN, nj = t % TN;
         // K-byte offset of the two pieces of instruction j: (int8) 64j + 32h + 16q, (16-bit) 64h + 32j + 16q
-        const int c2lo = (DT == SP24_I8) ? 2 * j : j, c2hi = (DT == SP24_I8) ? 2 * j + 1 : 2 + j;
+        const int c2lo = is8<DT> ? 2 * j : j, c2hi = is8<DT> ? 2 * j + 1 : 2 + j;
         uint4v lo, hi;
         if constexpr (NMAJ) {
             lo = b_nm.piece(base, c2lo, nj);
@@ -661,11 +661,11 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
             }
             if (t + 2 < NF) read_frag(cur, t + 2, f[(t + 2) % 3]);
             else read_frag(nxt, t + 2 - NF, f_first[t + 2 - NF]);
-            if (t == 0) read_a(cur, 1, av[1], mv[1], DT == SP24_I8);
+            if (t == 0) read_a(cur, 1, av[1], mv[1], is8<DT>);
             if (t == T1) read_a(nxt, 0, a_first, m_first, true);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t % 3], acc[i][nj], mv[j][i]);
+                if constexpr (is8<DT>) acc[i][nj] = smfmac32<DT, 0>(av[j][i], f[t % 3], acc[i][nj], mv[j][i]);
                 else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], f[t % 3], acc[i][nj], mv[0][i]);
                 else acc[i][nj] = smfmac32<DT, 1>(av[1][i], f[t % 3], acc[i][nj], mv[0][i]);
                 if (t < T1) dma_slot(2 * TM + t * TM + i, (u + NS - 1) % NS);
@@ -718,7 +718,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
         int4v av[2][TM];
         int mv[2][TM];
         read_a(lds_all, 0, av[0], mv[0], true);
-        read_a(lds_all, 1, av[1], mv[1], DT == SP24_I8);
+        read_a(lds_all, 1, av[1], mv[1], is8<DT>);
 #pragma unroll
         for (int t = 0; t < NF; ++t) {
             const int j = t / TN, nj = t % TN;
@@ -726,7 +726,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_spmm_pipe(MmArgs a, int til
             read_frag(lds_all, t, fb);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                if constexpr (DT == SP24_I8) acc[i][nj] = smfmac32<DT, 0>(av[j][i], fb, acc[i][nj], mv[j][i]);
+                if constexpr (is8<DT>) acc[i][nj] = smfmac32<DT, 0>(av[j][i], fb, acc[i][nj], mv[j][i]);
                 else if (j == 0) acc[i][nj] = smfmac32<DT, 0>(av[0][i], fb, acc[i][nj], mv[0][i]);
                 else acc[i][nj] = smfmac32<DT, 1>(av[1][i], fb, acc[i][nj], mv[0][i]);
             }
@@ -748,7 +748,7 @@ template <int DT, int OUT, int WM, int WN, int TM, int TN, int NS, int BSRC>
 __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr bool CONV = BSRC == 1, NMAJ = BSRC == 2;
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     constexpr int BK = kRowBytes / ES;
     constexpr int NW = WM * WN;
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;

@@ -1,0 +1,9 @@
+// Tiled product kernels instantiated for f8 inputs and f32 output (one translation unit per type
+// pair so that they compile side by side).
+#include "mm_tiled.hpp"
+
+namespace sp24 {
+
+sp24_status tiled_f8_f32(const MmArgs& a, hipStream_t st) { return pick_tile<SP24_F8, SP24_F32>(a, st); }
+
+} // namespace sp24

@@ -165,19 +165,24 @@ __device__ __forceinline__ double kept_of_keys(const uint32_t (&key)[4])
     const uint32_t hi23 = max(key[2], key[3]), lo23 = min(key[2], key[3]);
     const uint32_t first = max(hi01, hi23), second = max(min(hi01, hi23), max(lo01, lo23));
     if constexpr (DT == SP24_I8) return (double)(first + second);
-    else if constexpr (DT == SP24_F16)
+    else if constexpr (DT == SP24_F8) {
+        // the keys are the bit patterns without their sign; the NaN pattern is the largest and makes the sum NaN
+        const double nan = (double)__builtin_nanf("");
+        return (first == 0x7Fu ? nan : (double)magnitude_f8(first)) + (second == 0x7Fu ? nan : (double)magnitude_f8(second));
+    } else if constexpr (DT == SP24_F16)
         return (double)(float)__builtin_bit_cast(_Float16, (uint16_t)first) + (double)(float)__builtin_bit_cast(_Float16, (uint16_t)second);
     else return (double)__uint_as_float(first << 16) + (double)__uint_as_float(second << 16);
 }
 template <int DT, typename ROW, typename ORDER>
 __device__ __forceinline__ double kept_of_group(ROW row, const ORDER& col, int64_t g)
 {
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     uint32_t key[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t bits = element_bits<ES>(row, col(4 * g + i));
         if constexpr (DT == SP24_I8) key[i] = mag_key8(bits);
+        else if constexpr (DT == SP24_F8) key[i] = mag_key_f8(bits);
         else key[i] = mag_key16<DT>(bits);
     }
     return kept_of_keys<DT>(key);
@@ -196,6 +201,12 @@ __device__ __forceinline__ double kept_of_chunk(const uint4v& w)
             total += max(hi01, hi23) + max(min(hi01, hi23), max(lo01, lo23));
         }
         sum = (double)total;
+    } else if constexpr (DT == SP24_F8) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t key[4] = {mag_key_f8(w[g]), mag_key_f8(w[g] >> 8), mag_key_f8(w[g] >> 16), mag_key_f8(w[g] >> 24)};
+            sum += kept_of_keys<DT>(key);
+        }
     } else {
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
@@ -215,7 +226,7 @@ template <int DT>
 __global__ __launch_bounds__(64 * kPermWaves) void k_retained_magnitude(const uint8_t* A, const int32_t* perm, double* out, int64_t M, int64_t K,
                                                                         int64_t lda)
 {
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];   // staged: the order (2 K bytes), then kPermWaves rows
     __shared__ double partial[kPermWaves];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -330,7 +341,7 @@ sp24_status launch_permute_columns(const void* A, const void* perm, void* P, int
     static const bool ready = allow_lds(k_permute_columns<1>) && allow_lds(k_permute_columns<2>);
     if (!ready) return SP24_ERR_LAUNCH;
     const size_t lds = staged_lds_bytes(K, esize_of(t));
-    if (t == SP24_I8) k_permute_columns<1><<<grid, block, lds, st>>>(a, p, o, M, K, lda, ldp);
+    if (esize_of(t) == 1) k_permute_columns<1><<<grid, block, lds, st>>>(a, p, o, M, K, lda, ldp);
     else k_permute_columns<2><<<grid, block, lds, st>>>(a, p, o, M, K, lda, ldp);
     return launch_result();
 }
@@ -351,7 +362,7 @@ sp24_status launch_retained_magnitude(const void* A, const void* perm, double* o
                                       hipStream_t st)
 {
     static const bool ready = allow_lds(k_retained_magnitude<SP24_F16>) && allow_lds(k_retained_magnitude<SP24_BF16>) &&
-                              allow_lds(k_retained_magnitude<SP24_I8>);
+                              allow_lds(k_retained_magnitude<SP24_I8>) && allow_lds(k_retained_magnitude<SP24_F8>);
     if (!ready) return SP24_ERR_LAUNCH;
     k_zero_double<<<1, 1, 0, st>>>(out);
     if (M * K != 0) {
@@ -361,6 +372,7 @@ sp24_status launch_retained_magnitude(const void* A, const void* perm, double* o
         const size_t lds = p ? staged_lds_bytes(K, esize_of(t)) : 0;   // the given order needs no staging
         if (t == SP24_F16) k_retained_magnitude<SP24_F16><<<grid, block, lds, st>>>(a, p, out, M, K, lda);
         else if (t == SP24_BF16) k_retained_magnitude<SP24_BF16><<<grid, block, lds, st>>>(a, p, out, M, K, lda);
+        else if (t == SP24_F8) k_retained_magnitude<SP24_F8><<<grid, block, lds, st>>>(a, p, out, M, K, lda);
         else k_retained_magnitude<SP24_I8><<<grid, block, lds, st>>>(a, p, out, M, K, lda);
     }
     return launch_result();

@@ -67,6 +67,8 @@ __device__ __forceinline__ auto search_magnitude(uint32_t bits)
     if constexpr (DT == SP24_I8) {
         const int v = (int)(int8_t)bits;
         return v < 0 ? -v : v;
+    } else if constexpr (DT == SP24_F8) {
+        return (double)magnitude_f8(bits);
     } else {
         float f;
         if constexpr (DT == SP24_F16) f = (float)__builtin_bit_cast(_Float16, (uint16_t)(bits & 0x7FFFu));
@@ -84,7 +86,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_permute_search_round(const uint8_t* __restrict__ A, int32_t* perm, int64_t M, int64_t K,
                                                               int64_t lda_bytes, int bit, int64_t G)
 {
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     using sum_t = typename std::conditional<DT == SP24_I8, int, double>::type;
     constexpr FourOfEight sets = make_four_of_eight();
     __shared__ double part[4][70];
@@ -179,6 +181,7 @@ sp24_status launch_permute_search(const void* A, int32_t* perm, int64_t M, int64
         for (int r = 0; r < rounds; ++r) {
             if (t == SP24_F16) k_permute_search_round<SP24_F16><<<grid, block, 0, st>>>(a, perm, M, K, lda * es, r, G);
             else if (t == SP24_BF16) k_permute_search_round<SP24_BF16><<<grid, block, 0, st>>>(a, perm, M, K, lda * es, r, G);
+            else if (t == SP24_F8) k_permute_search_round<SP24_F8><<<grid, block, 0, st>>>(a, perm, M, K, lda * es, r, G);
             else k_permute_search_round<SP24_I8><<<grid, block, 0, st>>>(a, perm, M, K, lda * es, r, G);
             if (hipGetLastError() != hipSuccess) return SP24_ERR_LAUNCH;
         }

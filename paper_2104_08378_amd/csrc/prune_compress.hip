@@ -33,7 +33,7 @@ __device__ __forceinline__ uint32_t opaque(uint32_t v)
 // (a & m) | (b & ~m): one v_bfi_b32
 __device__ __forceinline__ uint32_t bit_select(uint32_t m, uint32_t a, uint32_t b) { return (a & m) | (b & ~m); }
 
-// int8: a group is one dword; two groups a and b are taken together, column i of both in the halves of one
+// One-byte types: a group is one dword; two groups a and b are taken together, column i of both in the halves of one
 // register (a in the low half), so that every step of the selection is one packed instruction for both groups
 // and none moves data between halves.  Keys |x| * 4 + (3 - column) are distinct and order a group by (magnitude
 // descending, column ascending); the two largest stay, i.e. those not below the second largest key t.
@@ -41,14 +41,22 @@ __device__ __forceinline__ uint32_t bit_select(uint32_t m, uint32_t a, uint32_t 
 struct Sel8x2 {
     uint32_t s[4];
 };
+template <int DT>
 __device__ __forceinline__ Sel8x2 select8x2(uint32_t wa, uint32_t wb)
 {
     s16x2 k[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        // byte i of a and of b into the high bytes of the halves (the low bytes cleared), then sign-extended
-        s16x2 x = as_s16x2(__builtin_amdgcn_perm(wb, wa, 0x040C000Cu + 0x01000100u * i)) >> 8;
-        x = __builtin_elementwise_max(x, -x);                 // |-128| = 128 fits the half
+        s16x2 x;
+        if constexpr (DT == SP24_F8) {
+            // 8-bit float: the bit pattern without its sign orders the magnitudes, the NaN pattern on top; byte i
+            // of a and of b into the low bytes of the halves
+            x = as_s16x2(__builtin_amdgcn_perm(wb, wa, 0x0C040C00u + 0x00010001u * i) & 0x007F007Fu);
+        } else {
+            // int8: byte i of a and of b into the high bytes of the halves (the low bytes cleared), then sign-extended
+            x = as_s16x2(__builtin_amdgcn_perm(wb, wa, 0x040C000Cu + 0x01000100u * i)) >> 8;
+            x = __builtin_elementwise_max(x, -x);             // |-128| = 128 fits the half
+        }
         k[i] = (x << 2) + s16x2{(short)(3 - i), (short)(3 - i)};
     }
     // second largest of four = max(min of the pair maxima, max of the pair minima)
@@ -74,9 +82,10 @@ __device__ __forceinline__ void prune8x2(uint32_t& wa, uint32_t& wb, const Sel8x
 // Two int8 groups: their survivors in column order (bytes 0-1 those of a, bytes 2-3 those of b) and their codes
 // (bits 0-3 a, bits 4-7 b).  With d_i the removed flags (exactly two are set per group) the survivors sit at
 // pos0 = d0 * (1 + d1) and pos1 = 3 - d3 * (1 + d2).
+template <int DT>
 __device__ __forceinline__ void compress8x2(uint32_t wa, uint32_t wb, uint32_t& values, uint32_t& codes)
 {
-    const Sel8x2 sel = select8x2(wa, wb);
+    const Sel8x2 sel = select8x2<DT>(wa, wb);
     u16x2 d[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) d[i] = as_u16x2(sel.s[i]) >> 15;
@@ -185,7 +194,7 @@ __device__ __forceinline__ uint32_t unpack8(uint32_t pair, uint32_t code)
 
 // Four int8 groups (16 bytes of a row): the survivors (8 bytes) and the four codes (16 bits, group 0 lowest).
 // FIXED: the positions come from `given` (four stored codes) instead of the magnitudes.
-template <bool FIXED>
+template <int DT, bool FIXED>
 __device__ __forceinline__ void compress8x4(const uint4v& w, uint32_t given, uint32_t& v0, uint32_t& v1, uint32_t& codes)
 {
     if constexpr (FIXED) {
@@ -197,8 +206,8 @@ __device__ __forceinline__ void compress8x4(const uint4v& w, uint32_t given, uin
         codes = 0;
     } else {
         uint32_t c01, c23;
-        compress8x2(w[0], w[1], v0, c01);
-        compress8x2(w[2], w[3], v1, c23);
+        compress8x2<DT>(w[0], w[1], v0, c01);
+        compress8x2<DT>(w[2], w[3], v1, c23);
         codes = c01 | (c23 << 8);
     }
 }
@@ -226,10 +235,10 @@ __device__ __forceinline__ void compress16x2(const uint4v& w, uint32_t given, ui
 template <int DT, int LAYOUT>
 __device__ __forceinline__ uint32_t stored_codes(const uint8_t* meta, int64_t m, int64_t c, int64_t K8, int64_t KB)
 {
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     constexpr int GROUPS = 4 / ES;                       // groups per 16-byte piece
     if constexpr (LAYOUT == SP24_LAYOUT_CANONICAL) {
-        if constexpr (DT == SP24_I8) return *reinterpret_cast<const uint16_t*>(meta + m * K8 + c * 2);
+        if constexpr (is8<DT>) return *reinterpret_cast<const uint16_t*>(meta + m * K8 + c * 2);
         else return meta[m * K8 + c];
     } else {
         const int64_t e0 = c * (16 / ES);                // first column of the piece
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, ui
         uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
         uint32_t codes = 0;
         if constexpr (FIXED) codes = stored_codes<DT, LAYOUT>(meta, m, c, K8, KB);
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             if constexpr (FIXED) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) w[g] = prune8_by_mask(w[g], mask_of_code((codes >> (4 * g)) & 0xFu));
@@ -272,7 +281,7 @@ __global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, ui
 #pragma unroll
                 for (int g = 0; g < 4; g += 2) {
                     uint32_t wa = w[g], wb = w[g + 1];
-                    prune8x2(wa, wb, select8x2(wa, wb));
+                    prune8x2(wa, wb, select8x2<DT>(wa, wb));
                     w[g] = wa;
                     w[g + 1] = wb;
                 }
@@ -329,7 +338,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_prune_transposable(const uint8_t* __restrict__ A, uint8_t* __restrict__ P, int64_t M4,
                                                             int64_t K4, int64_t lda_bytes, int64_t ldp_bytes)
 {
-    constexpr int ES = (DT == SP24_I8) ? 1 : 2;
+    constexpr int ES = is8<DT> ? 1 : 2;
     using sum_t = typename std::conditional<DT == SP24_I8, int, double>::type;
     constexpr PatternTable table = make_pattern_table();
     constexpr int c0[6] = {0, 0, 0, 1, 1, 2}, c1[6] = {1, 2, 3, 2, 3, 3};
@@ -342,11 +351,14 @@ __global__ __launch_bounds__(256) void k_prune_transposable(const uint8_t* __res
     for (int i = 0; i < 4; ++i) {
         const uint8_t* src = A + (bm * 4 + i) * lda_bytes + bk * (4 * ES);
         sum_t mag[4];
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             raw[i][0] = *reinterpret_cast<const uint32_t*>(src);
             raw[i][1] = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) mag[j] = (int)mag_key8((raw[i][0] >> (8 * j)) & 0xFFu);
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (DT == SP24_I8) mag[j] = (int)mag_key8((raw[i][0] >> (8 * j)) & 0xFFu);
+                else mag[j] = (double)magnitude_f8(raw[i][0] >> (8 * j));
+            }
         } else {
             const uint2v w = *reinterpret_cast<const uint2v*>(src);
             raw[i][0] = w[0];
@@ -412,7 +424,7 @@ __global__ __launch_bounds__(256) void k_prune_transposable(const uint8_t* __res
         const uint32_t k0 = (0x940u >> (2 * p)) & 3u, k1 = (0xFB9u >> (2 * p)) & 3u;
         const uint32_t keep = (1u << k0) | (1u << k1);
         uint8_t* dst = P + (bm * 4 + i) * ldp_bytes + bk * (4 * ES);
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             *reinterpret_cast<uint32_t*>(dst) = prune8_by_mask(raw[i][0], keep);
         } else {
             uint32_t w0 = raw[i][0], w1 = raw[i][1];
@@ -441,10 +453,10 @@ __global__ __launch_bounds__(256) void k_compress_canon(const uint8_t* __restric
         const uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
         uint2v v;
         uint32_t v0, v1, codes;
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             uint32_t given = 0;
             if constexpr (FIXED) given = *reinterpret_cast<const uint16_t*>(meta + id * 2);
-            compress8x4<FIXED>(w, given, v0, v1, codes);
+            compress8x4<DT, FIXED>(w, given, v0, v1, codes);
             if constexpr (!FIXED) *reinterpret_cast<uint16_t*>(meta + id * 2) = (uint16_t)codes;
         } else {
             uint32_t given = 0;
@@ -472,14 +484,14 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
                                                         int64_t lda_bytes, int64_t row_bytes)
 {
     constexpr int kPitch = 9;                                                // 8 pieces of a row and one of padding
-    __shared__ uint4v image[(DT == SP24_I8) ? 4 : 1][(DT == SP24_I8) ? 32 * kPitch : 1];
+    __shared__ uint4v image[is8<DT> ? 4 : 1][is8<DT> ? 32 * kPitch : 1];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, r = lane & 31u, h = lane >> 5;
     const int64_t col0 = ((int64_t)blockIdx.x * 4 + wave) * 128;            // first byte of the wavefront's columns
     if (col0 >= row_bytes) return;
     const bool whole = col0 + 128 <= row_bytes;                             // int8 with an odd number of tiles: the last wavefront has one
     for (int64_t rb = blockIdx.y; rb < RBs; rb += gridDim.y) {
         uint4v w[4];
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             uint4v* img = image[wave];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
@@ -501,7 +513,7 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
 #pragma unroll
             for (int q = 0; q < 4; ++q) w[q] = src[q];
         }
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             const int64_t kb = col0 / 64 + h;                               // this lane's tile
             if (kb < KB) {
                 const int64_t tile = rb * KB + kb;
@@ -512,9 +524,9 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
                     if constexpr (FIXED) given = meta[slot];
                     uint4v v;
                     uint32_t a, b;
-                    compress8x4<FIXED>(w[2 * hh], given, a, b, c0);
+                    compress8x4<DT, FIXED>(w[2 * hh], given, a, b, c0);
                     v[0] = a; v[1] = b;
-                    compress8x4<FIXED>(w[2 * hh + 1], given >> 16, a, b, c1);
+                    compress8x4<DT, FIXED>(w[2 * hh + 1], given >> 16, a, b, c1);
                     v[2] = a; v[3] = b;
                     *reinterpret_cast<uint4v*>(V + slot * 16) = v;
                     if constexpr (!FIXED) meta[slot] = c0 | (c1 << 16);
@@ -553,7 +565,7 @@ __global__ __launch_bounds__(256) void k_decompress_canon(const uint8_t* __restr
         const int64_t id = m * chunks_per_row + c;
         uint2v v = *reinterpret_cast<const uint2v*>(V + id * 8);
         uint4v w;
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             uint32_t codes = *reinterpret_cast<const uint16_t*>(meta + id * 2);
             w[0] = unpack8(v[0] & 0xFFFFu, codes & 0xFu);
             w[1] = unpack8(v[0] >> 16, (codes >> 4) & 0xFu);
@@ -580,7 +592,7 @@ __global__ __launch_bounds__(256) void k_decompress_tiled(const uint8_t* __restr
                                                           uint8_t* __restrict__ P, int64_t RBs, int64_t KB,
                                                           int64_t ldp_bytes)
 {
-    constexpr int kPieces = (DT == SP24_I8) ? 4 : 8;          // 16-byte pieces per tile row
+    constexpr int kPieces = is8<DT> ? 4 : 8;          // 16-byte pieces per tile row
     constexpr int kPitch = kPieces + 1;
     __shared__ uint4v image[4][32 * kPitch];
     const uint32_t slot = threadIdx.x & 63u, wave = threadIdx.x >> 6, r = slot & 31u, h = slot >> 5;
@@ -590,7 +602,7 @@ __global__ __launch_bounds__(256) void k_decompress_tiled(const uint8_t* __restr
     for (int64_t rb = blockIdx.y; rb < RBs; rb += gridDim.y) {
         const int64_t tile = rb * KB + kb;
         uint32_t codes = meta[tile * 64 + slot];
-        if constexpr (DT == SP24_I8) {
+        if constexpr (is8<DT>) {
             uint4v v = *reinterpret_cast<const uint4v*>(V + (tile * 64 + slot) * 16);
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
@@ -665,7 +677,7 @@ template <int DT>
 static void run_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda, int64_t ldp, const void* meta, sp24_layout l,
                       hipStream_t st)
 {
-    constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
+    constexpr int64_t es = is8<DT> ? 1 : 2;
     const int64_t cpr = K * es / 16;
     dim3 grid;
     const RowTile rt = row_tile(M, cpr, grid);
@@ -681,7 +693,7 @@ static void run_prune(const void* A, void* P, int64_t M, int64_t K, int64_t lda,
 template <int DT, bool FIXED>
 static void run_compress(const void* A, void* V, void* meta, int64_t M, int64_t K, int64_t lda, sp24_layout l, hipStream_t st)
 {
-    constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
+    constexpr int64_t es = is8<DT> ? 1 : 2;
     if (l == SP24_LAYOUT_CANONICAL) {
         int64_t cpr = K * es / 16;
         dim3 grid;
@@ -689,14 +701,14 @@ static void run_compress(const void* A, void* V, void* meta, int64_t M, int64_t 
         k_compress_canon<DT, FIXED><<<grid, 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint8_t*)meta, M, cpr, lda * es, rt);
     } else {
         int64_t KB = K / 64, RBs = M / 32;
-        k_compress_tiled<DT, FIXED><<<tile_grid(RBs, KB, DT == SP24_I8 ? 8 : 4), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint32_t*)meta, RBs, KB, lda * es, K * es);
+        k_compress_tiled<DT, FIXED><<<tile_grid(RBs, KB, is8<DT> ? 8 : 4), 256, 0, st>>>((const uint8_t*)A, (uint8_t*)V, (uint32_t*)meta, RBs, KB, lda * es, K * es);
     }
 }
 
 template <int DT>
 static void run_decompress(const void* V, const void* meta, void* P, int64_t M, int64_t K, int64_t ldp, sp24_layout l, hipStream_t st)
 {
-    constexpr int64_t es = (DT == SP24_I8) ? 1 : 2;
+    constexpr int64_t es = is8<DT> ? 1 : 2;
     if (l == SP24_LAYOUT_CANONICAL) {
         int64_t cpr = K * es / 16;
         dim3 grid;
@@ -715,6 +727,7 @@ sp24_status launch_prune(const void* A, void* P, int64_t M, int64_t K, int64_t l
     if (M * K == 0) return SP24_OK;
     if (t == SP24_F16) run_prune<SP24_F16>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
     else if (t == SP24_BF16) run_prune<SP24_BF16>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
+    else if (t == SP24_F8) run_prune<SP24_F8>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
     else run_prune<SP24_I8>(A, P, M, K, lda, ldp, nullptr, SP24_LAYOUT_CANONICAL, st);
     return launch_result();
 }
@@ -728,6 +741,7 @@ sp24_status launch_prune_transposable(const void* A, void* P, int64_t M, int64_t
     uint8_t* p = (uint8_t*)P;
     if (t == SP24_F16) k_prune_transposable<SP24_F16><<<grid, 256, 0, st>>>(a, p, M4, K4, lda * 2, ldp * 2);
     else if (t == SP24_BF16) k_prune_transposable<SP24_BF16><<<grid, 256, 0, st>>>(a, p, M4, K4, lda * 2, ldp * 2);
+    else if (t == SP24_F8) k_prune_transposable<SP24_F8><<<grid, 256, 0, st>>>(a, p, M4, K4, lda, ldp);
     else k_prune_transposable<SP24_I8><<<grid, 256, 0, st>>>(a, p, M4, K4, lda, ldp);
     return launch_result();
 }
@@ -758,6 +772,7 @@ sp24_status launch_compress(const void* A, void* V, void* meta, int64_t M, int64
     if (M * K == 0) return SP24_OK;
     if (t == SP24_F16) run_compress<SP24_F16, false>(A, V, meta, M, K, lda, l, st);
     else if (t == SP24_BF16) run_compress<SP24_BF16, false>(A, V, meta, M, K, lda, l, st);
+    else if (t == SP24_F8) run_compress<SP24_F8, false>(A, V, meta, M, K, lda, l, st);
     else run_compress<SP24_I8, false>(A, V, meta, M, K, lda, l, st);
     return launch_result();
 }

@@ -14,11 +14,11 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsp24.so")
 
-F16, BF16, I8, F32, I32 = 0, 1, 2, 3, 4
+F16, BF16, I8, F32, I32, F8 = 0, 1, 2, 3, 4, 5
 CANONICAL, TILED = 0, 1
 B_KMAJOR, B_NMAJOR = 0, 1
 
-_DT = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8, torch.float32: F32, torch.int32: I32}
+_DT = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8, torch.float32: F32, torch.int32: I32, torch.float8_e4m3fn: F8}
 _LAYOUT = {"canonical": CANONICAL, "tiled": TILED}
 _lib = None
 
@@ -121,8 +121,8 @@ def _compressed(V, meta):
     _dev(V, "V"), _dev(meta, "meta")
     if V.dim() != 2 or not V.is_contiguous():
         raise ValueError("V must be a contiguous 2-d tensor [M, K/2]")
-    if V.dtype not in (torch.float16, torch.bfloat16, torch.int8):
-        raise ValueError("V must be float16, bfloat16 or int8")
+    if V.dtype not in (torch.float16, torch.bfloat16, torch.int8, torch.float8_e4m3fn):
+        raise ValueError("V must be float16, bfloat16, int8 or float8_e4m3fn")
     M, K = V.shape[0], V.shape[1] * 2
     _meta_arg(meta, M, K)
     return M, K

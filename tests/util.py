@@ -15,7 +15,7 @@ def tiled_from_canonical(V, meta, dtype):
     K = 2 * K2
     RB, KB = M // 32, K // 64
     meta_t = np.zeros((RB, KB, 64, 4), dtype=np.uint8)
-    if dtype == "i8":
+    if dtype in ("i8", "f8"):
         V_t = np.zeros((RB, KB, 64, 16), dtype=V.dtype)
     else:
         V_t = np.zeros((RB, KB, 2, 64, 8), dtype=V.dtype)
@@ -25,7 +25,7 @@ def tiled_from_canonical(V, meta, dtype):
                 rows = slice(rb * 32, rb * 32 + 32)
                 slots = slice(32 * h, 32 * h + 32)
                 meta_t[rb, kb, slots, :] = meta[rows, 8 * kb + 4 * h: 8 * kb + 4 * h + 4]
-                if dtype == "i8":
+                if dtype in ("i8", "f8"):
                     V_t[rb, kb, slots, :] = V[rows, 32 * kb + 16 * h: 32 * kb + 16 * h + 16]
                 else:
                     for s in range(2):
