@@ -108,25 +108,25 @@ __device__ __forceinline__ const uint8_t* wave_uniform(const uint8_t* p)
 __device__ __forceinline__ void lds_dma16(const uint8_t* base, uint32_t off, const uint8_t* lds)
 {
     const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr)lds);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0", "memory");
 }
 __device__ __forceinline__ void lds_dma4(const uint8_t* base, uint32_t off, const uint8_t* lds)
 {
     const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr)lds);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0", "memory");
 }
 
 // The same transfer with a full 64-bit address per lane (for gathers that a base + 32-bit offset cannot express).
 __device__ __forceinline__ void lds_dma16_addr(const uint8_t* addr, const uint8_t* lds)
 {
     const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(l) : "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(l) : "m0", "memory");
 }
 
 __device__ __forceinline__ void lds_dma4_addr(const uint8_t* addr, const uint8_t* lds)
 {
     const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(addr), "s"(l) : "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(addr), "s"(l) : "m0", "memory");
 }
 
 // 128 zero bytes: the source of B rows that fall into a convolution's padding or past the last output pixel, and

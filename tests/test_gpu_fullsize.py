@@ -34,6 +34,12 @@ def test_full_size_workload(name):
     assert np.array_equal(to_bits(V), wantV)
     assert np.array_equal(to_bits(meta), wantmeta)
     del wantV, wantmeta, oV, ometa
+    # and back: the whole decompressed matrix is the whole pruned matrix, both from the oracle and from sp24_prune
+    P2 = sp24.sp24_decompress(V, meta, layout="tiled")
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(P2), oracle.prune(A, dt))
+    assert torch.equal(P2.view(torch.uint8), P.view(torch.uint8))
+    del P2
 
     # sampled outputs: corners, tile edges and random picks
     rng = np.random.default_rng(7)
@@ -103,3 +109,18 @@ def test_full_size_quantised_product():
         got = got_t[torch.as_tensor(rows, device="cuda")][:, torch.as_tensor(cols, device="cuda")].cpu().numpy()
         assert np.array_equal(got, want)
     assert len(np.unique(want)) > 30
+
+
+def test_full_size_int8_sparse_equals_dense_of_pruned_everywhere():
+    """Every one of the 8192 x 8192 outputs: the sparse product of the compressed matrix and the dense product of the
+    pruned matrix are the same integers (Sec. 3.2, Fig. 2: the sparse operation skips only multiplications by
+    zero), compared on the GPU -- a misplaced tile anywhere would show.  Sampled outputs of both are checked
+    against the oracle above."""
+    A, Bt = synth.make("square_i8")
+    Ad, Bd = to_gpu(A, "i8"), to_gpu(Bt, "i8")
+    V, meta = sp24.sp24_compress(Ad, layout="tiled")
+    D = sp24.sp24_spmm(V, meta, Bd, torch.int32, layout="tiled")
+    Dd = sp24.sp24_gemm_dense(sp24.sp24_prune(Ad), Bd, torch.int32)
+    torch.cuda.synchronize()
+    assert torch.equal(D, Dd)
+    assert int(D.abs().max()) > 100000                           # not trivially equal

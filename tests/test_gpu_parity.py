@@ -410,3 +410,23 @@ def test_removed_positions_take_no_part_in_the_sum(dtype, shape):
         torch.cuda.synchronize()
         ref = oracle.gemm(oracle.prune(Abits, dtype), synth.to_bits(B, dtype), dtype)     # the finite B: rows 20, 21 never count
         assert torch.equal(D.cpu(), torch.from_numpy(ref).to(torch.float32)), (dtype, shape, layout)
+
+
+def test_int8_product_with_minus_128_in_both_operands():
+    """-128 has no positive counterpart in int8: its products (+16384 with itself, -16256 with 127) must come out of
+    the integer matrix instructions exactly, in the general, the streaming and both tiled kernels."""
+    rng = np.random.default_rng(91)
+    pool = np.array([-128, -128, -127, 127, -1, 0, 1, 64], dtype=np.int8)
+    for M, N, K, layout in ((33, 17, 64, "canonical"), (64, 16, 256, "tiled"), (256, 160, 384, "tiled"), (128, 128, 128, "canonical"),
+                            (3840, 3840, 128, "tiled")):
+        A, Bt = rng.choice(pool, size=(M, K)), rng.choice(pool, size=(N, K))
+        Ad, Bd = to_gpu(A, "i8"), to_gpu(Bt, "i8")
+        V, meta = sp24.sp24_compress(Ad, layout=layout)
+        D = sp24.sp24_spmm(V, meta, Bd, torch.int32, layout=layout)
+        Dd = sp24.sp24_gemm_dense(sp24.sp24_prune(Ad), Bd, torch.int32)
+        torch.cuda.synchronize()
+        rows = np.arange(M) if M < 1000 else np.unique(np.concatenate([[0, 255, 256, M - 1], rng.integers(0, M, 10)]))
+        ref = oracle.gemm(oracle.prune(np.ascontiguousarray(A[rows]), "i8"), np.ascontiguousarray(Bt.T), "i8")
+        assert np.array_equal(D.cpu().numpy()[rows], ref), (M, N, K)
+        assert np.array_equal(Dd.cpu().numpy()[rows], ref), (M, N, K)
+        assert (np.abs(ref) >= 16384).any()

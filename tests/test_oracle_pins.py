@@ -469,6 +469,17 @@ def test_conv_workload_matrix_is_the_im2col_of_its_activations():
 
 # ---- epilogue of the quantised path -------------------------------------------------------------------------
 
+def test_dequant_hand_computed_case():
+    # worked by hand: acc = [[100, -3], [7, 0]], w_scale = [0.5, 0.25], x_scale = 2, bias = [1, -10]
+    #   row 0: s = 1.0  -> 100 + 1 = 101, -3 + 1 = -2        (ReLU: 101, 0)
+    #   row 1: s = 0.5  -> 3.5 - 10 = -6.5, 0 - 10 = -10     (ReLU: 0, 0)
+    acc = np.array([[100, -3], [7, 0]], dtype=np.int32)
+    w, b = np.array([0.5, 0.25], dtype=np.float32), np.array([1.0, -10.0], dtype=np.float32)
+    assert np.array_equal(oracle.dequant(acc, w, 2.0, b, False), np.array([[101.0, -2.0], [-6.5, -10.0]]))
+    assert np.array_equal(oracle.dequant(acc, w, 2.0, b, True), np.array([[101.0, 0.0], [0.0, 0.0]]))
+    assert np.array_equal(oracle.dequant(acc, w, 2.0, None, False), np.array([[100.0, -3.0], [3.5, 0.0]]))
+
+
 def test_requant_with_unit_scales_is_a_saturating_copy():
     acc = np.array([[-300, -129, -128, -1, 0, 1, 127, 128, 300]], dtype=np.int32)
     q = oracle.requant(acc, [1.0], 1.0, 1.0)
