@@ -107,12 +107,12 @@ __device__ __forceinline__ const uint8_t* wave_uniform(const uint8_t* p)
 
 __device__ __forceinline__ void lds_dma16(const uint8_t* base, uint32_t off, const uint8_t* lds)
 {
-    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr)lds);
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0", "memory");
 }
 __device__ __forceinline__ void lds_dma4(const uint8_t* base, uint32_t off, const uint8_t* lds)
 {
-    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr)lds);
+    const uint32_t l = (uint32_t)(uintptr_t)(lds_ptr)lds;
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(wave_uniform(base)), "s"(l) : "m0", "memory");
 }
 
@@ -979,7 +979,7 @@ static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
 }
 
 template <int DT, int OUT>
-static sp24_status pick_tile(const MmArgs& a, hipStream_t st)
+static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
 {
     // 256x256 tiles when they still fill the 256 compute units, else 128x128
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);

@@ -1,6 +1,6 @@
 // Tiled product kernels instantiated for i8 inputs and i32 output (one translation unit per type
 // pair so that they compile side by side).
-#include "mm_tiled.hpp"
+#include "conv_patch.hpp"
 
 namespace sp24 {
 
