@@ -34,9 +34,16 @@ CASES = [
     ("bf16", "bf16", 64, 1, 7, 9, 32, 3, 2, (0, 1), (2, 1), "tiled"),      # general (N = 27 < 32)
     ("i8", "i32", 33, 3, 5, 5, 32, 3, 3, (1, 1), (1, 1), "canonical"),      # general, ragged M
     ("i8", "i32", 64, 2, 6, 6, 64, 3, 3, (2, 2), (1, 1), "tiled"),          # general (C*1 = 64 bytes < a step), pad > needed
-    ("f16", "f16", 128, 3, 12, 12, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # tiled 128x128, 9 steps, one tap per step
+    ("f16", "f16", 128, 3, 12, 12, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # 3x3 patch kernel (sparse), one chunk of channels, ragged N = 432
+    ("f16", "f16", 96, 5, 9, 11, 192, 3, 3, (1, 1), (1, 1), "tiled"),       # patch kernel: three chunks, ragged M (three row blocks), N = 495
+    ("bf16", "f32", 160, 40, 4, 4, 256, 3, 3, (1, 1), (1, 1), "tiled"),     # patch kernel: four chunks, a tile spans eight images, ragged M
+    ("i8", "i32", 128, 3, 16, 8, 384, 3, 3, (0, 1), (1, 1), "tiled"),       # patch kernel: no vertical padding (output images shorter than input), int8, three chunks
+    ("i8", "i32", 128, 3, 13, 9, 384, 3, 3, (0, 0), (1, 1), "tiled"),       # no padding at all: a patch could span 222 pixels, the general tiled kernel
+    ("f16", "f32", 128, 2, 20, 20, 128, 3, 3, (1, 0), (1, 1), "tiled"),     # patch kernel: padding on one axis only, two chunks, output rows shorter than input, patch of up to 186 pixels
+    ("bf16", "bf16", 256, 1, 24, 24, 320, 3, 3, (1, 1), (1, 1), "tiled"),   # patch kernel: five chunks, one image larger than a tile
+    ("f16", "f16", 128, 2, 30, 30, 64, 3, 3, (0, 0), (1, 1), "tiled"),      # 3x3 but a patch would span 198 pixels: the general tiled kernel
     ("bf16", "f32", 192, 2, 11, 13, 128, 2, 3, (1, 0), (2, 1), "tiled"),    # tiled, two steps per tap, strides, ragged N = 132
-    ("i8", "i32", 256, 4, 10, 10, 128, 3, 3, (1, 1), (1, 1), "tiled"),      # tiled int8, 9 steps
+    ("i8", "i32", 256, 4, 10, 10, 128, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel int8, one chunk (dense: tiled, 9 steps)
     ("f16", "f32", 128, 2, 8, 8, 256, 1, 1, (0, 0), (1, 1), "tiled"),       # pointwise: plain product
     ("bf16", "bf16", 64, 5, 9, 7, 64, 5, 3, (2, 1), (3, 2), "tiled"),       # 5x3 filter, stride 3x2
     ("f16", "f16", 2048, 64, 10, 10, 64, 3, 3, (1, 1), (1, 1), "tiled"),    # 8 x 25 tiles of 256x256 (eight-wavefront shape)

@@ -175,8 +175,8 @@ def test_f8_other_operations():
     torch.cuda.synchronize()
     ref = oracle.gemm(oracle.prune(A2, "f8"), np.ascontiguousarray(B2.T), "f8")
     assert f8_close(out_to_f64(D), ref, oracle.prune(A2, "f8"), B2)
-    # convolution as an implicit GEMM: 3x3, pad 1, 128 channels (a step of the tiled kernel inside one filter tap)
-    C, R, S = 128, 3, 3
+    # convolution as an implicit GEMM: 3x3, pad 1, 384 channels (three 128-byte chunks of channels per filter tap)
+    C, R, S = 384, 3, 3
     W = draw(128, R * S * C, 0.5, 85)
     X = synth.normal_bits((2, 9, 9, C), 1.0, "f8", 86, 9, 1)
     Vc, mc = sp24.sp24_compress(to_gpu(W, "f8"), layout="tiled")
