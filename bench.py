@@ -401,7 +401,7 @@ def measured_traffic(name):
         if section is None or "{" not in ln:
             continue
         kernel = ln[:ln.index("{")]
-        sparse = "k_spmm_pipe" in kernel or ("k_mm_skinny" in kernel and "true" in kernel)
+        sparse = "k_spmm_pipe" in kernel or "k_conv_patch" in kernel or ("k_mm_skinny" in kernel and "true" in kernel)
         who = "kernel" if sparse else "copy" if "copyBuffer" in kernel else None
         if who and (who, section) not in got:
             got[(who, section)] = float(ast.literal_eval(ln[ln.index("{"):ln.index("}") + 1])[section])
