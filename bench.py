@@ -152,28 +152,29 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
         fn()
         return (time.perf_counter() - t0) * M / rows       # scaled from `rows` rows to the whole matrix
 
-    Pm = torch.empty_like(As[0])
-    Vm = torch.empty_like(V)
+    # outputs rotate like the inputs (a fixed output buffer would stay in the last-level cache from launch to launch)
+    Pms = [torch.empty_like(As[0]) for _ in range(R)]
+    Vms = [torch.empty_like(V) for _ in range(R)]
     perm_h = np.random.default_rng(0).permutation(K).astype(np.int32)
     perm_d = torch.from_numpy(perm_h).cuda()
     rperm_d = torch.from_numpy(np.random.default_rng(1).permutation(M).astype(np.int32)).cuda()
     total = torch.empty(1, dtype=torch.float64, device="cuda")
     out = {}
     ops = {
-        "mask_apply": (lambda i: sp24.sp24_mask_apply(As[i % R], meta, layout="tiled", out=Pm), 2.0 * M * K * es + M * K / 8,
+        "mask_apply": (lambda i: sp24.sp24_mask_apply(As[i % R], meta, layout="tiled", out=Pms[i % R]), 2.0 * M * K * es + M * K / 8,
                        lambda: oracle.mask_apply(sample, smeta, dt)),
-        "compress_masked": (lambda i: sp24.sp24_compress_masked(As[i % R], meta, layout="tiled", out=Vm), 1.5 * M * K * es + M * K / 8,
+        "compress_masked": (lambda i: sp24.sp24_compress_masked(As[i % R], meta, layout="tiled", out=Vms[i % R]), 1.5 * M * K * es + M * K / 8,
                             lambda: oracle.compress_masked(sample, smeta, dt)),
-        "prune_transposable": (lambda i: sp24.sp24_prune_transposable(As[i % R], out=Pm), 2.0 * M * K * es,
+        "prune_transposable": (lambda i: sp24.sp24_prune_transposable(As[i % R], out=Pms[i % R]), 2.0 * M * K * es,
                                lambda: oracle.prune_transposable(sample, dt)),
         # channel permutations: the gather reads and writes the matrix once, the figure of merit reads it once
-        "permute_columns": (lambda i: sp24.sp24_permute_columns(As[i % R], perm_d, out=Pm), 2.0 * M * K * es + 4.0 * K,
+        "permute_columns": (lambda i: sp24.sp24_permute_columns(As[i % R], perm_d, out=Pms[i % R]), 2.0 * M * K * es + 4.0 * K,
                             lambda: oracle.permute_columns(sample, perm_h, dt)),
         "retained_magnitude": (lambda i: sp24.sp24_retained_magnitude(As[i % R], perm_d, out=total), 1.0 * M * K * es + 4.0 * K,
                                lambda: oracle.retained_magnitude(sample, dt, perm=perm_h)),
         "retained_magnitude_given_order": (lambda i: sp24.sp24_retained_magnitude(As[i % R], out=total), 1.0 * M * K * es,
                                            lambda: oracle.retained_magnitude(sample, dt)),
-        "permute_rows": (lambda i: sp24.sp24_permute_rows(As[i % R], rperm_d, out=Pm), 2.0 * M * K * es + 4.0 * M,
+        "permute_rows": (lambda i: sp24.sp24_permute_rows(As[i % R], rperm_d, out=Pms[i % R]), 2.0 * M * K * es + 4.0 * M,
                          lambda: oracle.permute_rows(sample, np.random.default_rng(1).permutation(rows).astype(np.int32), dt)),
     }
     for op, (fn, nbytes, cfn) in ops.items():
@@ -435,17 +436,26 @@ def measure(name, args, brief=False):
     R = max(2, min(96, int(600e6 // per_set) + 1))          # rotating input sets: footprint beyond the last-level cache
     As = [to_gpu(A, dt) for _ in range(R)]
     Bs = [to_gpu(Bsrc, dt) for _ in range(R)]
-    P = torch.empty_like(As[0])
-    P2 = torch.empty_like(As[0])
-    D = torch.empty((M, N), dtype=out_dt, device="cuda")
-    Dd = torch.empty((M, N), dtype=out_dt, device="cuda")
+    # every buffer a step touches rotates with the inputs -- outputs and the compressed pair included -- so that no
+    # launch finds what it reads, or the lines it overwrites, in the 256 MB last-level cache from the launch before
+    Ps = [torch.empty_like(As[0]) for _ in range(R)]
+    P2s = [torch.empty_like(As[0]) for _ in range(R)]
+    d_bytes = M * N * os_
+    Rd = max(2, min(R, int(1.5e9 // max(d_bytes, 1))))        # copies of each product's output
+    Ds = [torch.empty((M, N), dtype=out_dt, device="cuda") for _ in range(Rd)]
+    Dds = [torch.empty((M, N), dtype=out_dt, device="cuda") for _ in range(Rd)]
     ops = ["prune", "compress", "decompress", "spmm", "dense"]
     only = ([o for o in args.only.split(",") if o] if not brief else []) or list(ops)
-    V, meta = sp24.sp24_compress(As[0], layout="tiled")
-    sp24.sp24_prune(As[0], out=P)
+    VMs = [sp24.sp24_compress(a_, layout="tiled") for a_ in As]
+    for a_, p_ in zip(As, Ps):
+        sp24.sp24_prune(a_, out=p_)
+    V, meta = VMs[0]
+    P, P2, D, Dd = Ps[0], P2s[0], Ds[0], Dds[0]
 
     def step(i, ev=None):
         a, b = As[i % R], Bs[i % R]
+        p_, p2_, (v_, m_) = Ps[i % R], P2s[i % R], VMs[i % R]
+        d_, dd_ = Ds[i % Rd], Dds[i % Rd]
         k = 0
 
         def mark():
@@ -455,25 +465,25 @@ def measure(name, args, brief=False):
             k += 1
         mark()
         if "prune" in only:
-            sp24.sp24_prune(a, out=P)
+            sp24.sp24_prune(a, out=p_)
         mark()
         if "compress" in only:
-            sp24.sp24_compress(a, layout="tiled", out=(V, meta))
+            sp24.sp24_compress(a, layout="tiled", out=(v_, m_))
         mark()
         if "decompress" in only:
-            sp24.sp24_decompress(V, meta, layout="tiled", out=P2)
+            sp24.sp24_decompress(v_, m_, layout="tiled", out=p2_)
         mark()
         if "spmm" in only:
             if conv:
-                sp24.sp24_spmm_conv2d(V, meta, b, out_dt, 3, 3, (1, 1), (1, 1), layout="tiled", out=D)
+                sp24.sp24_spmm_conv2d(v_, m_, b, out_dt, 3, 3, (1, 1), (1, 1), layout="tiled", out=d_)
             else:
-                sp24.sp24_spmm(V, meta, b, out_dt, layout="tiled", out=D)
+                sp24.sp24_spmm(v_, m_, b, out_dt, layout="tiled", out=d_)
         mark()
         if "dense" in only:
             if conv:
-                sp24.sp24_conv2d_dense(P, b, out_dt, 3, 3, (1, 1), (1, 1), out=Dd)
+                sp24.sp24_conv2d_dense(p_, b, out_dt, 3, 3, (1, 1), (1, 1), out=dd_)
             else:
-                sp24.sp24_gemm_dense(P, b, out_dt, out=Dd)
+                sp24.sp24_gemm_dense(p_, b, out_dt, out=dd_)
         mark()
 
     for i in range(args.warmup):
@@ -532,9 +542,9 @@ def measure(name, args, brief=False):
                 xs = [b.view(-1, 14, 14, K // 9).permute(0, 3, 1, 2) for b in Bs]
                 run = lambda i: torch.nn.functional.conv2d(xs[i % R], wt, padding=1)
             elif dt == "i8":
-                run = lambda i: torch._int_mm(P, Bs[i % R].t())
+                run = lambda i: torch._int_mm(Ps[i % R], Bs[i % R].t())
             else:
-                run = lambda i: torch.matmul(P, Bs[i % R].t())
+                run = lambda i: torch.matmul(Ps[i % R], Bs[i % R].t())
             for i in range(5):
                 run(i)
             batches = []
@@ -651,7 +661,7 @@ def measure(name, args, brief=False):
             line["extras"] = extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A, args.steps, conv)
         if args.cpu_seconds > 0:
             line["cpu_baseline"] = cpu_baseline(name, A, Bt, args.cpu_seconds)
-    del As, Bs, P, P2, D, Dd, V, meta
+    del As, Bs, Ps, P2s, Ds, Dds, VMs, P, P2, D, Dd, V, meta
     torch.cuda.empty_cache()
     return line
 

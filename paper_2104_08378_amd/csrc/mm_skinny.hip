@@ -90,11 +90,13 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void k_mm_skinny(MmArgs a)
                         va[u][1] = ok ? *reinterpret_cast<const uint4v*>(vrow + kb * 64 + 16) : zero4;
                     }
                 } else {
-                    codes[u] = ok ? Mp[tile * 64 + lane] : 0u;
-                    if constexpr (is8<DT>) va[u][0] = ok ? Vp[tile * 64 + lane] : zero4;
+                    // the compressed operand passes once: loads marked as such leave B, which every workgroup re-reads,
+                    // in the L2 (8192 x 8192 x 16 bf16 with the operand streamed from HBM: 21.1 -> 19.3 us)
+                    codes[u] = ok ? __builtin_nontemporal_load(Mp + tile * 64 + lane) : 0u;
+                    if constexpr (is8<DT>) va[u][0] = ok ? __builtin_nontemporal_load(Vp + tile * 64 + lane) : zero4;
                     else {
-                        va[u][0] = ok ? Vp[(tile * 2) * 64 + lane] : zero4;
-                        va[u][1] = ok ? Vp[(tile * 2 + 1) * 64 + lane] : zero4;
+                        va[u][0] = ok ? __builtin_nontemporal_load(Vp + (tile * 2) * 64 + lane) : zero4;
+                        va[u][1] = ok ? __builtin_nontemporal_load(Vp + (tile * 2 + 1) * 64 + lane) : zero4;
                     }
                 }
             } else {

@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, ui
     const int64_t c = rt.piece();
     if (c >= chunks_per_row) return;
     for (int64_t m = rt.first_row(); m < M; m += rt.row_stride()) {
-        uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
+        uint4v w = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16));
         uint32_t codes = 0;
         if constexpr (FIXED) codes = stored_codes<DT, LAYOUT>(meta, m, c, K8, KB);
         if constexpr (is8<DT>) {
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void k_prune(const uint8_t* __restrict__ A, ui
                 w[2 * g + 1] = w1;
             }
         }
-        *reinterpret_cast<uint4v*>(P + m * ldp_bytes + c * 16) = w;
+        __builtin_nontemporal_store(w, reinterpret_cast<uint4v*>(P + m * ldp_bytes + c * 16));
     }
 }
 
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(256) void k_compress_canon(const uint8_t* __restric
     if (c >= chunks_per_row) return;
     for (int64_t m = rt.first_row(); m < M; m += rt.row_stride()) {
         const int64_t id = m * chunks_per_row + c;      // V rows are 8 * chunks bytes, metadata rows chunks (16-bit) or 2 * chunks (int8) bytes
-        const uint4v w = *reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16);
+        const uint4v w = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(A + m * lda_bytes + c * 16));
         uint2v v;
         uint32_t v0, v1, codes;
         if constexpr (is8<DT>) {
@@ -496,7 +496,7 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const uint32_t row = (lane >> 3) + 8 * t, pc = lane & 7u;
-                if (whole || pc < 4) img[row * kPitch + pc] = *reinterpret_cast<const uint4v*>(A + (rb * 32 + row) * lda_bytes + col0 + pc * 16);
+                if (whole || pc < 4) img[row * kPitch + pc] = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(A + (rb * 32 + row) * lda_bytes + col0 + pc * 16));
             }
             // the image is this wavefront's own and the LDS serves a wavefront's operations in order: no barrier,
             // only the compiler must not move the reads above the writes
@@ -528,8 +528,8 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
                     v[0] = a; v[1] = b;
                     compress8x4<DT, FIXED>(w[2 * hh + 1], given >> 16, a, b, c1);
                     v[2] = a; v[3] = b;
-                    *reinterpret_cast<uint4v*>(V + slot * 16) = v;
-                    if constexpr (!FIXED) meta[slot] = c0 | (c1 << 16);
+                    __builtin_nontemporal_store(v, reinterpret_cast<uint4v*>(V + slot * 16));
+                    if constexpr (!FIXED) __builtin_nontemporal_store(c0 | (c1 << 16), &meta[slot]);
                 }
             }
         } else {
@@ -546,9 +546,9 @@ __global__ __launch_bounds__(256) void k_compress_tiled(const uint8_t* __restric
                 compress16x2<DT, FIXED>(w[2 * s + 1], given >> (16 * s + 8), a, b, c);
                 v[2] = a; v[3] = b;
                 codes |= c << (16 * s + 8);
-                *reinterpret_cast<uint4v*>(V + ((tile * 2 + s) * 64 + lane) * 16) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<uint4v*>(V + ((tile * 2 + s) * 64 + lane) * 16));
             }
-            if constexpr (!FIXED) meta[tile * 64 + lane] = codes;
+            if constexpr (!FIXED) __builtin_nontemporal_store(codes, &meta[tile * 64 + lane]);
         }
     }
 }
@@ -579,7 +579,7 @@ __global__ __launch_bounds__(256) void k_decompress_canon(const uint8_t* __restr
             unpack16(v[1], codes >> 4, a, b);
             w[2] = a; w[3] = b;
         }
-        *reinterpret_cast<uint4v*>(P + m * ldp_bytes + c * 16) = w;
+        __builtin_nontemporal_store(w, reinterpret_cast<uint4v*>(P + m * ldp_bytes + c * 16));
     }
 }
 
@@ -616,7 +616,7 @@ __global__ __launch_bounds__(256) void k_decompress_tiled(const uint8_t* __restr
         } else {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                uint4v v = *reinterpret_cast<const uint4v*>(V + ((tile * 2 + s) * 64 + slot) * 16);
+                uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(V + ((tile * 2 + s) * 64 + slot) * 16));
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     uint32_t cc = (codes >> (8 * (2 * s + q))) & 0xFFu;
@@ -640,7 +640,7 @@ __global__ __launch_bounds__(256) void k_decompress_tiled(const uint8_t* __restr
         for (int t = 0; t < 32 / kRowsPerStore; ++t) {
             const uint32_t row = slot / kPieces + t * kRowsPerStore, pc = slot % kPieces;
             const uint4v w = img[row * kPitch + pc];
-            *reinterpret_cast<uint4v*>(P + (rb * 32 + row) * ldp_bytes + kb * (16 * kPieces) + pc * 16) = w;
+            __builtin_nontemporal_store(w, reinterpret_cast<uint4v*>(P + (rb * 32 + row) * ldp_bytes + kb * (16 * kPieces) + pc * 16));
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();                      // the next tile's writes stay behind these reads
