@@ -212,6 +212,20 @@ def extras(name, As, Bs, V, meta, P, D, Dd, out_dt, A_host, steps, conv):
         out["spmm_i8_scaled_int8_out"] = {"us": ts * 1e6, "dense_us": td * 1e6, "speedup_vs_dense": td / ts,
                                           "dense_equiv_Tops": 2.0 * M * N * K / ts / 1e12,
                                           "frac_of_sparse_peak": M * N * K / ts / PEAK_DENSE[dt]}
+        # the same shape on 8-bit floats (4 exponent, 3 fraction bits): operands N(0, 0.5) and N(0, 1) rounded to the
+        # type, fp32 accumulation, bf16 output; against the chip's dense fp8 matrix-core peak (5.0 PFLOP/s)
+        f8 = torch.float8_e4m3fn
+        A8s = [(torch.randn((M, K), device="cuda") * 0.5).to(f8) for _ in range(2)]
+        B8s = [torch.randn((N, K), device="cuda").to(f8) for _ in range(R)]
+        VM8 = [sp24.sp24_compress(a_, layout="tiled") for a_ in A8s]
+        P8 = [sp24.sp24_prune(a_) for a_ in A8s]
+        Df8 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        ts = timed(lambda i: sp24.sp24_spmm(VM8[i % 2][0], VM8[i % 2][1], B8s[i % R], torch.bfloat16, layout="tiled", out=Df8))
+        td = timed(lambda i: sp24.sp24_gemm_dense(P8[i % 2], B8s[i % R], torch.bfloat16, out=Df8))
+        out["spmm_f8_bf16_out"] = {"us": ts * 1e6, "dense_us": td * 1e6, "speedup_vs_dense": td / ts,
+                                   "dense_equiv_Tflops": 2.0 * M * N * K / ts / 1e12,
+                                   "frac_of_sparse_peak": M * N * K / ts / 5.0e15}
+        del A8s, B8s, VM8, P8, Df8
     return out
 
 
