@@ -124,3 +124,39 @@ def test_full_size_int8_sparse_equals_dense_of_pruned_everywhere():
     torch.cuda.synchronize()
     assert torch.equal(D, Dd)
     assert int(D.abs().max()) > 100000                           # not trivially equal
+
+
+def test_full_size_search_for_a_column_order():
+    """The search on the matrix bench.py --extras times it on (square_i8's A, 8192 x 8192): the whole order equals
+    the oracle's on the first 512 rows (all 8192 columns: eleven rounds of 1024 pairs of groups); on all rows the
+    order is a permutation, keeps no less magnitude than before, and every pair of groups of the last round is
+    optimal among its 35 ways by the oracle's figure of merit on those eight columns (the order depends on every
+    row, so the oracle cannot reproduce it from a sample of rows)."""
+    A, _ = synth.make("square_i8")
+    M, K = A.shape
+    Ad = to_gpu(A, "i8")
+    top = np.ascontiguousarray(A[:512])
+    got_top = sp24.sp24_permute_search(to_gpu(top, "i8"), sweeps=1)
+    perm = sp24.sp24_permute_search(Ad, sweeps=1)
+    before = float(sp24.sp24_retained_magnitude(Ad).cpu()[0])
+    after = float(sp24.sp24_retained_magnitude(Ad, perm).cpu()[0])
+    torch.cuda.synchronize()
+    assert np.array_equal(got_top.cpu().numpy(), oracle.permute_search(top, "i8", sweeps=1))
+    p = perm.cpu().numpy()
+    assert sorted(p.tolist()) == list(range(K))
+    assert after >= before
+    assert after == oracle.retained_magnitude(A, "i8", perm=p)          # int8: every sum is an exact integer
+    # the last round pairs group g (bit 10 clear) with g + 1024
+    from itertools import combinations
+    rng = np.random.default_rng(11)
+    G = K // 4
+    for g in rng.choice([g for g in range(G) if not g & (G // 2)], size=24, replace=False):
+        h = g + G // 2
+        cols = np.concatenate([p[4 * g:4 * g + 4], p[4 * h:4 * h + 4]])
+        sub = np.ascontiguousarray(A[:, cols])
+        kept = oracle.retained_magnitude(sub, "i8")
+        for rest in combinations(range(1, 8), 3):
+            first = (0,) + rest
+            other = tuple(i for i in range(8) if i not in first)
+            way = np.array(first + other, dtype=np.int32)
+            assert oracle.retained_magnitude(sub, "i8", perm=way) <= kept, (g, way)
