@@ -66,7 +66,7 @@ inline bool conv_patch_fits(const MmArgs& a)
 }
 
 template <int DT, int OUT>
-__global__ __launch_bounds__(256, 1) void k_conv_patch(MmArgs a, int tiles_m, int tiles_n)
+__global__ __launch_bounds__(256, 2) void k_conv_patch(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr int ES = is8<DT> ? 1 : 2;
     constexpr int BK = kRowBytes / ES;                 // K elements (channels) per step
@@ -77,11 +77,12 @@ __global__ __launch_bounds__(256, 1) void k_conv_patch(MmArgs a, int tiles_m, in
     constexpr int kLoadsA = TM * (is8<DT> ? 4 : 3);    // loads of a step's A per wavefront: values twice, codes once (twice for 8-bit)
         constexpr int TAPS = 9, PF = 3;                    // PF: steps of A in registers, the one in use and two ahead; divides TAPS
     constexpr int kPitch = kPatchPitch;
-    constexpr int kPatchBytes = kPatchRows * kPitch;
-    // LDS: buffer 0, buffer 1, a row of zeros, and a second row of zeros one buffer further on: a row address is
-    // formed for buffer 0 and reaches buffer 1 by an immediate offset, whichever row it is
-    constexpr int kZeroOff = 2 * kPatchBytes;
-    constexpr int kLdsBytes = kZeroOff + kPatchBytes + 256;
+    // LDS: two buffers, each the patch's rows and behind them a row of zeros: a row address is formed for buffer 0
+    // and reaches buffer 1 by an immediate offset, whichever row it is.  55 KiB, so that two workgroups share a
+    // compute unit where the grid has them
+    constexpr int kPatchBytes = (kPatchRows + 1) * kPitch;
+    constexpr int kZeroOff = kPatchRows * kPitch;
+    constexpr int kLdsBytes = 2 * kPatchBytes;
     using acc_t = typename acc_of<DT>::type;
     static_assert(4 * epilogue_geometry<OUT, TN>::kWaveBytes <= kLdsBytes, "store scratch");
     static_assert(kPatchBytes + 96 + 16 <= 65536 && kLdsBytes <= 160 * 1024, "the second buffer and a fragment's place in a row as a 16-bit immediate");
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(256, 1) void k_conv_patch(MmArgs a, int tiles_m, in
         for (int j = 0; j < TN; ++j) acc[i][j] = acc_t{};
 
     // ---- prologue: the row of zeros, the first patch, the second patch in flight, A of steps 0 and 1, B of step 0 ----
-    if (tid < 128) reinterpret_cast<uint32_t*>(lds_all + kZeroOff + (tid >> 6) * kPatchBytes)[tid & 63] = 0u;
+    if (tid < 2 * (kPitch / 4)) reinterpret_cast<uint32_t*>(lds_all + kZeroOff + (tid / (kPitch / 4)) * kPatchBytes)[tid % (kPitch / 4)] = 0u;
     Patch pp;
     load_patch(0, pp);
     store_patch(pp, 0);
