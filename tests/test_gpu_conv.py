@@ -42,6 +42,7 @@ CASES = [
     ("f16", "f32", 128, 2, 20, 20, 128, 3, 3, (1, 0), (1, 1), "tiled"),     # patch kernel: padding on one axis only, two chunks, output rows shorter than input, patch of up to 186 pixels
     ("bf16", "bf16", 256, 1, 24, 24, 320, 3, 3, (1, 1), (1, 1), "tiled"),   # patch kernel: five chunks, one image larger than a tile
     ("f16", "f16", 128, 2, 30, 30, 64, 3, 3, (0, 0), (1, 1), "tiled"),      # 3x3 but a patch would span 198 pixels: the general tiled kernel
+    ("f16", "f16", 256, 300, 8, 8, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel, 300 tiles: more workgroups than compute units, two on some
     ("bf16", "f32", 192, 2, 11, 13, 128, 2, 3, (1, 0), (2, 1), "tiled"),    # tiled, two steps per tap, strides, ragged N = 132
     ("i8", "i32", 256, 4, 10, 10, 128, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel int8, one chunk (dense: tiled, 9 steps)
     ("f16", "f32", 128, 2, 8, 8, 256, 1, 1, (0, 0), (1, 1), "tiled"),       # pointwise: plain product
