@@ -514,6 +514,13 @@ static sp24_status conv_common(MmArgs& a, int64_t n_img, int64_t H, int64_t W, i
     a.K = K;
     a.bo = SP24_B_KMAJOR;
     a.ldb = K;
+    if (R == 1 && S == 1 && pad_h == 0 && pad_w == 0 && stride_h == 1 && stride_w == 1) {
+        // a pointwise convolution is the plain product with the NHWC input as the K-major second operand, one row
+        // per pixel: it takes the product kernels as they are (the streaming one for few pixels included)
+        a.conv = ConvGeom{};
+        a.ldb = C;
+        return mm_common(a, st);
+    }
     a.conv = ConvGeom{1, (int)H, (int)W, (int)C, R, S, pad_h, pad_w, stride_h, stride_w, (int)OH, (int)OW};
     return mm_common(a, st, (size_t)n_img * H * W * C * es);
 }

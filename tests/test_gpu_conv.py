@@ -45,7 +45,10 @@ CASES = [
     ("f16", "f16", 256, 300, 8, 8, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel, 300 tiles: more workgroups than compute units, two on some
     ("bf16", "f32", 192, 2, 11, 13, 128, 2, 3, (1, 0), (2, 1), "tiled"),    # tiled, two steps per tap, strides, ragged N = 132
     ("i8", "i32", 256, 4, 10, 10, 128, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel int8, one chunk (dense: tiled, 9 steps)
-    ("f16", "f32", 128, 2, 8, 8, 256, 1, 1, (0, 0), (1, 1), "tiled"),       # pointwise: plain product
+    ("f16", "f32", 128, 2, 8, 8, 256, 1, 1, (0, 0), (1, 1), "tiled"),       # pointwise: the plain product's kernels (N = 128: tiled)
+    ("i8", "i32", 64, 1, 4, 4, 256, 1, 1, (0, 0), (1, 1), "tiled"),         # pointwise on 16 pixels: the streaming kernel
+    ("bf16", "bf16", 256, 8, 16, 16, 512, 1, 1, (0, 0), (1, 1), "canonical"),  # pointwise, 2048 pixels, canonical layout
+    ("f16", "f16", 128, 2, 9, 9, 128, 1, 1, (0, 0), (2, 2), "tiled"),       # 1x1 with stride 2: still a gather
     ("bf16", "bf16", 64, 5, 9, 7, 64, 5, 3, (2, 1), (3, 2), "tiled"),       # 5x3 filter, stride 3x2
     ("f16", "f16", 2048, 64, 10, 10, 64, 3, 3, (1, 1), (1, 1), "tiled"),    # 8 x 25 tiles of 256x256 (eight-wavefront shape)
 ]
