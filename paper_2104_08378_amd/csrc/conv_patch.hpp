@@ -15,7 +15,7 @@
 //     one short run of the NHWC input: output pixel n = (img, oy, ox) meets, for tap (r, s), the input pixel with
 //     linear index lin0(n) + r*W + s, lin0(n) = (img*H + oy - pad_h)*W + ox - pad_w, and lin0 grows with n when
 //     the output is no larger than the input.  Per chunk of channels (one 128-byte step of K) that run -- the
-//     patch, at most kPatchRows pixels x 128 bytes -- is put into LDS once per chunk, and every tap reads its B
+//     patch, at most 192 or 256 pixels x 128 bytes -- is put into LDS once per chunk, and every tap reads its B
 //     fragments from it at a row offset of r*W + s.  Rows are 144 bytes apart, which keeps 16-byte reads of
 //     consecutive rows on distinct banks without an address swizzle, so the 8 fragments of a step sit at
 //     immediate offsets from one row address per output pixel; taps in the padding read a row of zeros;
@@ -39,9 +39,8 @@
 
 namespace sp24 {
 
-constexpr int kPatchRows = 192;                    // pixels a patch holds
+constexpr int kPatchRowsSmall = 192, kPatchRowsLarge = 256;   // pixels a patch holds: two sizes of the kernel
 constexpr int kPatchPitch = 144;                   // bytes from one patch row to the next in LDS
-constexpr int kPatchParts = kPatchRows / 8 / 4;    // 1 KiB parts (8 pixels) per wavefront and chunk
 
 // f(integral_constant<int, I>) for every I of the sequence, in order: a loop whose index is a constant in its body
 template <int... I, class F>
@@ -50,36 +49,37 @@ __device__ __forceinline__ void for_each_index(std::integer_sequence<int, I...>,
     (f(std::integral_constant<int, I>{}), ...);
 }
 
-// Can the patch kernel take this convolution?  (The caller has checked what the tiled kernels need.)
-inline bool conv_patch_fits(const MmArgs& a)
+// The pixels a tile's patch may span if the patch kernel can take this convolution, else 0.  (The caller has checked
+// what the tiled kernels need.)
+inline int64_t conv_patch_span(const MmArgs& a)
 {
     const ConvGeom& g = a.conv;
-    if (!g.on || !a.sparse || a.layout != SP24_LAYOUT_TILED) return false;
-    if (g.R != 3 || g.S != 3 || g.stride_h != 1 || g.stride_w != 1 || g.OH > g.H || g.OW > g.W) return false;
+    if (!g.on || !a.sparse || a.layout != SP24_LAYOUT_TILED) return 0;
+    if (g.R != 3 || g.S != 3 || g.stride_h != 1 || g.stride_w != 1 || g.OH > g.H || g.OW > g.W) return 0;
     // the compressed rows of one wavefront's two row blocks, as a buffer load's 32-bit offset
-    if (a.K * 64 >= (int64_t)1 << 31) return false;
+    if (a.K * 64 >= (int64_t)1 << 31) return 0;
     // rows a tile's patch spans at most: 128 consecutive output pixels, the extra input pixels at every change of
     // output row and image among them, and the reach of the filter
     const int64_t row_changes = 127 / g.OW + 1, img_changes = 127 / ((int64_t)g.OH * g.OW) + 1;
     const int64_t span = 128 + row_changes * (g.W - g.OW) + img_changes * (int64_t)(g.H - g.OH) * g.W + (int64_t)(g.R - 1) * g.W + g.S - 1;
-    return span <= kPatchRows;
+    return span <= kPatchRowsLarge ? span : 0;
 }
 
-template <int DT, int OUT>
-__global__ __launch_bounds__(256, 2) void k_conv_patch(MmArgs a, int tiles_m, int tiles_n)
+template <int DT, int OUT, int kPatchRows>
+__global__ __launch_bounds__(256, kPatchRows <= kPatchRowsSmall ? 2 : 1) void k_conv_patch(MmArgs a, int tiles_m, int tiles_n)
 {
     constexpr int ES = is8<DT> ? 1 : 2;
     constexpr int BK = kRowBytes / ES;                 // K elements (channels) per step
     constexpr int T64 = BK / 64;
     constexpr int WN = 2, TM = 2, TN = 2, BM = 128, BN = 128, RB = BM / 32;
     constexpr int NF = 2 * TN;                         // B fragments of a step: instruction j = f / TN, block nj = f % TN
-    constexpr int XP = kPatchParts;
+    constexpr int XP = kPatchRows / 8 / 4;             // 1 KiB parts (8 pixels) of a patch per wavefront
     constexpr int kLoadsA = TM * (is8<DT> ? 4 : 3);    // loads of a step's A per wavefront: values twice, codes once (twice for 8-bit)
-        constexpr int TAPS = 9, PF = 3;                    // PF: steps of A in registers, the one in use and two ahead; divides TAPS
+    constexpr int TAPS = 9, PF = 3;                    // PF: steps of A in registers, the one in use and two ahead; divides TAPS
     constexpr int kPitch = kPatchPitch;
     // LDS: two buffers, each the patch's rows and behind them a row of zeros: a row address is formed for buffer 0
-    // and reaches buffer 1 by an immediate offset, whichever row it is.  55 KiB, so that two workgroups share a
-    // compute unit where the grid has them
+    // and reaches buffer 1 by an immediate offset, whichever row it is.  55 KiB with the smaller patch, so that two
+    // workgroups share a compute unit where the grid has them; 74 KiB with the larger
     constexpr int kPatchBytes = (kPatchRows + 1) * kPitch;
     constexpr int kZeroOff = kPatchRows * kPitch;
     constexpr int kLdsBytes = 2 * kPatchBytes;
@@ -302,7 +302,8 @@ static sp24_status run_conv_patch(const MmArgs& a, hipStream_t st)
 {
     const int tiles_m = (int)((a.M + 127) / 128), tiles_n = (int)((a.N + 127) / 128);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-    k_conv_patch<DT, OUT><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    if (conv_patch_span(a) <= kPatchRowsSmall) k_conv_patch<DT, OUT, kPatchRowsSmall><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+    else k_conv_patch<DT, OUT, kPatchRowsLarge><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
     return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;
 }
 
@@ -311,7 +312,7 @@ static sp24_status run_conv_patch(const MmArgs& a, hipStream_t st)
 template <int DT, int OUT>
 static sp24_status pick_tile(const MmArgs& a, hipStream_t st)
 {
-    if (a.conv.on && ((a.M + 255) / 256) * ((a.N + 255) / 256) < 200 && conv_patch_fits(a)) return run_conv_patch<DT, OUT>(a, st);
+    if (a.conv.on && ((a.M + 255) / 256) * ((a.N + 255) / 256) < 200 && conv_patch_span(a) > 0) return run_conv_patch<DT, OUT>(a, st);
     return pick_tile_general<DT, OUT>(a, st);
 }
 

@@ -38,10 +38,12 @@ CASES = [
     ("f16", "f16", 96, 5, 9, 11, 192, 3, 3, (1, 1), (1, 1), "tiled"),       # patch kernel: three chunks, ragged M (three row blocks), N = 495
     ("bf16", "f32", 160, 40, 4, 4, 256, 3, 3, (1, 1), (1, 1), "tiled"),     # patch kernel: four chunks, a tile spans eight images, ragged M
     ("i8", "i32", 128, 3, 16, 8, 384, 3, 3, (0, 1), (1, 1), "tiled"),       # patch kernel: no vertical padding (output images shorter than input), int8, three chunks
-    ("i8", "i32", 128, 3, 13, 9, 384, 3, 3, (0, 0), (1, 1), "tiled"),       # no padding at all: a patch could span 222 pixels, the general tiled kernel
+    ("i8", "i32", 128, 3, 13, 9, 384, 3, 3, (0, 0), (1, 1), "tiled"),       # no padding at all: a patch may span 222 pixels, the 256-pixel patch kernel
+    ("f16", "f16", 128, 1, 56, 56, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # 56 pixels wide: patches of 242 pixels (the 256-pixel kernel), ragged N = 3136
+    ("bf16", "f32", 96, 2, 36, 20, 256, 3, 3, (1, 1), (1, 1), "tiled"),     # 20 wide and 36 tall, patches of 170 pixels, four chunks
     ("f16", "f32", 128, 2, 20, 20, 128, 3, 3, (1, 0), (1, 1), "tiled"),     # patch kernel: padding on one axis only, two chunks, output rows shorter than input, patch of up to 186 pixels
     ("bf16", "bf16", 256, 1, 24, 24, 320, 3, 3, (1, 1), (1, 1), "tiled"),   # patch kernel: five chunks, one image larger than a tile
-    ("f16", "f16", 128, 2, 30, 30, 64, 3, 3, (0, 0), (1, 1), "tiled"),      # 3x3 but a patch would span 198 pixels: the general tiled kernel
+    ("f16", "f16", 128, 2, 30, 30, 64, 3, 3, (0, 0), (1, 1), "tiled"),      # 3x3 but a patch would span 260 pixels: the general tiled kernel
     ("f16", "f16", 256, 300, 8, 8, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel, 300 tiles: more workgroups than compute units, two on some
     ("bf16", "f32", 192, 2, 11, 13, 128, 2, 3, (1, 0), (2, 1), "tiled"),    # tiled, two steps per tap, strides, ragged N = 132
     ("i8", "i32", 256, 4, 10, 10, 128, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel int8, one chunk (dense: tiled, 9 steps)
