@@ -2,11 +2,12 @@
 // straight into registers (Sec. 3.2: convolutions are GEMM-like with the sparse tensor first; Sec. 4.2: inner
 // dimension C x R x S; Sec. 3.1: the compressed operand needs no indirection and is read with full-width accesses).
 //
-// The kernel is for outputs with too few tiles for the 256 x 256 shape: 128 x 128 tiles, one workgroup of four
-// wavefronts per compute unit, i.e. ONE wavefront per SIMD.  A lone wavefront issues at most one instruction every
+// The kernel was written for outputs with too few tiles for the 256 x 256 shape: 128 x 128 tiles, one workgroup of
+// four wavefronts per compute unit, i.e. ONE wavefront per SIMD (it serves larger outputs too: it turned out no
+// slower per product than the 256 x 256 kernels).  A lone wavefront issues at most one instruction every
 // four clocks, and the 8 matrix instructions of a step (16-bit inputs) occupy the matrix core for 256 clocks: a
 // step stays at that pace only while it has well under 64 instructions.  Counters of the general implicit-GEMM
-// path on this shape show where its 0.34 us (820 clocks) per step go: the matrix cores are busy a fifth of the
+// path on a shape of 196 tiles show where its 0.34 us (820 clocks) per step go: the matrix cores are busy a fifth of the
 // time, and more than half of all wavefront cycles are instruction issue -- the per-tap gather addresses, the LDS
 // transfers with their M0 writes, 18 LDS operand reads, the counters.  Three properties of the problem remove
 // most of that work:
