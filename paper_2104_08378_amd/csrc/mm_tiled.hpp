@@ -986,7 +986,11 @@ static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
     // one workgroup of eight wavefronts of 64x128 each per compute unit (its wavefronts sit two to a SIMD, so that
     // one computes while the other waits); measured
     // faster than four of 128x128 on the short-K transformer shape and equal on the long-K square one
-    if (big >= 200) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
+    // -- unless the large tile would be mostly padding: rows and columns it covers beyond M and N are computed all the
+    // same, and per product computed the small tile (two workgroups to a unit) costs about a third more
+    const double cover_big = (double)(((a.M + 255) / 256) * 256) * (double)(((a.N + 255) / 256) * 256);
+    const double cover_small = (double)(((a.M + 127) / 128) * 128) * (double)(((a.N + 127) / 128) * 128);
+    if (big >= 200 && cover_big <= 1.35 * cover_small) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
     // 128x128 tiles, four wavefronts.  With few tiles one workgroup per compute unit is all there is, and a short
     // step (a quarter of the large tile's arithmetic) hides little latency: six (dense: four) stages, transfers
     // five (three) steps ahead.  With many tiles three (two) stages leave room for two workgroups per compute unit.
