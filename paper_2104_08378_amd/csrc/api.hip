@@ -323,13 +323,13 @@ static sp24_status mm_common(const MmArgs& a, hipStream_t st, size_t x_bytes = 0
 // with the least estimated time among the candidates, where splitting costs 6 us (8 us for the streaming kernel:
 // the second kernel and the shorter pipelines) plus the partial images written and read once at 4 TB/s, and must
 // win by a tenth.
-//  * N > 32, M >= 64 (tiled kernels, 128x128 tiles): 1 .. min(8, compute units / tiles, steps / 4) slices of whole
+//  * N > 32 (tiled kernels, 128x128 tiles; rows past M are computed on a valid row and never stored): 1 .. min(8, compute units / tiles, steps / 4) slices of whole
 //    128-byte steps; a launch takes 5 us plus 400 ns per step of its workgroups (fitted to measurements of both
 //    types at 16 - 128 steps, operands from HBM).
 //  * N <= 32, M >= 32 (streaming kernel, one workgroup per 32 rows): 1 .. min(8, compute units / row blocks,
 //    tiles / 32) slices of whole 64-column tiles; a workgroup takes 130 ns (16-bit) or 80 ns (8-bit) per tile of
 //    its 32 rows (measured at K = 16384: latency-bound, the same whether 16 or 128 workgroups run).
-//  * M < 32: not split (the general kernel).
+//  * N <= 32, M < 32: not split (the general kernel).
 struct SplitPlan {
     int slices, slice_steps;    // slice_steps in the kernel's own unit: 128-byte steps, or 64-column tiles
     bool streaming;             // the N <= 32 kernel
@@ -339,7 +339,7 @@ struct SplitPlan {
 static SplitPlan split_plan(int64_t M, int64_t N, int64_t K, sp24_dtype in)
 {
     SplitPlan p = {1, 0, N <= 32, 0, 0};
-    if (M < 32 || (N > 32 && M < 64)) return p;
+    if (N <= 32 && M < 32) return p;
     const int es = esize_of(in);
     const int64_t ldw = (N + 3) / 4 * 4;
     int64_t units, most, unit_ns, base_ns, fixed_ns;         // K in the kernel's units; slices at most; time per unit; per launch; cost of splitting

@@ -211,7 +211,8 @@ def test_split_product_validation_and_workspace_size():
     assert w(2048, 256, 4096, sp24.I8) == 0                              # the images would cost more than the steps saved
     assert w(8192, 128, 8192, sp24.I8) == 4 * 8192 * 128 * 4
     assert w(4096, 4096, 1024, sp24.BF16) == 0                           # fills the chip: not split
-    assert w(32, 256, 8192, sp24.I8) == 0                                # M < 64 at N > 32: the general kernel's shape
+    assert w(32, 256, 8192, sp24.I8) == 8 * 32 * 256 * 4                 # few rows: two 128x128 tiles, 64 steps
+    assert w(8, 256, 8192, sp24.F16) == 8 * 8 * 256 * 4 and w(8, 32, 8192, sp24.F16) == 0   # N <= 32, M < 32: the general kernel
     # N <= 32 (one workgroup per 32 rows): slices of whole 64-column tiles, 130 / 80 ns per tile, a split costs 8 us
     assert w(8192, 16, 8192, sp24.BF16) == 0                             # 256 row blocks fill the chip
     assert w(4096, 16, 16384, sp24.BF16) == 2 * 4096 * 16 * 4

@@ -42,6 +42,8 @@ CASES = [
     ("f16", "f16", 128, 1, 56, 56, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # 56 pixels wide: patches of 242 pixels (the 256-pixel kernel), ragged N = 3136
     ("bf16", "f32", 96, 2, 36, 20, 256, 3, 3, (1, 1), (1, 1), "tiled"),     # 20 wide and 36 tall, patches of 170 pixels, four chunks
     ("f16", "f32", 128, 2, 20, 20, 128, 3, 3, (1, 0), (1, 1), "tiled"),     # patch kernel: padding on one axis only, two chunks, output rows shorter than input, patch of up to 186 pixels
+    ("f16", "f16", 32, 2, 12, 12, 128, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel with a single row block of filters
+    ("bf16", "f32", 24, 2, 10, 10, 64, 3, 3, (1, 1), (1, 1), "canonical"),  # fewer filters than a row block: the tiled kernel
     ("bf16", "bf16", 256, 1, 24, 24, 320, 3, 3, (1, 1), (1, 1), "tiled"),   # patch kernel: five chunks, one image larger than a tile
     ("f16", "f16", 128, 2, 30, 30, 64, 3, 3, (0, 0), (1, 1), "tiled"),      # 3x3 but a patch would span 260 pixels: the general tiled kernel
     ("f16", "f16", 256, 300, 8, 8, 64, 3, 3, (1, 1), (1, 1), "tiled"),      # patch kernel, 300 tiles: more workgroups than compute units, two on some

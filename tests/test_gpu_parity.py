@@ -232,6 +232,26 @@ def test_dense_tiled_kernels_match_oracle(case):
     run_mm_case(*case, layout="canonical", b_order="k", sparse=False, seed=3)
 
 
+FEW_ROWS_CASES = [
+    # fewer rows than a 128x128 tile, down to one: the tiled kernels compute the missing rows on a valid one and store none of them
+    ("f16", "f32", 1, 96, 128),
+    ("i8", "i32", 8, 304, 256),
+    ("bf16", "bf16", 33, 520, 192),
+    ("i8", "i32", 48, 128, 640),
+    ("f16", "f16", 32, 1000, 128),        # one row block: also in the tiled layout
+    ("bf16", "f32", 31, 4104, 64),
+]
+
+
+@pytest.mark.parametrize("case", FEW_ROWS_CASES)
+@pytest.mark.parametrize("b_order", ["k", "n"])
+def test_products_with_few_rows_match_oracle(case, b_order):
+    run_mm_case(*case, layout="canonical", b_order=b_order, sparse=True, seed=12)
+    run_mm_case(*case, layout="canonical", b_order=b_order, sparse=False, seed=13)
+    if case[2] % 32 == 0:
+        run_mm_case(*case, layout="tiled", b_order=b_order, sparse=True, seed=14)
+
+
 NMAJOR_CASES = [
     # B stored N-major (element (k, n) at B[k*ldb + n]) on the tiled kernels: transposing LDS reads
     ("i8", "i32", 320, 304, 256),         # 128x128 tiles, ragged N (a whole number of 16-byte chunks)

@@ -27,6 +27,8 @@ CASES = [
     ("f16", "f16", 128, 65, 4096, "canonical", "k"),    # odd N: rows of the partial images padded to 68
     ("bf16", "bf16", 4096, 64, 8192, "tiled", "k"),     # 32 tiles, 128 steps
     ("bf16", "bf16", 320, 40, 4096, "canonical", "k"),  # ragged M and N
+    ("i8", "i32", 32, 256, 4096, "tiled", "k"),         # one row block: two tiles with 96 rows never stored
+    ("f16", "f32", 8, 200, 4096, "canonical", "n"),     # fewer rows than a row block
     # N <= 32: the streaming kernel, slices of whole 64-column tiles
     ("bf16", "bf16", 1024, 16, 8192, "tiled", "k"),     # 32 row blocks, 4 slices
     ("i8", "i32", 512, 32, 16384, "canonical", "k"),    # 16 row blocks, 8 slices
@@ -96,7 +98,7 @@ def test_workspace_contents_are_ignored_and_a_workspace_serves_calls_of_differen
         ws.fill_(0xFF)
 
 
-@pytest.mark.parametrize("dtype,out,M,N,K", [("bf16", "bf16", 512, 16, 1024), ("i8", "i32", 32, 256, 4096), ("f16", "f32", 256, 256, 128)])
+@pytest.mark.parametrize("dtype,out,M,N,K", [("bf16", "bf16", 512, 16, 1024), ("i8", "i32", 16, 32, 4096), ("f16", "f32", 256, 256, 128)])
 def test_shapes_that_are_not_split_take_the_unsplit_path(dtype, out, M, N, K):
     """Workspace size 0: the call is the unsplit product, bit for bit, and needs no workspace."""
     assert sp24.sp24_splitk_workspace_bytes(M, N, K, IN_DT[dtype]) == 0
