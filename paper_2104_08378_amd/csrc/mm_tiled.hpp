@@ -981,16 +981,22 @@ static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
 template <int DT, int OUT>
 static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
 {
-    // 256x256 tiles when they still fill the 256 compute units, else 128x128
+    // 256x256 tiles when there are enough of them for half the chip, else 128x128
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
     // one workgroup of eight wavefronts of 64x128 each per compute unit (its wavefronts sit two to a SIMD, so that
-    // one computes while the other waits); measured
-    // faster than four of 128x128 on the short-K transformer shape and equal on the long-K square one
+    // one computes while the other waits).  The large tile moves half the operand bytes per product through the
+    // L2 and LDS, and that outweighs idle compute units well below a full chip.  Measured on 100 - 192 large tiles,
+    // K from 512 to 8192, operands from HBM: up to 128 large tiles the 512 small ones run in one round, two
+    // workgroups to a unit, and the two shapes are level (the small one ahead by 10 - 17 % at K <= 1024); from
+    // there on the small tiles need a second round and the large tile wins by 10 - 26 % (sparse), 3 - 38 % (dense).
+    // The 16-bit dense product, the one that moves the most bytes per instruction, gains 7 - 14 % from 100 tiles on.
+    // Convolutions keep the earlier rule (a full chip's worth).
     // -- unless the large tile would be mostly padding: rows and columns it covers beyond M and N are computed all the
     // same, and per product computed the small tile (two workgroups to a unit) costs about a third more
+    const int64_t enough = a.conv.on ? 200 : (!is8<DT> && !a.sparse) ? 100 : 129;
     const double cover_big = (double)(((a.M + 255) / 256) * 256) * (double)(((a.N + 255) / 256) * 256);
     const double cover_small = (double)(((a.M + 127) / 128) * 128) * (double)(((a.N + 127) / 128) * 128);
-    if (big >= 200 && cover_big <= 1.35 * cover_small) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
+    if (big >= enough && cover_big <= 1.35 * cover_small) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
     // 128x128 tiles, four wavefronts.  With few tiles one workgroup per compute unit is all there is, and a short
     // step (a quarter of the large tile's arithmetic) hides little latency: six (dense: four) stages, transfers
     // five (three) steps ahead.  With many tiles three (two) stages leave room for two workgroups per compute unit.

@@ -218,7 +218,9 @@ TILED_CASES = [
     # more tiles than compute units (several rounds of workgroups), interior and edge tiles
     ("i8", "i32", 4352, 4000, 384),       # 17 x 16 tiles of 256x256, ragged N, 3 steps
     ("bf16", "bf16", 4384, 4001, 128),    # 18 x 16 tiles, ragged M, odd N (no 16-byte stores), 2 steps
-    ("f16", "f32", 3040, 3300, 192),      # 24 x 26 tiles of 128x128, ragged both ways, 3 steps
+    ("f16", "f32", 2400, 2500, 192),      # sparse: 19 x 20 tiles of 128x128, two workgroups to a unit; dense: 10 x 10 tiles of 256x256; ragged both ways, 3 steps
+    ("f16", "f32", 3040, 3300, 192),      # 12 x 13 tiles of 256x256: fewer than compute units, ragged both ways
+    ("i8", "i32", 3008, 2800, 256),       # 12 x 11 tiles of 256x256: just past what 128x128 tiles cover in one round
 ]
 
 
