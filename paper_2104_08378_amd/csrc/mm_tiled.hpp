@@ -990,10 +990,11 @@ static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
     // workgroups to a unit, and the two shapes are level (the small one ahead by 10 - 17 % at K <= 1024); from
     // there on the small tiles need a second round and the large tile wins by 10 - 26 % (sparse), 3 - 38 % (dense).
     // The 16-bit dense product, the one that moves the most bytes per instruction, gains 7 - 14 % from 100 tiles on.
-    // Convolutions keep the earlier rule (a full chip's worth).
+    // Convolutions follow the general rule (dense 16-bit at 108 tiles: the large tile 40 % slower; at 154 - 196: 7 - 20 %
+    // faster, strided sparse ones 25 - 28 %).
     // -- unless the large tile would be mostly padding: rows and columns it covers beyond M and N are computed all the
     // same, and per product computed the small tile (two workgroups to a unit) costs about a third more
-    const int64_t enough = a.conv.on ? 200 : (!is8<DT> && !a.sparse) ? 100 : 129;
+    const int64_t enough = (!a.conv.on && !is8<DT> && !a.sparse) ? 100 : 129;
     const double cover_big = (double)(((a.M + 255) / 256) * 256) * (double)(((a.N + 255) / 256) * 256);
     const double cover_small = (double)(((a.M + 127) / 128) * 128) * (double)(((a.N + 127) / 128) * 128);
     if (big >= enough && cover_big <= 1.35 * cover_small) return run_pipe<DT, OUT, 4, 2, 2, 4, 3, 2>(a, st);
