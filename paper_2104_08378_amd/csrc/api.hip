@@ -297,17 +297,38 @@ static sp24_status mm_validate(const MmArgs& a, size_t x_bytes, bool* empty)
     return SP24_OK;
 }
 
+// N <= 32 with very many rows: the tiled kernels (one 128x128 tile per 128 rows, most of its columns unused) overtake
+// the streaming kernel, whose workgroups of 32 rows each re-read all of B and run in more than one round past 256
+// row blocks.  Measured at K = 4096 and 8192, operands from HBM, in tiles = ceil(M / 128): N > 16 from 86 tiles on
+// (11008 rows: level for sparse, dense 18 - 25 % faster); N <= 16: the 16-bit sparse product from 192 tiles on
+// (32000 x 4096, N = 1: 36.4 -> 32.4 us; 128256 rows: 133 -> 117 us), the 16-bit dense one from 160 tiles while
+// they run in one round (past that only for N > 8), the 8-bit dense one for N > 8 from 160 tiles; the 8-bit sparse
+// product stays with the streaming kernel (10 - 20 % ahead at N <= 8 up to 128256 rows).
+static bool tiled_before_streaming(const MmArgs& a)
+{
+    if (a.N > 32) return true;                             // the streaming kernel does not take it anyway
+    const int64_t tiles = (a.M + 127) / 128;
+    if (a.N > 16) return tiles >= 86;
+    if (esize_of(a.in) == 2) return a.sparse ? tiles >= 192 : tiles >= 160 && (tiles <= 256 || a.N > 8);
+    return !a.sparse && a.N > 8 && tiles >= 160;
+}
+
 // The kernel for a checked product: streaming (N <= 32), tiled, or general.
 static sp24_status mm_dispatch(const MmArgs& a, hipStream_t st)
 {
     bool handled = false;
     sp24_status s;
-    if (!a.conv.on) {
+    const bool tiled_first = a.conv.on || tiled_before_streaming(a);
+    if (!tiled_first) {
         s = launch_mm_skinny(a, st, &handled);
         if (handled) return s;
     }
     s = launch_mm_tiled(a, st, &handled);
     if (handled) return s;
+    if (tiled_first && !a.conv.on) {
+        s = launch_mm_skinny(a, st, &handled);
+        if (handled) return s;
+    }
     return launch_mm_simple(a, st);
 }
 

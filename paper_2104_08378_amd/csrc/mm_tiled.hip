@@ -29,12 +29,12 @@ sp24_status launch_mm_tiled(const MmArgs& a, hipStream_t st, bool* handled)
     const int es = esize_of(a.in);
     // K: whole 32-byte runs (a last, partial step is filled up with zeros)
     bool ok = a.bo == SP24_B_KMAJOR && (a.K * es) % 32 == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 &&
-              (a.ldb * es) % 16 == 0 && a.N >= 32 && a.M >= 1 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
+              (a.ldb * es) % 16 == 0 && a.N >= 1 && a.M >= 1 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
               a.ldb * es < ((int64_t)1 << 22) && ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
     if (!a.conv.on && a.bo == SP24_B_NMAJOR) {
         // N-major B: whole 16-byte chunks of columns, rows 16-byte aligned, 32-bit row offsets within a step
         ok = (a.K * es) % 32 == 0 && (reinterpret_cast<uintptr_t>(a.B) & 15u) == 0 && (a.ldb * es) % 16 == 0 &&
-             (a.N * es) % 16 == 0 && a.N >= 32 && a.M >= 1 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
+             (a.N * es) % 16 == 0 && a.N >= 1 && a.M >= 1 && a.M <= ((int64_t)1 << 30) && a.N <= ((int64_t)1 << 30) &&
              a.ldb * es < ((int64_t)1 << 22) && ((a.M + 127) / 128) * ((a.N + 127) / 128) < ((int64_t)1 << 30);
     }
     if (a.conv.on) {

@@ -254,6 +254,29 @@ def test_products_with_few_rows_match_oracle(case, b_order):
         run_mm_case(*case, layout="tiled", b_order=b_order, sparse=True, seed=14)
 
 
+FEW_COLUMNS_CASES = [
+    # N <= 32 where the tiled kernels run instead of the streaming one (very many rows), and products small both ways
+    ("bf16", "bf16", 24704, 1, 64),       # 193 tiles of 128 rows: sparse and dense 16-bit, a single column
+    ("f16", "f32", 24704, 7, 128),
+    ("i8", "i32", 20608, 12, 128),        # 161 tiles: the dense 8-bit product (N > 8); the sparse one streams
+    ("bf16", "f32", 11008, 24, 192),      # N > 16 from 86 tiles on
+    ("i8", "i32", 11136, 32, 256),
+    ("f16", "f16", 16, 16, 256),          # fewer than 32 rows and columns
+    ("i8", "i32", 8, 31, 128),
+]
+
+
+@pytest.mark.parametrize("case", FEW_COLUMNS_CASES)
+def test_products_with_few_columns_on_the_tiled_kernels_match_oracle(case):
+    run_mm_case(*case, layout="canonical", b_order="k", sparse=True, seed=15)
+    run_mm_case(*case, layout="canonical", b_order="k", sparse=False, seed=16)
+    if case[2] % 32 == 0:
+        run_mm_case(*case, layout="tiled", b_order="k", sparse=True, seed=17)
+    if case[3] * (1 if case[0] == "i8" else 2) % 16 == 0:
+        run_mm_case(*case, layout="canonical", b_order="n", sparse=True, seed=18)
+        run_mm_case(*case, layout="canonical", b_order="n", sparse=False, seed=19)
+
+
 NMAJOR_CASES = [
     # B stored N-major (element (k, n) at B[k*ldb + n]) on the tiled kernels: transposing LDS reads
     ("i8", "i32", 320, 304, 256),         # 128x128 tiles, ragged N (a whole number of 16-byte chunks)
