@@ -170,6 +170,14 @@ MM_CASES = [
 ]
 
 
+def unaligned_rows(B):
+    """The same matrix as a view whose rows start K + 4 elements apart: no 16-byte alignment, so the products run
+    the general kernel."""
+    wide = torch.zeros((B.shape[0], B.shape[1] + 4), dtype=B.dtype, device=B.device)
+    wide[:, :B.shape[1]] = B
+    return wide[:, :B.shape[1]]
+
+
 def run_mm_case(dtype, out, M, N, K, layout, b_order, sparse, seed=0):
     A, Bt = synth.make(NAME_OF[dtype], M=M, N=N, K=K, seed=seed)
     Pn = oracle.prune(A, dtype)
@@ -399,11 +407,11 @@ def test_empty_problem_is_a_no_op():
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("out", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("shape", [(64, 64, 64), (256, 320, 128)])          # the general kernel, the tiled kernel
+@pytest.mark.parametrize("shape", [(64, 64, 64, True), (64, 64, 64, False), (256, 320, 128, False)])   # the general kernel (B rows unaligned), the tiled kernel
 def test_special_values_reach_the_output_as_ieee_conversion_gives_them(dtype, out, shape):
     """Small integers (sums exact in any order), a NaN weight, infinities and sums beyond the 16-bit ranges: the stored
     result is the exact sum converted once, round to nearest even -- NaN stays NaN, overflow becomes infinity."""
-    M, N, K = shape
+    M, N, K, general = shape
     rng = np.random.default_rng(31)
     A = rng.integers(-3, 4, size=(M, K)).astype(np.float64)
     B = rng.integers(-4, 5, size=(K, N)).astype(np.float64)
@@ -417,8 +425,9 @@ def test_special_values_reach_the_output_as_ieee_conversion_gives_them(dtype, ou
     Abits, Bbits = synth.to_bits(A, dtype), synth.to_bits(np.ascontiguousarray(B.T), dtype)      # B stored K-major
     P = oracle.prune(Abits, dtype)
     V, meta = sp24.sp24_compress(to_gpu(Abits, dtype))
-    D = sp24.sp24_spmm(V, meta, to_gpu(Bbits, dtype), OUT_DT[out])
-    Dd = sp24.sp24_gemm_dense(to_gpu(P, dtype), to_gpu(Bbits, dtype), OUT_DT[out])
+    Bd = unaligned_rows(to_gpu(Bbits, dtype)) if general else to_gpu(Bbits, dtype)
+    D = sp24.sp24_spmm(V, meta, Bd, OUT_DT[out])
+    Dd = sp24.sp24_gemm_dense(to_gpu(P, dtype), Bd, OUT_DT[out])
     torch.cuda.synchronize()
     with np.errstate(invalid="ignore", over="ignore"):
         ref = oracle.gemm(P, synth.to_bits(B, dtype), dtype)                                      # fp64
@@ -433,11 +442,11 @@ def test_special_values_reach_the_output_as_ieee_conversion_gives_them(dtype, ou
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("shape", [(64, 64, 64), (64, 16, 128), (256, 320, 128)])   # general, skinny and tiled kernels
+@pytest.mark.parametrize("shape", [(64, 64, 64, True), (64, 16, 128, False), (256, 320, 128, False)])   # general (B rows unaligned), skinny and tiled kernels
 def test_removed_positions_take_no_part_in_the_sum(dtype, shape):
     """Sec. 3.2: the products with removed weights are skipped, not computed -- an infinity in B opposite a removed
     position leaves the result finite (the dense product of the pruned matrix has 0 * inf = NaN there)."""
-    M, N, K = shape
+    M, N, K, general = shape
     rng = np.random.default_rng(37)
     A = rng.integers(1, 4, size=(M, K)).astype(np.float64) * rng.choice([-1.0, 1.0], size=(M, K))
     B = rng.integers(-4, 5, size=(K, N)).astype(np.float64)
@@ -451,7 +460,8 @@ def test_removed_positions_take_no_part_in_the_sum(dtype, shape):
         if layout == "tiled" and (M % 32 or K % 64):
             continue
         V, meta = sp24.sp24_compress(to_gpu(Abits, dtype), layout=layout)
-        D = sp24.sp24_spmm(V, meta, to_gpu(synth.to_bits(np.ascontiguousarray(Binf.T), dtype), dtype), torch.float32, layout=layout)
+        Bd = to_gpu(synth.to_bits(np.ascontiguousarray(Binf.T), dtype), dtype)
+        D = sp24.sp24_spmm(V, meta, unaligned_rows(Bd) if general else Bd, torch.float32, layout=layout)
         torch.cuda.synchronize()
         ref = oracle.gemm(oracle.prune(Abits, dtype), synth.to_bits(B, dtype), dtype)     # the finite B: rows 20, 21 never count
         assert torch.equal(D.cpu(), torch.from_numpy(ref).to(torch.float32)), (dtype, shape, layout)
@@ -462,10 +472,12 @@ def test_int8_product_with_minus_128_in_both_operands():
     the integer matrix instructions exactly, in the general, the streaming and both tiled kernels."""
     rng = np.random.default_rng(91)
     pool = np.array([-128, -128, -127, 127, -1, 0, 1, 64], dtype=np.int8)
-    for M, N, K, layout in ((33, 17, 64, "canonical"), (64, 16, 256, "tiled"), (256, 160, 384, "tiled"), (128, 128, 128, "canonical"),
-                            (3840, 3840, 128, "tiled")):
+    for M, N, K, layout, general in ((33, 17, 64, "canonical", True), (33, 17, 64, "canonical", False), (64, 16, 256, "tiled", False),
+                                     (256, 160, 384, "tiled", False), (128, 128, 128, "canonical", False), (3840, 3840, 128, "tiled", False)):
         A, Bt = rng.choice(pool, size=(M, K)), rng.choice(pool, size=(N, K))
         Ad, Bd = to_gpu(A, "i8"), to_gpu(Bt, "i8")
+        if general:
+            Bd = unaligned_rows(Bd)
         V, meta = sp24.sp24_compress(Ad, layout=layout)
         D = sp24.sp24_spmm(V, meta, Bd, torch.int32, layout=layout)
         Dd = sp24.sp24_gemm_dense(sp24.sp24_prune(Ad), Bd, torch.int32)

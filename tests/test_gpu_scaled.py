@@ -14,8 +14,10 @@ pytestmark = pytest.mark.gpu
 
 CASES = [
     # M, N, K, layout                     -- kernel that serves it
-    (45, 70, 96, "canonical"),            # general, ragged
-    (64, 200, 128, "tiled"),              # general / 128x128 tiled depending on size rules
+    (45, 70, 96, "canonical"),            # 128x128 tile, ragged both ways, fewer rows than a tile
+    (64, 200, 128, "tiled"),
+    (8, 300, 128, "canonical"),           # fewer rows than a row block
+    (11136, 24, 128, "tiled"),            # N <= 32 on the tiled kernels (many rows)
     (128, 16, 2112, "tiled"),             # skinny (N <= 32)
     (320, 300, 256, "tiled"),             # 128x128 tiles, ragged N
     (4096, 3328, 256, "tiled"),           # 256x256 tiles, eight wavefronts
@@ -54,7 +56,27 @@ def test_int8_output_is_bit_exact(case, sparse):
         assert len(np.unique(got)) > 20
 
 
-@pytest.mark.parametrize("case", CASES[:4])
+@pytest.mark.parametrize("sparse", [True, False])
+def test_int8_output_from_the_general_kernel_is_bit_exact(sparse):
+    """Rows of B that are not 16-byte aligned (a view with a leading dimension of K + 4): the general kernel."""
+    M, N, K = 45, 70, 96
+    A, Bt, w_scale, bias, x_scale = make(M, N, K, 6)
+    Pn = oracle.prune(A, "i8")
+    acc = oracle.gemm(Pn, np.ascontiguousarray(Bt.T), "i8")
+    ws, bs = torch.from_numpy(w_scale).cuda(), torch.from_numpy(bias).cuda()
+    wide = torch.zeros((N, K + 4), dtype=torch.int8, device="cuda")
+    wide[:, :K] = to_gpu(Bt, "i8")
+    Bd = wide[:, :K]
+    if sparse:
+        V, meta = sp24.sp24_compress(to_gpu(A, "i8"))
+        D = sp24.sp24_spmm_i8_scaled(V, meta, Bd, torch.int8, ws, x_scale, bs, True, 29.5)
+    else:
+        D = sp24.sp24_gemm_dense_i8_scaled(to_gpu(Pn, "i8"), Bd, torch.int8, ws, x_scale, bs, True, 29.5)
+    torch.cuda.synchronize()
+    assert np.array_equal(D.cpu().numpy(), oracle.requant(acc, w_scale, x_scale, 29.5, bias, True))
+
+
+@pytest.mark.parametrize("case", CASES[:6])
 @pytest.mark.parametrize("out", ["f32", "f16", "bf16"])
 def test_float_outputs_match_the_double_epilogue(case, out):
     M, N, K, layout = case
