@@ -58,6 +58,32 @@ def test_full_size_workload(name):
             assert rel_err(out_to_f64(got), ref, rms) <= 1e-2, name
 
 
+@pytest.mark.parametrize("dt,out,M,N,K", [("bf16", "bf16", 32000, 1, 4096), ("bf16", "bf16", 32000, 32, 4096),
+                                          ("i8", "i32", 32000, 16, 4096), ("f16", "f32", 11008, 24, 4096)])
+def test_full_size_tall_products_with_few_columns(dt, out, M, N, K):
+    """The output projection of a language model on a handful of tokens: N <= 32 with so many rows that the tiled
+    kernels run instead of the streaming one (the 8-bit sparse product at N <= 16 stays with the streaming kernel)."""
+    A, Bt = synth.make({"bf16": "ffn_bf16", "f16": "tiny_f16", "i8": "square_i8"}[dt], M=M, N=N, K=K, seed=41)
+    Ad, Bd = to_gpu(A, dt), to_gpu(Bt, dt)
+    V, meta = sp24.sp24_compress(Ad, layout="tiled")
+    P = sp24.sp24_prune(Ad)
+    D = sp24.sp24_spmm(V, meta, Bd, OUT_DT[out], layout="tiled")
+    Dd = sp24.sp24_gemm_dense(P, Bd, OUT_DT[out])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(43)
+    rows = np.unique(np.concatenate([[0, 31, 32, 127, 128, M - 129, M - 128, M - 1], rng.integers(0, M, 120)]))
+    ref = oracle.gemm(oracle.prune(np.ascontiguousarray(A[rows]), dt), np.ascontiguousarray(Bt.T), dt)
+    for got_t in (D, Dd):
+        got = got_t[torch.as_tensor(rows, device="cuda")]
+        if dt == "i8":
+            assert np.array_equal(got.cpu().numpy(), ref)
+        else:
+            rms = float(np.sqrt(np.mean(ref * ref)))
+            assert rel_err(out_to_f64(got), ref, rms) <= 1e-2
+    if dt == "i8":
+        assert torch.equal(D, Dd)
+
+
 def test_full_size_convolution_without_im2col():
     """conv3x3_f16 as its title says, an implicit GEMM on the NHWC activations: sampled filters x pixels against
     the oracle's direct convolution of whole images (the images that hold the sampled pixels)."""
