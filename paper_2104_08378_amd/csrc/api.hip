@@ -297,20 +297,23 @@ static sp24_status mm_validate(const MmArgs& a, size_t x_bytes, bool* empty)
     return SP24_OK;
 }
 
-// N <= 32 with very many rows: the tiled kernels (one 128x128 tile per 128 rows, most of its columns unused) overtake
-// the streaming kernel, whose workgroups of 32 rows each re-read all of B and run in more than one round past 256
-// row blocks.  Measured at K = 4096 and 8192, operands from HBM, in tiles = ceil(M / 128): N > 16 from 86 tiles on
-// (11008 rows: level for sparse, dense 18 - 25 % faster); N <= 16: the 16-bit sparse product from 192 tiles on
-// (32000 x 4096, N = 1: 36.4 -> 32.4 us; 128256 rows: 133 -> 117 us), the 16-bit dense one from 160 tiles while
-// they run in one round (past that only for N > 8), the 8-bit dense one for N > 8 from 160 tiles; the 8-bit sparse
-// product stays with the streaming kernel (10 - 20 % ahead at N <= 8 up to 128256 rows).
+// N <= 32: where the tiled kernels (tiles of 64 or 128 rows, most of their columns unused) overtake the streaming
+// kernel, whose workgroups of 32 rows each re-read all of B and run in more than one round past 256 row blocks.
+// Measured at K = 4096 and 8192, M = 2048 .. 128256, operands from HBM, in tiles = ceil(M / 128):
+//  * N > 16: the dense product always (M = 4096, K = 8192, N = 32: 40.6 -> 32.6 us), the sparse one from 86 tiles on
+//    (11008 rows; below that it depends on M, within 15 % either way);
+//  * N <= 16, 16-bit: from 86 tiles on, sparse 3 - 10 % faster up to 128 tiles (64-row tiles), level to 191, then
+//    ahead for good (32000 x 4096, N = 1: 36.4 -> 31.5 us; 128256 rows: 133 -> 117 us); dense 15 - 30 % faster
+//    at 86 - 256 tiles, past that only for N > 8;
+//  * N <= 16, 8-bit: the dense product for N > 8 from 86 tiles on; the sparse one stays with the streaming kernel
+//    (10 - 20 % ahead at N <= 8 up to 128256 rows, level at N = 16).
 static bool tiled_before_streaming(const MmArgs& a)
 {
     if (a.N > 32) return true;                             // the streaming kernel does not take it anyway
     const int64_t tiles = (a.M + 127) / 128;
-    if (a.N > 16) return tiles >= 86;
-    if (esize_of(a.in) == 2) return a.sparse ? tiles >= 192 : tiles >= 160 && (tiles <= 256 || a.N > 8);
-    return !a.sparse && a.N > 8 && tiles >= 160;
+    if (a.N > 16) return !a.sparse || tiles >= 86;
+    if (esize_of(a.in) == 2) return tiles >= 86 && (a.sparse || tiles <= 256 || a.N > 8);
+    return !a.sparse && a.N > 8 && tiles >= 86;
 }
 
 // The kernel for a checked product: streaming (N <= 32), tiled, or general.

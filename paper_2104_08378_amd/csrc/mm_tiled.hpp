@@ -1002,6 +1002,19 @@ static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
     // step (a quarter of the large tile's arithmetic) hides little latency: six (dense: four) stages, transfers
     // five (three) steps ahead.  With many tiles three (two) stages leave room for two workgroups per compute unit.
     const int64_t small = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+    // At most 128 of them: tiles of 64 rows, two wavefronts, put twice as many compute units to work.  Such a product
+    // is bound by what one unit can keep in flight (its LDS ring against the latency of the L2 and of HBM), not
+    // by arithmetic; the smaller stages also allow a deeper ring, and with N <= 64 a 64-column tile does not fetch
+    // B rows that do not exist.  Measured on 16 shapes per type, operands from HBM: the sparse product 28 - 31 %
+    // faster at N <= 64 (8192 x 64 x 8192 bf16: 43.8 -> 31.5 us), 6 - 17 % at N = 96 .. 128, 5 - 14 % on small
+    // squarish shapes; the dense one 23 - 34 % and 15 - 25 % in a single column of tiles, but 10 - 15 % (16-bit)
+    // slower with several, where halving the rows doubles the traffic of B: it keeps 128 rows there.
+    // (Not for a product already split along K, whose slices fill the chip.)
+    if (small <= 128 && !a.conv.on && a.k_slices <= 1 && (a.sparse || a.N <= 128)) {
+        // (an N-major B keeps 128-column tiles: the swizzle of its 16-bit rows needs 16 chunks of 16 bytes)
+        if (a.N <= 64 && a.bo != SP24_B_NMAJOR) return run_pipe<DT, OUT, 2, 1, 1, 2, 9, 9>(a, st);
+        return run_pipe<DT, OUT, 2, 1, 1, 4, 7, 6>(a, st);
+    }
     if (small <= 256) return run_pipe<DT, OUT, 2, 2, 2, 2, 6, 4>(a, st);
     return run_pipe<DT, OUT, 2, 2, 2, 2, 3, 2>(a, st);
 }
