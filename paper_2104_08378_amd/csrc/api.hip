@@ -344,12 +344,13 @@ static sp24_status mm_common(const MmArgs& a, hipStream_t st, size_t x_bytes = 0
 }
 
 // K split across workgroups.  The number of slices is a function of the shape and the input type alone: the one
-// with the least estimated time among the candidates, where splitting costs 6 us (8 us for the streaming kernel:
+// with the least estimated time among the candidates, where splitting costs 3 us (8 us for the streaming kernel:
 // the second kernel and the shorter pipelines) plus the partial images written and read once at 4 TB/s, and must
 // win by a tenth.
 //  * N > 32 (tiled kernels, 128x128 tiles; rows past M are computed on a valid row and never stored): 1 .. min(8, compute units / tiles, steps / 4) slices of whole
 //    128-byte steps; a launch takes 5 us plus 400 ns per step of its workgroups (fitted to measurements of both
-//    types at 16 - 128 steps, operands from HBM).
+//    types at 16 - 128 steps, operands from HBM); the unsplit product it is compared with runs shorter steps when it
+//    has at most 128 tiles (tiles of 64 rows).
 //  * N <= 32, M >= 32 (streaming kernel, one workgroup per 32 rows): 1 .. min(8, compute units / row blocks,
 //    tiles / 32) slices of whole 64-column tiles; a workgroup takes 130 ns (16-bit) or 80 ns (8-bit) per tile of
 //    its 32 rows (measured at K = 16384: latency-bound, the same whether 16 or 128 workgroups run).
@@ -380,10 +381,14 @@ static SplitPlan split_plan(int64_t M, int64_t N, int64_t K, sp24_dtype in)
         if (most > units / 4) most = units / 4;
         unit_ns = 400;
         base_ns = 5000;
-        fixed_ns = 6000;
+        fixed_ns = 3000;
     }
     if (most > 8) most = 8;
-    int64_t best_ns = (base_ns + units * unit_ns) * 9 / 10, best = 1, best_per = units;
+    // the unsplit tiled product on at most 128 tiles runs on tiles of 64 rows, with shorter steps (215 ns when they are
+    // 64 columns wide, 325 ns else: fitted to the sparse products of both types at 64 and 128 steps)
+    int64_t unsplit_unit_ns = unit_ns;
+    if (!p.streaming && ((M + 127) / 128) * ((N + 127) / 128) <= 128) unsplit_unit_ns = N <= 64 ? 215 : 325;
+    int64_t best_ns = (base_ns + units * unsplit_unit_ns) * 9 / 10, best = 1, best_per = units;
     for (int64_t want = 2; want <= most; ++want) {
         const int64_t per = (units + want - 1) / want;
         const int64_t slices = (units + per - 1) / per;      // no slice is empty
