@@ -106,9 +106,14 @@ def _dev(t, name):
 
 def _rowmajor(t, name):
     _dev(t, name)
-    if t.dim() != 2 or t.stride(1) != 1:
+    if t.dim() != 2 or (t.stride(1) != 1 and t.shape[1] > 1):      # (the stride of a dimension of size 1 means nothing)
         raise ValueError(f"{name} must be 2-d with unit column stride")
     return t
+
+
+def _ld(t):
+    """Leading dimension of a row-major matrix in elements; a single row may carry any stride."""
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
 
 
 def _out(out, shape, dtype, device, name="out"):
@@ -295,7 +300,7 @@ def sp24_spmm(V, meta, B, out_dtype, b_order="k", layout="canonical", out=None):
         raise ValueError("inner dimensions differ")
     _same_type(B, V)
     D = _out(out, (M, N), out_dtype, V.device)
-    _check(lib().sp24_spmm(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0),
+    _check(lib().sp24_spmm(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, _ld(B),
                            D.stride(0), _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], _stream()), "sp24_spmm")
     return D
 
@@ -309,7 +314,7 @@ def sp24_gemm_dense(A, B, out_dtype, b_order="k", out=None):
         raise ValueError("inner dimensions differ")
     _same_type(B, A)
     D = _out(out, (M, N), out_dtype, A.device)
-    _check(lib().sp24_gemm_dense(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0),
+    _check(lib().sp24_gemm_dense(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), _ld(B),
                                  D.stride(0), _DT[A.dtype], _DT[D.dtype], bo, _stream()), "sp24_gemm_dense")
     return D
 
@@ -339,7 +344,7 @@ def sp24_spmm_splitk(V, meta, B, out_dtype, b_order="k", layout="canonical", wor
     _same_type(B, V)
     ws, ws_bytes = _workspace(workspace, M, N, K, V.dtype, V.device)
     D = _out(out, (M, N), out_dtype, V.device)
-    _check(lib().sp24_spmm_splitk(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
+    _check(lib().sp24_spmm_splitk(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, _ld(B), D.stride(0),
                                   _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], ws.data_ptr(), ws_bytes, _stream()), "sp24_spmm_splitk")
     return D
 
@@ -357,7 +362,7 @@ def sp24_spmm_splitk_static(V, meta, B, out_dtype, b_order="k", layout="canonica
         raise ValueError("inner dimensions differ")
     _same_type(B, V)
     D = _out(out, (M, N), out_dtype, V.device)
-    _check(lib().sp24_spmm_splitk_static(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
+    _check(lib().sp24_spmm_splitk_static(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, _ld(B), D.stride(0),
                                          _DT[V.dtype], _DT[D.dtype], bo, _LAYOUT[layout], _stream()), "sp24_spmm_splitk_static")
     return D
 
@@ -372,7 +377,7 @@ def sp24_gemm_dense_splitk(A, B, out_dtype, b_order="k", workspace=None, out=Non
     _same_type(B, A)
     ws, ws_bytes = _workspace(workspace, M, N, K, A.dtype, A.device)
     D = _out(out, (M, N), out_dtype, A.device)
-    _check(lib().sp24_gemm_dense_splitk(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0), D.stride(0),
+    _check(lib().sp24_gemm_dense_splitk(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), _ld(B), D.stride(0),
                                         _DT[A.dtype], _DT[D.dtype], bo, ws.data_ptr(), ws_bytes, _stream()), "sp24_gemm_dense_splitk")
     return D
 
@@ -435,7 +440,7 @@ def sp24_spmm_i8_scaled(V, meta, B, out_dtype, w_scale, x_scale, bias=None, relu
     _same_type(B, V)
     ws, bs = _scale_args(M, w_scale, bias)
     D = _out(out, (M, N), out_dtype, V.device)
-    _check(lib().sp24_spmm_i8_scaled(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, B.stride(0), D.stride(0),
+    _check(lib().sp24_spmm_i8_scaled(V.data_ptr(), meta.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, _ld(B), D.stride(0),
                                      ws, float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], bo, _LAYOUT[layout],
                                      _stream()), "sp24_spmm_i8_scaled")
     return D
@@ -451,7 +456,7 @@ def sp24_gemm_dense_i8_scaled(A, B, out_dtype, w_scale, x_scale, bias=None, relu
     _same_type(B, A)
     ws, bs = _scale_args(M, w_scale, bias)
     D = _out(out, (M, N), out_dtype, A.device)
-    _check(lib().sp24_gemm_dense_i8_scaled(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), B.stride(0), D.stride(0),
+    _check(lib().sp24_gemm_dense_i8_scaled(A.data_ptr(), B.data_ptr(), D.data_ptr(), M, N, K, A.stride(0), _ld(B), D.stride(0),
                                            ws, float(x_scale), bs, int(bool(relu)), float(inv_y_scale), _DT[D.dtype], bo, _stream()),
            "sp24_gemm_dense_i8_scaled")
     return D
