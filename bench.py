@@ -284,7 +284,8 @@ def sweep(name, steps):
 
 
 def few_tiles(name, steps):
-    """Products with few output tiles -- 32 < N <= 128 at large M and K, small M x N with a long K, N <= 32 with few rows: the sparse
+    """Products with few output tiles -- 32 < N <= 128 at large M and K, small M x N with a long K, N <= 32 with few rows or with
+    very many (a transformer's projections on a batch of 8 - 64 tokens, the last one onto 32000 outputs): the sparse
     and the dense product as they are, and with the inner dimension split across workgroups (partial products in a
     workspace, second kernel adds them), beside the vendor library's dense product.  Inputs as in sweep()."""
     import torch
@@ -317,7 +318,7 @@ def few_tiles(name, steps):
 
     rows = []
     for M, N, K in ((8192, 64, 8192), (8192, 128, 8192), (512, 512, 8192), (256, 256, 16384), (2048, 256, 4096),
-                    (4096, 16, 16384), (512, 32, 16384)):
+                    (4096, 16, 16384), (512, 32, 16384), (4096, 64, 4096), (11008, 32, 4096), (32000, 8, 4096)):
         es = 1 if dt == "i8" else 2
         R = max(2, min(24, int(600e6 // ((M + N) * K * es)) + 1))
         As = [draw(M, K, 0.02) for _ in range(R)]
