@@ -1009,7 +1009,8 @@ static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
     // faster at N <= 64 (8192 x 64 x 8192 bf16: 43.8 -> 31.5 us), 6 - 17 % at N = 96 .. 128, 5 - 14 % on small
     // squarish shapes; the dense one 23 - 34 % and 15 - 25 % in a single column of tiles, but 10 - 15 % (16-bit)
     // slower with several, where halving the rows doubles the traffic of B: it keeps 128 rows there.
-    // (Not for a product already split along K, whose slices fill the chip.)
+    // (Not for a product already split along K, whose slices fill the chip; not for convolutions, where the gather of
+    // B is the cost and doubles with it: strided 3x3 layers with 13 - 98 tiles were 20 - 30 % slower.)
     if (small <= 128 && !a.conv.on && a.k_slices <= 1 && (a.sparse || a.N <= 128)) {
         // (an N-major B keeps 128-column tiles: the swizzle of its 16-bit rows needs 16 chunks of 16 bytes)
         if (a.N <= 64 && a.bo != SP24_B_NMAJOR) return run_pipe<DT, OUT, 2, 1, 1, 2, 9, 9>(a, st);
