@@ -231,7 +231,7 @@ typedef int int2v __attribute__((ext_vector_type(2)));
 template <int ES>
 __device__ __forceinline__ int nmajor_swizzle(int k, int chunks)
 {
-    return (ES == 1) ? ((2 * (k & 7)) & (chunks - 1)) : (4 * (k & 3));
+    return (ES == 1) ? ((2 * (k & 7)) & (chunks - 1)) : ((4 * (k & 3)) & (chunks - 1));
 }
 
 // Offsets (from the tile's first column of the step's first row) of the B transfers of one of NW wavefronts:
@@ -1012,8 +1012,7 @@ static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
     // (Not for a product already split along K, whose slices fill the chip; not for convolutions, where the gather of
     // B is the cost and doubles with it: strided 3x3 layers with 13 - 98 tiles were 20 - 30 % slower.)
     if (small <= 128 && !a.conv.on && a.k_slices <= 1 && (a.sparse || a.N <= 128)) {
-        // (a 16-bit N-major B keeps 128-column tiles: the swizzle of its rows needs 16 chunks of 16 bytes)
-        if (a.N <= 64 && (a.bo != SP24_B_NMAJOR || is8<DT>)) return run_pipe<DT, OUT, 2, 1, 1, 2, 9, 9>(a, st);
+        if (a.N <= 64) return run_pipe<DT, OUT, 2, 1, 1, 2, 9, 9>(a, st);
         return run_pipe<DT, OUT, 2, 1, 1, 4, 7, 6>(a, st);
     }
     if (small <= 256) return run_pipe<DT, OUT, 2, 2, 2, 2, 6, 4>(a, st);
