@@ -959,13 +959,25 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void k_gemm_pipe(MmArgs a, int til
 // ---------------------------------------------------------------------------
 // Host side.
 // ---------------------------------------------------------------------------
-// NSS / NSD: pipeline stages of the sparse / dense kernel
-template <int DT, int OUT, int WM, int WN, int TM, int TN, int NSS, int NSD>
+// NSS / NSD: pipeline stages of the sparse / dense kernel; CONVS: whether the tile shape serves convolutions too
+// (a shape that never does is not compiled for them)
+template <int DT, int OUT, int WM, int WN, int TM, int TN, int NSS, int NSD, bool CONVS = true>
 static sp24_status run_pipe(const MmArgs& a, hipStream_t st)
 {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(a.k_slices > 1 ? a.k_slices : 1)), block(64 * WM * WN);
+    if constexpr (!CONVS) {
+        if (a.conv.on) return SP24_ERR_LAUNCH;
+        if (a.sparse) {
+            if (a.bo == SP24_B_NMAJOR) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 2><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+            else k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 0><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        } else {
+            if (a.bo == SP24_B_NMAJOR) k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, 2><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+            else k_gemm_pipe<DT, OUT, WM, WN, TM, TN, NSD, 0><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
+        }
+        return hipGetLastError() == hipSuccess ? SP24_OK : SP24_ERR_LAUNCH;
+    }
     if (a.sparse) {
         if (a.conv.on) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 1><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
         else if (a.bo == SP24_B_NMAJOR) k_spmm_pipe<DT, OUT, WM, WN, TM, TN, NSS, 2><<<grid, block, 0, st>>>(a, tiles_m, tiles_n);
@@ -1012,8 +1024,8 @@ static sp24_status pick_tile_general(const MmArgs& a, hipStream_t st)
     // (Not for a product already split along K, whose slices fill the chip; not for convolutions, where the gather of
     // B is the cost and doubles with it: strided 3x3 layers with 13 - 98 tiles were 20 - 30 % slower.)
     if (small <= 128 && !a.conv.on && a.k_slices <= 1 && (a.sparse || a.N <= 128)) {
-        if (a.N <= 64) return run_pipe<DT, OUT, 2, 1, 1, 2, 9, 9>(a, st);
-        return run_pipe<DT, OUT, 2, 1, 1, 4, 7, 6>(a, st);
+        if (a.N <= 64) return run_pipe<DT, OUT, 2, 1, 1, 2, 9, 9, false>(a, st);
+        return run_pipe<DT, OUT, 2, 1, 1, 4, 7, 6, false>(a, st);
     }
     if (small <= 256) return run_pipe<DT, OUT, 2, 2, 2, 2, 6, 4>(a, st);
     return run_pipe<DT, OUT, 2, 2, 2, 2, 3, 2>(a, st);
